@@ -1,0 +1,92 @@
+"""Mutation check of the oracle's pins (CPU only).
+
+Each entry plants one plausible mistake in a copy of the oracle's source (a
+dropped term, a wrong sign, a transposed index, eps inside the root, ...),
+builds it, and runs the pin tests against that build.  Every mutant must be
+caught by at least one pin; if one survives, the pins are too weak."""
+import os
+import subprocess
+import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+from oracle import build as obuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PIN_TESTS = ["tests/test_oracle_half.py", "tests/test_oracle_norm_clip.py", "tests/test_oracle_adam.py"]
+
+MUTANTS = [
+    ("norm: sum of |x| instead of squares", "s += x * x;", "s += std::fabs(x);"),
+    ("norm: square root dropped", "norms[b] = std::sqrt(s);", "norms[b] = s;"),
+    ("norm: segment begin ignored", "for (uint64_t i = seg_begin[k]; i < seg_begin[k] + seg_len[k]; ++i) {\n        const double x",
+     "for (uint64_t i = 0; i < seg_len[k]; ++i) {\n        const double x"),
+    ("norm: last element of each segment dropped", "i < seg_begin[k] + seg_len[k]; ++i) {\n        const double x",
+     "i + 1 < seg_begin[k] + seg_len[k]; ++i) {\n        const double x"),
+    ("norm: sum not reset between buckets", "    double s = 0.0;\n    for (uint64_t k = bucket_seg_off[b]", "    static double s = 0.0;\n    for (uint64_t k = bucket_seg_off[b]"),
+    ("coef: inverted ratio", "coef = c / n;", "coef = n / c;"),
+    ("coef: clips when below threshold", "} else if (n >= c) {", "} else if (n <= c) {"),
+    ("coef: torch-style fudge term", "coef = c / n;", "coef = c / (n + 1e-6);"),
+    ("coef: squared norm compared", "} else if (n >= c) {", "} else if (n * n >= c) {"),
+    ("alg1: threshold divided by B instead of sqrt(B)", "return c / std::sqrt(static_cast<double>(n_buckets));",
+     "return c / static_cast<double>(n_buckets);"),
+    ("scale: unclipped buckets rewritten through fp32 multiply by wrong bucket", "store_scaled_grad(g, gdt, i, coefs[b]);",
+     "store_scaled_grad(g, gdt, i, coefs[0]);"),
+    ("scale: fp16 product truncated instead of rounded", "g[i] = float_to_half_bits(prod);",
+     "g[i] = float_to_half_bits(prod) & 0xfffe;"),
+    ("half: subnormal exponent off by one", "std::ldexp(static_cast<double>(frac), -24)", "std::ldexp(static_cast<double>(frac), -25)"),
+    ("half: ties away from zero", "const double r = std::nearbyint(q);", "const double r = std::floor(q + 0.5);"),
+    ("adam: beta1 and 1-beta1 swapped", "m = h.beta1 * m + (1.0 - h.beta1) * g;", "m = (1.0 - h.beta1) * m + h.beta1 * g;"),
+    ("adam: second moment uses g not g^2", "v = h.beta2 * v + (1.0 - h.beta2) * g * g;", "v = h.beta2 * v + (1.0 - h.beta2) * g;"),
+    ("adam: no bias correction on m", "const double mhat = m / bc1;", "const double mhat = m;"),
+    ("adam: no bias correction on v", "const double vhat = v / bc2;", "const double vhat = v;"),
+    ("adam: eps inside the root", "std::sqrt(vhat) + h.eps", "std::sqrt(vhat + h.eps)"),
+    ("adam: eps before bias correction", "p = p - h.lr * (mhat / (std::sqrt(vhat) + h.eps) + h.wd * p);",
+     "p = p - h.lr * (mhat / ((std::sqrt(v) + h.eps) / std::sqrt(bc2)) + h.wd * p);"),
+    ("adam: ascent instead of descent", "p = p - h.lr * (mhat", "p = p + h.lr * (mhat"),
+    ("adam: weight decay dropped", " + h.wd * p);", ");"),
+    ("adam: weight decay not scaled by lr", "p = p - h.lr * (mhat / (std::sqrt(vhat) + h.eps) + h.wd * p);",
+     "p = p - h.lr * (mhat / (std::sqrt(vhat) + h.eps)) - h.wd * p;"),
+    ("adam: coupled (L2) weight decay", "  m = h.beta1 * m + (1.0 - h.beta1) * g;", "  g += h.wd * p;\n  m = h.beta1 * m + (1.0 - h.beta1) * g;"),
+    ("adam: bias correction uses step-1", "const double bc1 = 1.0 - std::pow(beta1, static_cast<double>(step));\n  const double bc2 = 1.0 - std::pow(beta2, static_cast<double>(step));\n  for (uint32_t t",
+     "const double bc1 = 1.0 - std::pow(beta1, static_cast<double>(step + 1));\n  const double bc2 = 1.0 - std::pow(beta2, static_cast<double>(step + 1));\n  for (uint32_t t"),
+    ("adam: beta1 used for second-moment correction", "const double bc2 = 1.0 - std::pow(beta2, static_cast<double>(step));\n  for (uint32_t t",
+     "const double bc2 = 1.0 - std::pow(beta1, static_cast<double>(step));\n  for (uint32_t t"),
+    ("fused: Adam sees unscaled gradient", "const double ghat = coef * load_grad(grads[t], gdt, i);", "const double ghat = load_grad(grads[t], gdt, i);"),
+    ("fused: Adam sees storage-rounded gradient", "adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);\n          if (write_back",
+     "adam_element(gdt == GRAD_F16 ? half_bits_to_double(float_to_half_bits((float)ghat)) : (double)(float)ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);\n          if (write_back"),
+    ("fused: write-back always on", "if (write_back && coefs[b] != 1.0f)", "if (coefs[b] != 1.0f)"),
+    ("fused: skip flag ignored", "if (!(skip_on_nonfinite && (status & ORC_STATUS_NONFINITE))) {", "if (true) {"),
+    ("fused: wrong tensor for state", "adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);", "adam_element(ghat, p[t][i], v[t][i], m[t][i], h, bc1, bc2);"),
+]
+
+
+def _run_mutant(args):
+    idx, (name, old, new) = args
+    src = open(obuild.SRC).read()
+    if src.count(old) < 1:
+        return name, "pattern not found in oracle source"
+    with tempfile.TemporaryDirectory() as td:
+        msrc, mlib = os.path.join(td, "m.cpp"), os.path.join(td, f"libm{idx}.so")
+        open(msrc, "w").write(src.replace(old, new, 1))
+        try:
+            subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-o", mlib, msrc],
+                           check=True, capture_output=True)
+        except subprocess.CalledProcessError as e:
+            return name, "mutant does not compile: " + e.stderr.decode()[-300:]
+        env = dict(os.environ, BCA_ORACLE_LIB=mlib)
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_TESTS],
+                           cwd=ROOT, env=env, capture_output=True)
+        if r.returncode == 0:
+            return name, "SURVIVED: no pin test failed"
+        if r.returncode != 1:
+            return name, f"pytest exit {r.returncode}: " + r.stdout.decode()[-300:]
+    return name, None
+
+
+def test_every_planted_mistake_is_caught_by_a_pin():
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        results = list(ex.map(_run_mutant, enumerate(MUTANTS)))
+    problems = [f"{n}: {why}" for n, why in results if why]
+    assert not problems, "\n".join(problems)
