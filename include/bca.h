@@ -1,0 +1,164 @@
+/* bca.h -- bucket-wise gradient clipping + Adam on one MI355X (gfx950).
+ *
+ * C ABI of libbca.so.  Plain pointers and sizes only; every pointer is marked
+ * HOST or DEVICE.  The library implements, as hand-written HIP kernels, the
+ * per-GPU part of one training iteration of the paper's Alg. 1 (App. B):
+ * for every gradient bucket G_b, clip it by its own L2 norm against the
+ * bucket's threshold (Sec. 2.3 defines clipping-by-norm; Sec. 4.2 applies it
+ * bucket by bucket, before the all-reduce), then update the parameters with
+ * Adam (Alg. 1, last line).  The all-reduce between the two is not part of
+ * this library.
+ *
+ * Conventions
+ *   - All compute calls only enqueue kernels on `stream` (a hipStream_t passed
+ *     as void*; NULL is the default stream).  Nothing synchronises with the
+ *     host; outputs are valid once the caller has synchronised the stream.
+ *   - Return value: 0 on success, a negative BCA_ERR_* otherwise.  On error
+ *     nothing has been enqueued.  bca_last_error() gives a message.
+ *   - Gradients are fp32 or fp16; parameters and both moments are fp32.
+ *   - The caller owns every gradient / parameter / moment / threshold / norm /
+ *     coefficient / status buffer.  The library owns only the plan (chunk
+ *     table, partial sums, per-bucket scratch), freed by bca_plan_destroy.
+ *   - A plan is bound to one device; calls on one plan must not overlap in time
+ *     (they share the plan's scratch).  Different plans are independent.
+ */
+#ifndef BCA_H_
+#define BCA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bca_plan bca_plan; /* opaque */
+
+/* gradient storage type */
+#define BCA_GRAD_F32 0
+#define BCA_GRAD_F16 1
+
+/* error codes */
+#define BCA_OK 0
+#define BCA_ERR_NULL (-1)    /* a required pointer is NULL                          */
+#define BCA_ERR_LAYOUT (-2)  /* segments do not partition the tensors exactly once  */
+#define BCA_ERR_RANGE (-3)   /* bucket range b0 > b1 or b1 > n_buckets, bad option  */
+#define BCA_ERR_HPARAM (-4)  /* beta outside [0,1), eps < 0, non-finite lr/wd, step 0 */
+#define BCA_ERR_UNBOUND (-5) /* compute call before bca_plan_bind, or host-only plan */
+#define BCA_ERR_HIP (-6)     /* a HIP runtime call failed (message has its string)  */
+#define BCA_ERR_DTYPE (-7)   /* unknown gradient type                               */
+#define BCA_ERR_ALIGN (-8)   /* a tensor pointer is not aligned to its element size */
+
+/* bits of the device status word written by the clip calls */
+#define BCA_STATUS_NONFINITE 1     /* some bucket's sum of squares is Inf or NaN          */
+#define BCA_STATUS_BAD_THRESHOLD 2 /* some threshold is <= 0 or NaN: that bucket not clipped */
+
+/* flags of bucket_clip_adam */
+#define BCA_WRITE_BACK_GRADS 1u       /* also store the scaled gradient into g (what Alg. 1
+                                         hands to the all-reduce)                          */
+#define BCA_SKIP_STEP_ON_NONFINITE 2u /* if any bucket norm is non-finite, leave g, p, m, v
+                                         untouched (status still reports it)               */
+
+/* One contiguous piece of one tensor inside a bucket, in elements. */
+typedef struct bca_segment {
+  uint32_t tensor;   /* index into the tensor list   */
+  uint32_t reserved; /* must be 0                    */
+  uint64_t begin;    /* first element of the piece   */
+  uint64_t len;      /* number of elements (may be 0) */
+} bca_segment;
+
+/* Adam hyper-parameters (App. A, Table 4 lists the ones the paper tunes).
+ * Read on the host during the call. */
+typedef struct bca_adam {
+  double lr;           /* learning rate eta, finite                 */
+  double beta1;        /* in [0, 1)                                 */
+  double beta2;        /* in [0, 1)                                 */
+  double eps;          /* >= 0, added to sqrt(vhat)                 */
+  double weight_decay; /* decoupled: p <- p - lr * (u + wd * p)     */
+} bca_adam;
+
+/* Launch tuning; zero in any field means "library default". */
+typedef struct bca_tuning {
+  uint32_t chunk_elems; /* largest chunk, in elements; multiple of 1024       */
+  uint32_t grid_norm;   /* workgroups of the squared-norm kernel              */
+  uint32_t grid_apply;  /* workgroups of the scale / Adam kernels             */
+  uint32_t reserved;
+} bca_tuning;
+
+/* ---- plan -----------------------------------------------------------------
+ * A plan records the bucket layout of Alg. 1's G = [G_1 ... G_B]: B buckets,
+ * bucket b being the concatenation of segments
+ * segments[bucket_seg_off[b] .. bucket_seg_off[b+1]-1] in that order.  Bucket 0
+ * is the first one backward produces (the paper's loop runs b = B ... 1, so the
+ * model's last tensors come first).  Every element of every tensor must lie in
+ * exactly one segment, else BCA_ERR_LAYOUT.  All arrays are HOST memory and are
+ * copied.  device >= 0 selects the GPU that will run the plan; device = -1
+ * builds a host-only plan (layout validation and chunk table only; compute
+ * calls return BCA_ERR_UNBOUND) so that the host logic can be exercised without
+ * a GPU.  tuning may be NULL. */
+int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64_t* tensor_numel /*HOST*/,
+                    uint32_t n_buckets, const uint64_t* bucket_seg_off /*HOST [n_buckets+1]*/,
+                    const bca_segment* segments /*HOST*/, int grad_dtype, const bca_tuning* tuning /*HOST*/);
+
+/* Attach the tensors.  Each argument is a HOST array of n_tensors DEVICE
+ * pointers (grads[t] points to tensor_numel[t] values of the plan's gradient
+ * type, the others to fp32).  Pointers of empty tensors may be NULL.  Pointers
+ * must be aligned to their element size (BCA_ERR_ALIGN); 16-byte alignment
+ * of all four arrays of a tensor lets the kernels use 128-bit accesses.  May
+ * be called again when the pointers change.  Synchronous (uploads the table). */
+int bca_plan_bind(bca_plan* plan, void* const* grads, float* const* params, float* const* exp_avg,
+                  float* const* exp_avg_sq);
+
+void bca_plan_destroy(bca_plan* plan);
+
+/* Introspection of the host-side plan (no GPU needed). */
+uint32_t bca_plan_num_buckets(const bca_plan* plan);
+uint32_t bca_plan_num_chunks(const bca_plan* plan);
+/* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
+int bca_plan_chunk_info(const bca_plan* plan, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
+                        uint32_t* bucket);
+/* Chunks of bucket b are [first, first + count). */
+int bca_plan_bucket_chunks(const bca_plan* plan, uint32_t b, uint32_t* first, uint32_t* count);
+
+/* ---- compute --------------------------------------------------------------*/
+
+/* ||G_b|| for b in [b0, b1)  (the norm in Alg. 1's test and in Sec. 2.3).
+ * norms is a DEVICE array of n_buckets floats indexed by bucket; only entries
+ * b0..b1-1 are written.  b0 == b1 is a no-op.  Sums are accumulated in fp32
+ * per lane, combined in fp64 in a fixed order: results are bit-reproducible. */
+int bucket_clip_norms(bca_plan* plan, uint32_t b0, uint32_t b1, float* norms /*DEVICE*/, void* stream);
+
+/* Clip buckets [b0, b1) in place: with n = norms[b] and c = thresholds[b], if
+ * n >= c then G_b <- (c / n) * G_b, else G_b is not touched (Sec. 2.3; Alg. 1
+ * passes c / sqrt(B) as every bucket's threshold -- that choice is the
+ * caller's).  The factor is computed in fp64 from the fp32 norm, rounded once
+ * to fp32 and, if coefs is not NULL, stored in coefs[b] (1 for unclipped
+ * buckets).  The product is rounded to the gradient's storage type.  status
+ * (DEVICE int32, may be NULL) receives BCA_STATUS_* bits for this call. */
+int bucket_clip_apply(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thresholds /*DEVICE [B]*/,
+                      const float* norms /*DEVICE [B]*/, float* coefs /*DEVICE [B] or NULL*/,
+                      int32_t* status /*DEVICE or NULL*/, void* stream);
+
+/* theta <- ADAM(theta, eta, G) over every tensor of the plan, reading the
+ * gradients as stored (Alg. 1, last line).  Adam as published by Kingma & Ba
+ * with bias correction; step >= 1 counts this update:
+ *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ *   p <- p - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + wd * p ). */
+int adam_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, void* stream);
+
+/* The fused step: norms and clip factors of all buckets, then one sweep that
+ * forms ghat = coef_b * g in registers and applies Adam to it.  g is read, not
+ * written, unless BCA_WRITE_BACK_GRADS.  norms / coefs (DEVICE [B]) and status
+ * (DEVICE int32) may each be NULL. */
+int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
+                     uint64_t step, uint32_t flags, float* norms, float* coefs, int32_t* status, void* stream);
+
+/* Message of the calling thread's last error; valid until its next call. */
+const char* bca_last_error(void);
+
+/* Library version, for the loader check. */
+int bca_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCA_H_ */

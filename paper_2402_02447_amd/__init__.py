@@ -1,0 +1,9 @@
+"""Bucket-wise gradient clipping fused with Adam for one MI355X (gfx950).
+
+Thin ctypes binding over libbca.so (include/bca.h).  Every step of the path
+runs in the library's HIP kernels; Python only marshals pointers and sizes.
+"""
+from .binding import (  # noqa: F401
+    BCA_GRAD_F16, BCA_GRAD_F32, BCA_SKIP_STEP_ON_NONFINITE, BCA_STATUS_BAD_THRESHOLD, BCA_STATUS_NONFINITE,
+    BCA_WRITE_BACK_GRADS, AdamHyper, BcaError, Plan, alg1_thresholds, library_path, load_library,
+)

@@ -1,0 +1,231 @@
+"""ctypes binding of libbca.so: same names as the C ABI, argument marshalling only.
+
+Device buffers are passed as anything with a ``data_ptr()`` method (torch
+tensors) or as plain integers; streams as a ``torch.cuda.Stream``, an integer
+handle, or None for the default stream.  There is no CPU fallback: if the
+shared library is missing or fails to load, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+BCA_GRAD_F32, BCA_GRAD_F16 = 0, 1
+BCA_STATUS_NONFINITE, BCA_STATUS_BAD_THRESHOLD = 1, 2
+BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE = 1, 2
+
+_ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
+              -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN"}
+
+EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_chunks",
+           "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "adam_step",
+           "bucket_clip_adam", "bca_last_error", "bca_version"]
+
+
+class BcaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{_ERR_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+class _Segment(C.Structure):
+    _fields_ = [("tensor", C.c_uint32), ("reserved", C.c_uint32), ("begin", C.c_uint64), ("len", C.c_uint64)]
+
+
+class _Adam(C.Structure):
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double)]
+
+
+class _Tuning(C.Structure):
+    _fields_ = [("chunk_elems", C.c_uint32), ("grid_norm", C.c_uint32), ("grid_apply", C.c_uint32),
+                ("reserved", C.c_uint32)]
+
+
+@dataclass
+class AdamHyper:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-6
+    weight_decay: float = 0.01
+
+    def _c(self) -> _Adam:
+        return _Adam(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay)
+
+
+def library_path() -> str:
+    return os.environ.get("BCA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbca.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libbca.so.  Raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # A process must hold one HIP runtime only.  PyTorch-ROCm ships its own
+    # libamdhip64 (same soname as the system one); importing torch first makes the
+    # loader resolve libbca's dependency to that copy, so that device pointers and
+    # streams created by torch are valid in libbca's calls.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(path)
+    vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+    L.bca_plan_create.argtypes = [C.POINTER(vp), i32, u32, C.POINTER(u64), u32, C.POINTER(u64), C.POINTER(_Segment), i32,
+                                  C.POINTER(_Tuning)]
+    L.bca_plan_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+    L.bca_plan_destroy.argtypes = [vp]
+    L.bca_plan_destroy.restype = None
+    L.bca_plan_num_buckets.argtypes = [vp]
+    L.bca_plan_num_buckets.restype = u32
+    L.bca_plan_num_chunks.argtypes = [vp]
+    L.bca_plan_num_chunks.restype = u32
+    L.bca_plan_chunk_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
+    L.bca_plan_bucket_chunks.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u32)]
+    L.bucket_clip_norms.argtypes = [vp, u32, u32, vp, vp]
+    L.bucket_clip_apply.argtypes = [vp, u32, u32, vp, vp, vp, vp, vp]
+    L.adam_step.argtypes = [vp, C.POINTER(_Adam), u64, vp]
+    L.bucket_clip_adam.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp]
+    L.bca_last_error.restype = C.c_char_p
+    L.bca_version.restype = i32
+    for name in EXPORTS:
+        getattr(L, name)          # raises AttributeError if a declared symbol is missing
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise BcaError(rc, load_library().bca_last_error().decode())
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr()) or None
+    return int(x) or None
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return int(s.cuda_stream) or None
+    return int(s) or None
+
+
+def alg1_thresholds(c: float, n_buckets: int) -> np.ndarray:
+    """Per-bucket thresholds of Alg. 1: every bucket is compared with c / sqrt(B)."""
+    return np.full(n_buckets, c / math.sqrt(n_buckets), dtype=np.float32)
+
+
+class Plan:
+    """A bucket layout on one device (bca_plan_create / bind / destroy) and the four compute calls."""
+
+    def __init__(self, tensor_numel: Sequence[int], bucket_seg_off: Sequence[int], seg_tensor: Sequence[int],
+                 seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
+                 chunk_elems: int = 0, grid_norm: int = 0, grid_apply: int = 0):
+        L = load_library()
+        self._L = L
+        self._h = C.c_void_p()
+        numel = np.ascontiguousarray(tensor_numel, dtype=np.uint64)
+        off = np.ascontiguousarray(bucket_seg_off, dtype=np.uint64)
+        n_seg = len(seg_tensor)
+        segs = (_Segment * max(1, n_seg))()
+        for i in range(n_seg):
+            segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
+        tune = _Tuning(chunk_elems, grid_norm, grid_apply, 0)
+        _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                 len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
+                                 C.byref(tune)))
+        self.n_tensors = len(numel)
+        self.device = device
+        self.grad_dtype = grad_dtype
+        self._keep = None
+
+    @classmethod
+    def from_layout(cls, layout, grad_dtype: int = BCA_GRAD_F32, device: int = 0, **tuning) -> "Plan":
+        """`layout` is any object with tensor_numel, bucket_seg_off, seg_tensor, seg_begin, seg_len."""
+        return cls(layout.tensor_numel, layout.bucket_seg_off, layout.seg_tensor, layout.seg_begin, layout.seg_len,
+                   grad_dtype, device, **tuning)
+
+    # -- lifetime
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._L.bca_plan_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    # -- introspection
+    @property
+    def n_buckets(self) -> int:
+        return int(self._L.bca_plan_num_buckets(self._h))
+
+    @property
+    def n_chunks(self) -> int:
+        return int(self._L.bca_plan_num_chunks(self._h))
+
+    def chunk_info(self, i: int):
+        t, b, ln, bk = C.c_uint32(), C.c_uint64(), C.c_uint32(), C.c_uint32()
+        _check(self._L.bca_plan_chunk_info(self._h, i, C.byref(t), C.byref(b), C.byref(ln), C.byref(bk)))
+        return t.value, b.value, ln.value, bk.value
+
+    def bucket_chunks(self, b: int):
+        f, n = C.c_uint32(), C.c_uint32()
+        _check(self._L.bca_plan_bucket_chunks(self._h, b, C.byref(f), C.byref(n)))
+        return f.value, n.value
+
+    # -- binding
+    def bind(self, grads, params, exp_avg, exp_avg_sq) -> None:
+        def arr(xs):
+            if len(xs) != self.n_tensors:
+                raise ValueError(f"expected {self.n_tensors} tensors, got {len(xs)}")
+            a = (C.c_void_p * max(1, len(xs)))()
+            for i, x in enumerate(xs):
+                a[i] = _ptr(x)
+            return a
+        _check(self._L.bca_plan_bind(self._h, arr(grads), arr(params), arr(exp_avg), arr(exp_avg_sq)))
+        self._keep = (grads, params, exp_avg, exp_avg_sq)     # keep the tensors alive while bound
+
+    # -- compute (same names as the C ABI)
+    def bucket_clip_norms(self, b0: int, b1: int, norms, stream=None) -> None:
+        _check(self._L.bucket_clip_norms(self._h, b0, b1, _ptr(norms), _stream(stream)))
+
+    def bucket_clip_apply(self, b0: int, b1: int, thresholds, norms, coefs=None, status=None, stream=None) -> None:
+        _check(self._L.bucket_clip_apply(self._h, b0, b1, _ptr(thresholds), _ptr(norms), _ptr(coefs), _ptr(status),
+                                         _stream(stream)))
+
+    def adam_step(self, hp: AdamHyper, step: int, stream=None) -> None:
+        h = hp._c()
+        _check(self._L.adam_step(self._h, C.byref(h), step, _stream(stream)))
+
+    def bucket_clip_adam(self, thresholds, hp: AdamHyper, step: int, flags: int = 0, norms=None, coefs=None,
+                         status=None, stream=None) -> None:
+        h = hp._c()
+        _check(self._L.bucket_clip_adam(self._h, _ptr(thresholds), C.byref(h), step, flags, _ptr(norms), _ptr(coefs),
+                                        _ptr(status), _stream(stream)))

@@ -1,0 +1,190 @@
+"""CPU-only checks of libbca's host side: the library loads, exports every symbol
+declared in include/bca.h, validates layouts and hyper-parameters, and cuts the
+bucket layout into a correct chunk table.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2402_02447_amd as B
+from paper_2402_02447_amd import binding
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = B.load_library()
+    header = open(os.path.join(ROOT, "include", "bca.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|adam_step)\s*\(", header))
+    assert {"bucket_clip_norms", "bucket_clip_apply", "adam_step", "bucket_clip_adam"} <= declared
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.bca_version() >= 1
+
+
+def host_plan(layout, **kw):
+    return B.Plan.from_layout(layout, device=-1, **kw)
+
+
+@pytest.mark.parametrize("chunk", [1024, 4096, 16384])
+def test_chunk_table_partitions_the_layout(chunk):
+    numels = W.scaled_bert_numels(64, 2, 256, vocab=1000, max_pos=32) + [0, 7, 1]
+    lay = W.layout_flat_split(numels, 50_000)
+    p = host_plan(lay, chunk_elems=chunk)
+    assert p.n_buckets == lay.n_buckets
+    seen = [np.zeros(n, np.int8) for n in numels]
+    prev_bucket = 0
+    per_bucket = np.zeros(lay.n_buckets, np.int64)
+    for i in range(p.n_chunks):
+        t, beg, ln, b = p.chunk_info(i)
+        assert 0 < ln <= chunk
+        assert b >= prev_bucket                        # bucket-major order
+        prev_bucket = b
+        assert beg // chunk == (beg + ln - 1) // chunk  # never straddles a multiple of the chunk size
+        seen[t][beg:beg + ln] += 1
+        per_bucket[b] += ln
+        f, n = p.bucket_chunks(b)
+        assert f <= i < f + n
+    assert all((s == 1).all() for s in seen)
+    assert np.array_equal(per_bucket, lay.bucket_numel())
+    # chunks stay inside their segment's bucket: elements of bucket b per the layout
+    for b in range(lay.n_buckets):
+        f, n = p.bucket_chunks(b)
+        cover = {}
+        for i in range(f, f + n):
+            t, beg, ln, bb = p.chunk_info(i)
+            assert bb == b
+            cover.setdefault(t, []).append((beg, ln))
+        want = {}
+        for t, beg, ln in lay.segments_of(b):
+            if ln:
+                want.setdefault(t, []).append((beg, ln))
+        assert set(cover) == set(want)
+        for t in want:
+            assert sum(l for _, l in cover[t]) == sum(l for _, l in want[t])
+            assert min(bg for bg, _ in cover[t]) == min(bg for bg, _ in want[t])
+
+
+def test_chunk_counts_of_the_bert_large_configs():
+    for make, lo, hi in [(W.config_bert_large, 20_455, 21_300), (W.config_bert_large_fp16, 20_455, 23_500)]:
+        w = make()
+        p = host_plan(w.layout)
+        assert lo <= p.n_chunks <= hi           # ceil(N / 16384) = 20 456 plus cuts at tensor / bucket edges
+
+
+def _raw_create(numel, off, segs, gdt=0, device=-1, tuning=None):
+    L = B.load_library()
+    h = C.c_void_p()
+    numel = np.asarray(numel, np.uint64)
+    off = np.asarray(off, np.uint64)
+    arr = (binding._Segment * max(1, len(segs)))()
+    for i, (t, b, l) in enumerate(segs):
+        arr[i] = binding._Segment(t, 0, b, l)
+    rc = L.bca_plan_create(C.byref(h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)), len(off) - 1,
+                           off.ctypes.data_as(C.POINTER(C.c_uint64)), arr, gdt, tuning)
+    if rc == 0:
+        L.bca_plan_destroy(h)
+    return rc, L.bca_last_error().decode()
+
+
+def test_layout_errors_are_reported_and_nothing_is_created():
+    ok = _raw_create([10, 5], [0, 2], [(0, 0, 10), (1, 0, 5)])
+    assert ok[0] == 0
+    rc, msg = _raw_create([10, 5], [0, 2], [(0, 0, 10), (1, 0, 4)])          # gap at the end
+    assert rc == -2 and "cover" in msg
+    rc, msg = _raw_create([10, 5], [0, 2], [(0, 0, 6), (0, 5, 5), ])          # overlap + tensor 1 missing
+    assert rc == -2 and "overlap" in msg
+    rc, msg = _raw_create([10], [0, 2], [(0, 0, 4), (0, 5, 5)])               # hole in the middle
+    assert rc == -2 and "gap" in msg
+    rc, msg = _raw_create([10], [0, 1], [(0, 5, 6)])                          # runs past the end
+    assert rc == -2 and "exceeds" in msg
+    rc, msg = _raw_create([10], [0, 1], [(3, 0, 10)])                         # unknown tensor
+    assert rc == -2
+    rc, msg = _raw_create([10], [0, 1, 0], [(0, 0, 10)])                      # offsets decrease
+    assert rc == -2
+    rc, msg = _raw_create([10], [1, 1], [(0, 0, 10)])                         # offsets do not start at 0
+    assert rc == -2
+    rc, msg = _raw_create([10], [0], [])                                      # no bucket at all
+    assert rc == -2
+    rc, msg = _raw_create([10], [0, 1], [(0, 0, 10)], gdt=5)
+    assert rc == -7
+    t = binding._Tuning(1000, 0, 0, 0)                                         # chunk size not a multiple of 1024
+    rc, msg = _raw_create([10], [0, 1], [(0, 0, 10)], tuning=C.byref(t))
+    assert rc == -3
+    # empty buckets, empty segments and empty tensors are legal
+    assert _raw_create([10, 0], [0, 0, 3, 3], [(0, 0, 4), (1, 0, 0), (0, 4, 6)])[0] == 0
+
+
+def test_null_arguments_and_host_only_plans_are_refused_cleanly():
+    L = B.load_library()
+    assert L.bca_plan_create(None, -1, 0, None, 1, None, None, 0, None) == -1
+    assert L.bucket_clip_norms(None, 0, 0, None, None) == -1
+    assert L.adam_step(None, None, 1, None) == -1
+    p = host_plan(W.layout_one_tensor_per_bucket([8, 8]))
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip_norms(0, 2, 1234)
+    assert e.value.code == -5
+    with pytest.raises(B.BcaError) as e:
+        p.adam_step(B.AdamHyper(), 1)
+    assert e.value.code == -5
+    with pytest.raises(B.BcaError) as e:
+        p.bind([1, 2], [3, 4], [5, 6], [7, 8])
+    assert e.value.code == -5
+    with pytest.raises(B.BcaError):
+        p.chunk_info(10 ** 6)
+    L.bca_plan_destroy(None)     # no-op
+
+
+def test_argument_errors_come_before_any_launch():
+    # argument checks run before the plan is asked to launch anything, so a host-only plan shows them
+    p = host_plan(W.layout_one_tensor_per_bucket([8, 8]))
+    bad = [dict(beta1=1.0), dict(beta1=-0.1), dict(beta2=1.5), dict(beta2=float("nan")), dict(eps=-1e-8),
+           dict(lr=float("inf")), dict(weight_decay=float("nan"))]
+    for kw in bad:
+        with pytest.raises(B.BcaError) as e:
+            p.adam_step(B.AdamHyper(**kw), 1)
+        assert e.value.code == -4, kw
+        with pytest.raises(B.BcaError) as e:
+            p.bucket_clip_adam(1234, B.AdamHyper(**kw), 1)
+        assert e.value.code == -4, kw
+    with pytest.raises(B.BcaError) as e:
+        p.adam_step(B.AdamHyper(), 0)                      # steps count from 1
+    assert e.value.code == -4
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip_adam(1234, B.AdamHyper(), 1, flags=8)
+    assert e.value.code == -3
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip_adam(None, B.AdamHyper(), 1)
+    assert e.value.code == -1
+    for b0, b1 in [(2, 1), (0, 3), (3, 3)]:
+        with pytest.raises(B.BcaError) as e:
+            p.bucket_clip_norms(b0, b1, 1234)
+        assert e.value.code == -3
+        with pytest.raises(B.BcaError) as e:
+            p.bucket_clip_apply(b0, b1, 1234, 1234)
+        assert e.value.code == -3
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip_norms(0, 2, None)
+    assert e.value.code == -1
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip_apply(0, 2, None, 1234)
+    assert e.value.code == -1
+
+
+def test_a_device_plan_fails_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.BcaError) as e:
+        B.Plan.from_layout(W.layout_one_tensor_per_bucket([8]), device=0)
+    assert e.value.code == -6
+
+
+def test_alg1_threshold_helper():
+    thr = B.alg1_thresholds(1.0, 16)
+    assert thr.dtype == np.float32 and thr.shape == (16,) and np.all(thr == np.float32(0.25))
