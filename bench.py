@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused bucket_clip_adam step on one MI355X.
+
+A step is one pass of the whole hot path (per-bucket squared norms, finalize to
+norm and clip coefficient, clip-fused Adam sweep) over the BERT-Large fp32
+parameter set packed into 50 MiB buckets, with all inputs resident in HBM.
+
+Prints ONE JSON line: ms/step, plus `roofline` for the dominant kernel (the
+Adam sweep; HIP-event durations measured here, algorithmic bytes = 28 B per
+element) and `cpu_baseline` (the fp64 oracle timed on this machine's host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+# HBM traffic of one Adam-sweep launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), filled in
+# from profiles/ when a counter run exists for the workload; None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="BASELINE.json config number")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-norm", type=int, default=0)
+    ap.add_argument("--chunk-apply", type=int, default=0)
+    ap.add_argument("--unroll-apply", type=int, default=0)
+    ap.add_argument("--group-mib", type=int, default=0)
+    ap.add_argument("--grid-norm", type=int, default=0)
+    ap.add_argument("--grid-apply", type=int, default=0)
+    ap.add_argument("--tune-flags", type=int, default=0)
+    ap.add_argument("--write-back", action="store_true")
+    ap.add_argument("--oracle-steps", type=int, default=3)
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2402_02447_amd as B
+    import workloads as W
+
+    B.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    w = W.CONFIGS[a.config]()
+    lay = w.layout
+    numels = [int(n) for n in lay.tensor_numel]
+    N = lay.n_elements
+    f16 = w.grad_dtype == "f16"
+
+    # ---- synthetic inputs, generated on the device (seeded), one allocation per tensor
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    def randn(n, sigma):
+        return torch.randn(n, generator=gen, device=dev, dtype=torch.float32) * sigma
+    p = [randn(n, 0.02) for n in numels]
+    if w.warm:
+        m = [randn(n, 3e-4) for n in numels]
+        v = [(torch.rand(n, generator=gen, device=dev, dtype=torch.float32) + 0.5) * 1e-6 for n in numels]
+    else:
+        m = [torch.zeros(n, device=dev) for n in numels]
+        v = [torch.zeros(n, device=dev) for n in numels]
+    if f16:
+        def t3(n):
+            z = torch.randn(4, n, generator=gen, device=dev, dtype=torch.float32)
+            return (z[0] / torch.sqrt((z[1] ** 2 + z[2] ** 2 + z[3] ** 2) / 3.0) * w.sigma_g).to(torch.float16)
+        g = [t3(n) for n in numels]
+    else:
+        g = [randn(n, w.sigma_g) for n in numels]
+        for b in w.hot_buckets:
+            for t, beg, ln in lay.segments_of(b):
+                g[t][beg:beg + ln] *= 100.0
+    thr = torch.from_numpy(w.thresholds).to(dev)
+    hp = B.AdamHyper(w.hyper.lr, w.hyper.beta1, w.hyper.beta2, w.hyper.eps, w.hyper.weight_decay)
+
+    plan = B.Plan.from_layout(lay, B.BCA_GRAD_F16 if f16 else B.BCA_GRAD_F32, device=0, chunk_norm=a.chunk_norm,
+                              chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
+                              unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20)
+    plan.bind(g, p, m, v)
+    norms = torch.zeros(lay.n_buckets, dtype=torch.float32, device=dev)
+    coefs = torch.zeros_like(norms)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    flags = B.BCA_WRITE_BACK_GRADS if a.write_back else 0
+    stream = torch.cuda.current_stream()
+
+    # host copies for the CPU baseline are taken before the state evolves
+    host = None
+    if not a.no_cpu_baseline:
+        host = [[t.cpu().numpy() for t in xs] for xs in (g, p, m, v)]
+
+    step = w.first_step
+    def one_step():
+        nonlocal step
+        plan.bucket_clip_adam(thr, hp, step, flags, norms, coefs, status, stream)
+        step += 1
+
+    for _ in range(a.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    st = int(status.item())
+    assert st == 0, f"status word {st} after the timed steps"
+    n_clipped = int((coefs < 1).sum().item())
+
+    # ---- same K steps again with HIP events around each kernel (per-kernel durations)
+    plan.profile(a.steps)
+    for _ in range(a.steps):
+        one_step()
+    torch.cuda.synchronize()
+    (ms_norm, ms_fin, ms_adam), n_prof = plan.profile_read()
+    plan.profile(0)
+    ms_norm, ms_fin, ms_adam = ms_norm / n_prof, ms_fin / n_prof, ms_adam / n_prof
+
+    gbytes = 2 if f16 else 4
+    adam_bytes_per_elt = 24 + gbytes + (gbytes if a.write_back else 0)    # read g,p,m,v; write p,m,v (+g)
+    adam_bytes = adam_bytes_per_elt * N
+    achieved = adam_bytes / (ms_adam * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((a.config, a.write_back))
+    single = not (a.tune_flags & B.BCA_TUNE_MULTI_LAUNCH)
+    kname = ("k_step (whole fused step in one launch: gradients read from HBM once, re-read from Infinity Cache)"
+             if single else "k_adam (clip-fused Adam sweep, summed over bucket groups)")
+    roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": traffic, "bytes_per_elt": adam_bytes_per_elt, "ms_per_launch": round(ms_adam, 4)}
+    norm_gbps = gbytes * N / (ms_norm * 1e-3) / 1e9 if not single else None
+    step_bytes_min = adam_bytes                       # lower bound: second read of g served from cache
+    step_bytes_twice = adam_bytes + gbytes * N        # g read twice from HBM
+    extras = {
+        "kernels_ms": ({"k_prepare+gap": round(ms_norm, 4), "k_step": round(ms_adam, 4)} if single else
+                       {"k_sqnorm": round(ms_norm, 4), "k_finalize": round(ms_fin, 4), "k_adam": round(ms_adam, 4)}),
+        "k_sqnorm_GBps": round(norm_gbps, 1) if norm_gbps else None,
+        "step_GBps_g_read_once": round(step_bytes_min / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_GBps_g_read_twice": round(step_bytes_twice / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_frac_of_peak_g_read_twice": round(step_bytes_twice / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "elements": N, "buckets": lay.n_buckets, "chunks_norm": plan.n_chunks(B.BCA_TABLE_NORM), "chunks_apply": plan.n_chunks(B.BCA_TABLE_APPLY),
+        "groups": plan.n_groups, "buckets_clipped": n_clipped, "status": st,
+    }
+
+    cpu = None
+    if host is not None:
+        import oracle
+        hg, hp_, hm, hv = host
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            op, om, ov = (list(ex.map(lambda x: x.astype(np.float64), xs)) for xs in (hp_, hm, hv))
+        t1 = time.perf_counter()
+        for k in range(a.oracle_steps):
+            oracle.bucket_clip_adam(lay, hg, op, om, ov, w.thresholds, w.hyper.lr, w.hyper.beta1, w.hyper.beta2,
+                                    w.hyper.eps, w.hyper.weight_decay, w.first_step + k)
+        cpu_ms = (time.perf_counter() - t1) * 1e3 / a.oracle_steps
+        cpu = {"value": round(cpu_ms, 1), "unit": "ms/step", "cores": 1, "kind": "oracle",
+               "sample": f"{a.oracle_steps} full fused steps of the same workload ({N} elements), single thread, "
+                         f"host has {os.cpu_count()} logical cpus"}
+
+    out = {
+        "metric": "fused bucket_clip_adam step time, BERT-Large fp32 (ms/step; HBM fraction in roofline)",
+        "value": round(ms_per_step, 4), "unit": "ms/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not f16 else "f32 (f16 gradients)", "data": "synthetic",
+        "config": {"workload": f"configs[{a.config - 1}]: {w.name}, {N} params in {lay.n_tensors} tensors, "
+                               f"{lay.n_buckets} buckets, grads {w.grad_dtype}",
+                   "write_back": bool(a.write_back)},
+        "roofline": roofline, "cpu_baseline": cpu, **extras,
+    }
+    print(json.dumps(out))
+    plan.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -51,6 +51,8 @@ typedef struct bca_plan bca_plan; /* opaque */
 /* bits of the device status word written by the clip calls */
 #define BCA_STATUS_NONFINITE 1     /* some bucket's sum of squares is Inf or NaN          */
 #define BCA_STATUS_BAD_THRESHOLD 2 /* some threshold is <= 0 or NaN: that bucket not clipped */
+#define BCA_STATUS_TIMEOUT 4       /* a bounded wait inside the fused step expired; the step is
+                                      incomplete (never seen unless the GPU is wedged)         */
 
 /* flags of bucket_clip_adam */
 #define BCA_WRITE_BACK_GRADS 1u       /* also store the scaled gradient into g (what Alg. 1
@@ -77,12 +79,27 @@ typedef struct bca_adam {
 } bca_adam;
 
 /* Launch tuning; zero in any field means "library default". */
+#define BCA_TUNE_MULTI_LAUNCH 1u    /* bucket_clip_adam as separate norm / finalize / Adam launches per
+                                       bucket group instead of the single pipelined launch            */
+#define BCA_TUNE_TICKETS 4u          /* single launch: work items are handed out through an atomic
+                                       ticket instead of by workgroup index                          */
+#define BCA_TUNE_STAGE_TABLE_LDS 2u /* multi-launch kernels: persistent workgroups stage chunk-table
+                                       slices in LDS                                                 */
 typedef struct bca_tuning {
-  uint32_t chunk_elems; /* largest chunk, in elements; multiple of 1024       */
-  uint32_t grid_norm;   /* workgroups of the squared-norm kernel              */
-  uint32_t grid_apply;  /* workgroups of the scale / Adam kernels             */
-  uint32_t reserved;
+  uint32_t chunk_norm;   /* largest chunk of the squared-norm pass, elements, multiple of 1024  */
+  uint32_t chunk_apply;  /* largest chunk of the scale / Adam passes, elements, multiple of 1024 */
+  uint32_t grid_norm;    /* workgroups of the squared-norm kernel (0: one per chunk)            */
+  uint32_t grid_apply;   /* workgroups of the scale / Adam kernels (0: one per chunk)           */
+  uint32_t unroll_apply; /* 128-bit accesses in flight per lane and array in scale / Adam: 1, 2, 4 */
+  uint32_t flags;        /* BCA_TUNE_*                                                          */
+  uint64_t group_bytes;  /* bucket_clip_adam walks the buckets in groups of at most this many
+                            gradient bytes (norms, then Adam, group by group) so that a group's
+                            gradients are still in cache when Adam reads them; 0: default      */
 } bca_tuning;
+
+/* which chunk table an introspection call looks at */
+#define BCA_TABLE_NORM 0
+#define BCA_TABLE_APPLY 1
 
 /* ---- plan -----------------------------------------------------------------
  * A plan records the bucket layout of Alg. 1's G = [G_1 ... G_B]: B buckets,
@@ -110,14 +127,17 @@ int bca_plan_bind(bca_plan* plan, void* const* grads, float* const* params, floa
 
 void bca_plan_destroy(bca_plan* plan);
 
-/* Introspection of the host-side plan (no GPU needed). */
+/* Introspection of the host-side plan (no GPU needed).  `table` is BCA_TABLE_NORM
+ * or BCA_TABLE_APPLY: the layout is cut twice, coarsely for the squared-norm pass
+ * and finely for the passes that also write. */
 uint32_t bca_plan_num_buckets(const bca_plan* plan);
-uint32_t bca_plan_num_chunks(const bca_plan* plan);
+uint32_t bca_plan_num_groups(const bca_plan* plan);
+uint32_t bca_plan_num_chunks(const bca_plan* plan, int table);
 /* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
-int bca_plan_chunk_info(const bca_plan* plan, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
-                        uint32_t* bucket);
+int bca_plan_chunk_info(const bca_plan* plan, int table, uint32_t i, uint32_t* tensor, uint64_t* begin,
+                        uint32_t* len, uint32_t* bucket);
 /* Chunks of bucket b are [first, first + count). */
-int bca_plan_bucket_chunks(const bca_plan* plan, uint32_t b, uint32_t* first, uint32_t* count);
+int bca_plan_bucket_chunks(const bca_plan* plan, int table, uint32_t b, uint32_t* first, uint32_t* count);
 
 /* ---- compute --------------------------------------------------------------*/
 
@@ -148,9 +168,20 @@ int adam_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, void* 
 /* The fused step: norms and clip factors of all buckets, then one sweep that
  * forms ghat = coef_b * g in registers and applies Adam to it.  g is read, not
  * written, unless BCA_WRITE_BACK_GRADS.  norms / coefs (DEVICE [B]) and status
- * (DEVICE int32) may each be NULL. */
+ * (DEVICE int32) may each be NULL.  With BCA_SKIP_STEP_ON_NONFINITE all norms
+ * are computed before any update (no pipelining of bucket groups). */
 int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
                      uint64_t step, uint32_t flags, float* norms, float* coefs, int32_t* status, void* stream);
+
+/* ---- per-kernel timing (for benchmarks) -----------------------------------
+ * With profiling on, bucket_clip_adam records HIP events on `stream` around each
+ * of its kernels (squared norm, finalize, Adam sweep; once per bucket group), for at most
+ * `max_calls` calls after it was switched on (max_calls = 0 switches it off and
+ * frees the events).  bca_plan_profile_read waits for the recorded events and
+ * returns the summed duration of each kernel in milliseconds in ms[0..2] and the
+ * number of calls summed in *n_calls, then starts a new series. */
+int bca_plan_profile(bca_plan* plan, uint32_t max_calls);
+int bca_plan_profile_read(bca_plan* plan, double* ms /*HOST [3]*/, uint32_t* n_calls /*HOST*/);
 
 /* Message of the calling thread's last error; valid until its next call. */
 const char* bca_last_error(void);

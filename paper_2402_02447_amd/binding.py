@@ -18,13 +18,17 @@ import numpy as np
 BCA_GRAD_F32, BCA_GRAD_F16 = 0, 1
 BCA_STATUS_NONFINITE, BCA_STATUS_BAD_THRESHOLD = 1, 2
 BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE = 1, 2
+BCA_TUNE_MULTI_LAUNCH, BCA_TUNE_STAGE_TABLE_LDS, BCA_TUNE_TICKETS = 1, 2, 4
+BCA_STATUS_TIMEOUT = 4
+BCA_TABLE_NORM, BCA_TABLE_APPLY = 0, 1
 
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN"}
 
-EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_chunks",
+EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_groups",
+           "bca_plan_num_chunks",
            "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "adam_step",
-           "bucket_clip_adam", "bca_last_error", "bca_version"]
+           "bucket_clip_adam", "bca_plan_profile", "bca_plan_profile_read", "bca_last_error", "bca_version"]
 
 
 class BcaError(RuntimeError):
@@ -43,8 +47,9 @@ class _Adam(C.Structure):
 
 
 class _Tuning(C.Structure):
-    _fields_ = [("chunk_elems", C.c_uint32), ("grid_norm", C.c_uint32), ("grid_apply", C.c_uint32),
-                ("reserved", C.c_uint32)]
+    _fields_ = [("chunk_norm", C.c_uint32), ("chunk_apply", C.c_uint32), ("grid_norm", C.c_uint32),
+                ("grid_apply", C.c_uint32), ("unroll_apply", C.c_uint32), ("flags", C.c_uint32),
+                ("group_bytes", C.c_uint64)]
 
 
 @dataclass
@@ -91,14 +96,18 @@ def load_library():
     L.bca_plan_destroy.restype = None
     L.bca_plan_num_buckets.argtypes = [vp]
     L.bca_plan_num_buckets.restype = u32
-    L.bca_plan_num_chunks.argtypes = [vp]
+    L.bca_plan_num_groups.argtypes = [vp]
+    L.bca_plan_num_groups.restype = u32
+    L.bca_plan_num_chunks.argtypes = [vp, i32]
     L.bca_plan_num_chunks.restype = u32
-    L.bca_plan_chunk_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
-    L.bca_plan_bucket_chunks.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u32)]
+    L.bca_plan_chunk_info.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
+    L.bca_plan_bucket_chunks.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u32)]
     L.bucket_clip_norms.argtypes = [vp, u32, u32, vp, vp]
     L.bucket_clip_apply.argtypes = [vp, u32, u32, vp, vp, vp, vp, vp]
     L.adam_step.argtypes = [vp, C.POINTER(_Adam), u64, vp]
     L.bucket_clip_adam.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp]
+    L.bca_plan_profile.argtypes = [vp, u32]
+    L.bca_plan_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]
     L.bca_last_error.restype = C.c_char_p
     L.bca_version.restype = i32
     for name in EXPORTS:
@@ -138,7 +147,8 @@ class Plan:
 
     def __init__(self, tensor_numel: Sequence[int], bucket_seg_off: Sequence[int], seg_tensor: Sequence[int],
                  seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
-                 chunk_elems: int = 0, grid_norm: int = 0, grid_apply: int = 0):
+                 chunk_norm: int = 0, chunk_apply: int = 0, grid_norm: int = 0, grid_apply: int = 0,
+                 unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0):
         L = load_library()
         self._L = L
         self._h = C.c_void_p()
@@ -148,7 +158,7 @@ class Plan:
         segs = (_Segment * max(1, n_seg))()
         for i in range(n_seg):
             segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
-        tune = _Tuning(chunk_elems, grid_norm, grid_apply, 0)
+        tune = _Tuning(chunk_norm, chunk_apply, grid_norm, grid_apply, unroll_apply, tune_flags, group_bytes)
         _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
                                  len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
                                  C.byref(tune)))
@@ -187,17 +197,20 @@ class Plan:
         return int(self._L.bca_plan_num_buckets(self._h))
 
     @property
-    def n_chunks(self) -> int:
-        return int(self._L.bca_plan_num_chunks(self._h))
+    def n_groups(self) -> int:
+        return int(self._L.bca_plan_num_groups(self._h))
 
-    def chunk_info(self, i: int):
+    def n_chunks(self, table: int = BCA_TABLE_APPLY) -> int:
+        return int(self._L.bca_plan_num_chunks(self._h, table))
+
+    def chunk_info(self, i: int, table: int = BCA_TABLE_APPLY):
         t, b, ln, bk = C.c_uint32(), C.c_uint64(), C.c_uint32(), C.c_uint32()
-        _check(self._L.bca_plan_chunk_info(self._h, i, C.byref(t), C.byref(b), C.byref(ln), C.byref(bk)))
+        _check(self._L.bca_plan_chunk_info(self._h, table, i, C.byref(t), C.byref(b), C.byref(ln), C.byref(bk)))
         return t.value, b.value, ln.value, bk.value
 
-    def bucket_chunks(self, b: int):
+    def bucket_chunks(self, b: int, table: int = BCA_TABLE_APPLY):
         f, n = C.c_uint32(), C.c_uint32()
-        _check(self._L.bca_plan_bucket_chunks(self._h, b, C.byref(f), C.byref(n)))
+        _check(self._L.bca_plan_bucket_chunks(self._h, table, b, C.byref(f), C.byref(n)))
         return f.value, n.value
 
     # -- binding
@@ -211,6 +224,17 @@ class Plan:
             return a
         _check(self._L.bca_plan_bind(self._h, arr(grads), arr(params), arr(exp_avg), arr(exp_avg_sq)))
         self._keep = (grads, params, exp_avg, exp_avg_sq)     # keep the tensors alive while bound
+
+    # -- per-kernel timing of the fused call
+    def profile(self, max_calls: int) -> None:
+        _check(self._L.bca_plan_profile(self._h, max_calls))
+
+    def profile_read(self):
+        """(ms_sqnorm, ms_finalize, ms_adam) summed over n_calls, and n_calls."""
+        ms = (C.c_double * 3)()
+        n = C.c_uint32()
+        _check(self._L.bca_plan_profile_read(self._h, ms, C.byref(n)))
+        return (ms[0], ms[1], ms[2]), int(n.value)
 
     # -- compute (same names as the C ABI)
     def bucket_clip_norms(self, b0: int, b1: int, norms, stream=None) -> None:

@@ -1,6 +1,6 @@
-// Host side of libbca: plan construction (layout validation, chunk table),
-// binding, argument checks and the four compute entry points.  See bca.h for
-// the contract of every call.
+// Host side of libbca: plan construction (layout validation, chunk tables,
+// bucket groups), binding, argument checks and the compute entry points.  See
+// bca.h for the contract of every call.
 
 #include <algorithm>
 #include <cmath>
@@ -89,36 +89,123 @@ int validate_layout(uint32_t n_tensors, const uint64_t* numel, uint32_t n_bucket
 
 // Cut every segment at multiples of chunk_elems counted from the start of its
 // tensor, so that all chunks but a segment's first start vector-aligned.
-void build_chunks(bca_plan* p, const uint64_t* seg_off, const bca_segment* segs) {
-  const uint64_t C = p->chunk_elems;
-  p->chunks.clear();
-  p->bucket_chunk_off.assign(p->n_buckets + 1, 0);
-  for (uint32_t b = 0; b < p->n_buckets; ++b) {
-    p->bucket_chunk_off[b] = (uint32_t)p->chunks.size();
+void build_table(Table* t, uint32_t chunk_elems, uint32_t n_buckets, const uint64_t* seg_off, const bca_segment* segs) {
+  const uint64_t C = chunk_elems;
+  t->chunk_elems = chunk_elems;
+  t->chunks.clear();
+  t->bucket_off.assign(n_buckets + 1, 0);
+  for (uint32_t b = 0; b < n_buckets; ++b) {
+    t->bucket_off[b] = (uint32_t)t->chunks.size();
     for (uint64_t s = seg_off[b]; s < seg_off[b + 1]; ++s) {
       uint64_t pos = segs[s].begin;
       const uint64_t end = segs[s].begin + segs[s].len;
       while (pos < end) {
         const uint64_t stop = std::min(end, (pos / C + 1) * C);
-        p->chunks.push_back(ChunkInfo{segs[s].tensor, (uint32_t)(stop - pos), pos, b});
+        t->chunks.push_back(ChunkInfo{segs[s].tensor, (uint32_t)(stop - pos), pos, b});
         pos = stop;
       }
     }
   }
-  p->bucket_chunk_off[p->n_buckets] = (uint32_t)p->chunks.size();
+  t->bucket_off[n_buckets] = (uint32_t)t->chunks.size();
+}
+
+// Consecutive buckets are put in one group until their gradients exceed
+// group_bytes (0: the library default).  A group has at least one bucket.
+void build_groups(bca_plan* p, uint64_t group_bytes, const uint64_t* seg_off, const bca_segment* segs) {
+  p->groups.clear();
+  const uint64_t gsize0 = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+  if (group_bytes == 0) group_bytes = kDefaultGroupElems * gsize0;
+  const uint64_t gsize = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+  uint32_t first = 0;
+  uint64_t acc = 0;
+  for (uint32_t b = 0; b < p->n_buckets; ++b) {
+    uint64_t bytes = 0;
+    for (uint64_t s = seg_off[b]; s < seg_off[b + 1]; ++s) bytes += segs[s].len * gsize;
+    if (b > first && acc + bytes > group_bytes) {
+      p->groups.emplace_back(first, b);
+      first = b;
+      acc = 0;
+    }
+    acc += bytes;
+  }
+  p->groups.emplace_back(first, p->n_buckets);
+}
+
+// Work items of the single-launch step in pipeline order: the squared-norm
+// chunks of group i+1 come before the Adam chunks of group i, so that by the
+// time a bucket's Adam items start, its norm has long been finished, and its
+// gradients are read twice within two groups' worth of traffic.
+void build_work(bca_plan* p) {
+  p->work.clear();
+  const Table& TN = p->norm_tab;
+  const Table& TA = p->apply_tab;
+  auto push_norm = [&](const std::pair<uint32_t, uint32_t>& g) {
+    for (uint32_t b = g.first; b < g.second; ++b) {
+      if (TN.bucket_off[b] == TN.bucket_off[b + 1]) p->work.push_back((kItemEmpty << 30) | b);
+      for (uint32_t c = TN.bucket_off[b]; c < TN.bucket_off[b + 1]; ++c) p->work.push_back((kItemNorm << 30) | c);
+    }
+  };
+  auto push_adam = [&](const std::pair<uint32_t, uint32_t>& g) {
+    for (uint32_t c = TA.bucket_off[g.first]; c < TA.bucket_off[g.second]; ++c) p->work.push_back((kItemAdam << 30) | c);
+  };
+  for (size_t i = 0; i < p->groups.size(); ++i) {
+    push_norm(p->groups[i]);
+    if (i > 0) push_adam(p->groups[i - 1]);
+  }
+  if (!p->groups.empty()) push_adam(p->groups.back());
+}
+
+void free_profile(bca_plan* p) {
+  for (hipEvent_t e : p->prof_events) (void)hipEventDestroy(e);
+  p->prof_events.clear();
+  p->prof_calls = 0;
 }
 
 void free_device(bca_plan* p) {
   if (p->device < 0) return;
   DeviceGuard g(p->device);
-  if (p->d_table) (void)hipFree(p->d_table);
+  free_profile(p);
+  for (Table* t : {&p->norm_tab, &p->apply_tab}) {
+    if (t->d_chunks) (void)hipFree(t->d_chunks);
+    if (t->d_bucket_off) (void)hipFree(t->d_bucket_off);
+    t->d_chunks = nullptr, t->d_bucket_off = nullptr;
+  }
+  if (p->d_work) (void)hipFree(p->d_work);
+  if (p->d_arrived) (void)hipFree(p->d_arrived);
+  if (p->d_ready) (void)hipFree(p->d_ready);
+  if (p->d_ctl) (void)hipFree(p->d_ctl);
+  p->d_work = nullptr, p->d_arrived = nullptr, p->d_ready = nullptr, p->d_ctl = nullptr;
   if (p->d_partials) (void)hipFree(p->d_partials);
-  if (p->d_bucket_chunk_off) (void)hipFree(p->d_bucket_chunk_off);
   if (p->d_norms) (void)hipFree(p->d_norms);
   if (p->d_coefs) (void)hipFree(p->d_coefs);
   if (p->d_status) (void)hipFree(p->d_status);
-  p->d_table = nullptr, p->d_partials = nullptr, p->d_bucket_chunk_off = nullptr;
-  p->d_norms = nullptr, p->d_coefs = nullptr, p->d_status = nullptr;
+  p->d_partials = nullptr, p->d_norms = nullptr, p->d_coefs = nullptr, p->d_status = nullptr;
+}
+
+hipError_t alloc_table(Table* t, uint32_t n_buckets) {
+  const size_t nc = std::max<size_t>(t->chunks.size(), 1);
+  hipError_t e = hipMalloc((void**)&t->d_chunks, nc * sizeof(Chunk));
+  if (e == hipSuccess) e = hipMalloc((void**)&t->d_bucket_off, (n_buckets + 1) * sizeof(uint32_t));
+  if (e == hipSuccess)
+    e = hipMemcpy(t->d_bucket_off, t->bucket_off.data(), (n_buckets + 1) * sizeof(uint32_t), hipMemcpyHostToDevice);
+  return e;
+}
+
+hipError_t upload_table(const bca_plan* p, Table* t, void* const* grads, float* const* params, float* const* exp_avg,
+                        float* const* exp_avg_sq) {
+  const uint64_t gsize = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+  std::vector<Chunk> table(std::max<size_t>(t->chunks.size(), 1));
+  memset(table.data(), 0, table.size() * sizeof(Chunk));
+  for (size_t i = 0; i < t->chunks.size(); ++i) {
+    const ChunkInfo& c = t->chunks[i];
+    table[i].g = (uint64_t)(uintptr_t)grads[c.tensor] + c.begin * gsize;
+    table[i].p = (uint64_t)(uintptr_t)params[c.tensor] + c.begin * 4;
+    table[i].m = (uint64_t)(uintptr_t)exp_avg[c.tensor] + c.begin * 4;
+    table[i].v = (uint64_t)(uintptr_t)exp_avg_sq[c.tensor] + c.begin * 4;
+    table[i].len = c.len;
+    table[i].bucket = c.bucket;
+  }
+  return hipMemcpy(t->d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice);
 }
 
 int check_ready(const bca_plan* p) {
@@ -157,10 +244,15 @@ int make_adam_constants(const bca_adam* hp, uint64_t step, AdamK* k) {
   return BCA_OK;
 }
 
-uint32_t pick_grid(uint32_t requested, uint32_t fallback, uint32_t n_chunks) {
-  uint32_t g = requested ? requested : fallback;
-  g = std::min(g, n_chunks);
-  return std::max(g, 1u);
+// requested == 0: one workgroup per chunk.
+Launch make_launch(const bca_plan* p, uint32_t requested, uint32_t n_chunks, bool g_keep) {
+  const uint32_t g = requested ? std::min(requested, n_chunks) : n_chunks;
+  Launch L;
+  L.grid = std::max(g, 1u);
+  L.unroll = p->unroll_apply;
+  L.staged = (p->tune_flags & BCA_TUNE_STAGE_TABLE_LDS) != 0;
+  L.g_keep = g_keep;
+  return L;
 }
 
 }  // namespace
@@ -185,11 +277,19 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   if (grad_dtype != BCA_GRAD_F32 && grad_dtype != BCA_GRAD_F16) return fail(BCA_ERR_DTYPE, "unknown gradient type");
   if (bucket_seg_off[n_buckets] && !segments) return fail(BCA_ERR_NULL, "segments is NULL");
   if (device < -1) return fail(BCA_ERR_RANGE, "device must be >= 0, or -1 for a host-only plan");
-  uint32_t chunk = kDefaultChunk;
-  if (tuning && tuning->chunk_elems) {
-    if (tuning->chunk_elems % 1024u || tuning->chunk_elems > (1u << 24))
-      return fail(BCA_ERR_RANGE, "chunk_elems must be a multiple of 1024 and at most 2^24");
-    chunk = tuning->chunk_elems;
+  uint32_t chunk_norm = kDefaultChunkNorm, chunk_apply = kDefaultChunkApply, unroll = 0;
+  if (tuning) {
+    for (uint32_t c : {tuning->chunk_norm, tuning->chunk_apply})
+      if (c % 1024u || c > (1u << 24)) return fail(BCA_ERR_RANGE, "chunk sizes must be multiples of 1024, at most 2^24");
+    if (tuning->chunk_norm) chunk_norm = tuning->chunk_norm;
+    if (tuning->chunk_apply) chunk_apply = tuning->chunk_apply;
+    if (tuning->unroll_apply) {
+      if (tuning->unroll_apply != 1 && tuning->unroll_apply != 2 && tuning->unroll_apply != 4)
+        return fail(BCA_ERR_RANGE, "unroll_apply must be 1, 2 or 4");
+      unroll = tuning->unroll_apply;
+    }
+    if (tuning->flags & ~(BCA_TUNE_MULTI_LAUNCH | BCA_TUNE_STAGE_TABLE_LDS | BCA_TUNE_TICKETS))
+      return fail(BCA_ERR_RANGE, "unknown tuning flag bits");
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
@@ -199,14 +299,19 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   p->grad_dtype = grad_dtype;
   p->n_tensors = n_tensors;
   p->n_buckets = n_buckets;
-  p->chunk_elems = chunk;
   p->grid_norm = tuning ? tuning->grid_norm : 0;
   p->grid_apply = tuning ? tuning->grid_apply : 0;
+  // default: as many 128-bit accesses in flight as one pass over a full chunk needs, at most 4
+  p->unroll_apply = unroll ? unroll : (chunk_apply >= 4096 ? 4u : chunk_apply >= 2048 ? 2u : 1u);
+  p->tune_flags = tuning ? tuning->flags : 0;
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
-  build_chunks(p, bucket_seg_off, segments);
-  if (p->chunks.size() >= (1ull << 31)) {
+  build_table(&p->norm_tab, chunk_norm, n_buckets, bucket_seg_off, segments);
+  build_table(&p->apply_tab, chunk_apply, n_buckets, bucket_seg_off, segments);
+  build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
+  build_work(p);
+  if (p->apply_tab.chunks.size() >= (1ull << 30) || p->norm_tab.chunks.size() >= (1ull << 30)) {
     delete p;
-    return fail(BCA_ERR_RANGE, "too many chunks; raise chunk_elems");
+    return fail(BCA_ERR_RANGE, "too many chunks; raise the chunk sizes");
   }
 
   if (device >= 0) {
@@ -227,19 +332,27 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
       delete p;
       return fail_hip(e, "hipGetDeviceProperties");
     }
-    const uint32_t cus = (uint32_t)std::max(prop.multiProcessorCount, 1);
-    if (!p->grid_norm) p->grid_norm = cus * 8;
-    if (!p->grid_apply) p->grid_apply = cus * 8;
-    const size_t nc = std::max<size_t>(p->chunks.size(), 1);
+    if (prop.warpSize != 64) {
+      delete p;
+      return fail(BCA_ERR_HIP, "the kernels need 64-wide wavefronts (gfx950)");
+    }
+    const size_t np = std::max<size_t>(p->norm_tab.chunks.size(), 1) * kWaves;
     const size_t nb = n_buckets;
-    if ((e = hipMalloc((void**)&p->d_table, nc * sizeof(Chunk))) != hipSuccess ||
-        (e = hipMalloc((void**)&p->d_partials, nc * sizeof(double))) != hipSuccess ||
-        (e = hipMalloc((void**)&p->d_bucket_chunk_off, (nb + 1) * sizeof(uint32_t))) != hipSuccess ||
+    if ((e = alloc_table(&p->norm_tab, n_buckets)) != hipSuccess ||
+        (e = alloc_table(&p->apply_tab, n_buckets)) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_work, std::max<size_t>(p->work.size(), 1) * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemcpy(p->d_work, p->work.data(), p->work.size() * sizeof(uint32_t), hipMemcpyHostToDevice)) !=
+            hipSuccess ||
+        (e = hipMalloc((void**)&p->d_arrived, nb * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemset(p->d_arrived, 0, nb * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_ready, nb * sizeof(unsigned long long))) != hipSuccess ||
+        (e = hipMemset(p->d_ready, 0, nb * sizeof(unsigned long long))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_ctl, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemset(p->d_ctl, 0, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_partials, np * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_norms, nb * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_coefs, nb * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_status, sizeof(int32_t))) != hipSuccess ||
-        (e = hipMemcpy(p->d_bucket_chunk_off, p->bucket_chunk_off.data(), (nb + 1) * sizeof(uint32_t),
-                       hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemset(p->d_status, 0, sizeof(int32_t))) != hipSuccess) {
       free_device(p);
       delete p;
@@ -269,23 +382,13 @@ int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* 
       return fail(BCA_ERR_ALIGN, buf);
     }
   }
-  std::vector<Chunk> table(std::max<size_t>(p->chunks.size(), 1));
-  memset(table.data(), 0, table.size() * sizeof(Chunk));
-  for (size_t i = 0; i < p->chunks.size(); ++i) {
-    const ChunkInfo& c = p->chunks[i];
-    table[i].g = (uint64_t)(uintptr_t)grads[c.tensor] + c.begin * gsize;
-    table[i].p = (uint64_t)(uintptr_t)params[c.tensor] + c.begin * 4;
-    table[i].m = (uint64_t)(uintptr_t)exp_avg[c.tensor] + c.begin * 4;
-    table[i].v = (uint64_t)(uintptr_t)exp_avg_sq[c.tensor] + c.begin * 4;
-    table[i].len = c.len;
-    table[i].bucket = c.bucket;
-  }
   DeviceGuard g(p->device);
-  // The copy is synchronous with respect to the host; kernels enqueued earlier
-  // on any stream may still be reading the old table, so wait for them first.
+  // The copies are synchronous with respect to the host; kernels enqueued earlier
+  // on any stream may still be reading the old tables, so wait for them first.
   hipError_t e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = hipMemcpy(p->d_table, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice);
-  if (e != hipSuccess) return fail_hip(e, "uploading the chunk table");
+  if (e == hipSuccess) e = upload_table(p, &p->norm_tab, grads, params, exp_avg, exp_avg_sq);
+  if (e == hipSuccess) e = upload_table(p, &p->apply_tab, grads, params, exp_avg, exp_avg_sq);
+  if (e != hipSuccess) return fail_hip(e, "uploading the chunk tables");
   p->bound = true;
   return BCA_OK;
 }
@@ -301,13 +404,32 @@ void bca_plan_destroy(bca_plan* p) {
 }
 
 uint32_t bca_plan_num_buckets(const bca_plan* p) { return p ? p->n_buckets : 0; }
-uint32_t bca_plan_num_chunks(const bca_plan* p) { return p ? (uint32_t)p->chunks.size() : 0; }
 
-int bca_plan_chunk_info(const bca_plan* p, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
+static const Table* pick_table(const bca_plan* p, int which) {
+  if (!p) {
+    fail(BCA_ERR_NULL, "plan is NULL");
+    return nullptr;
+  }
+  if (which != BCA_TABLE_NORM && which != BCA_TABLE_APPLY) {
+    fail(BCA_ERR_RANGE, "table must be BCA_TABLE_NORM or BCA_TABLE_APPLY");
+    return nullptr;
+  }
+  return which == BCA_TABLE_NORM ? &p->norm_tab : &p->apply_tab;
+}
+
+uint32_t bca_plan_num_chunks(const bca_plan* p, int which) {
+  const Table* t = pick_table(p, which);
+  return t ? (uint32_t)t->chunks.size() : 0;
+}
+
+uint32_t bca_plan_num_groups(const bca_plan* p) { return p ? (uint32_t)p->groups.size() : 0; }
+
+int bca_plan_chunk_info(const bca_plan* p, int which, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
                         uint32_t* bucket) {
-  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
-  if (i >= p->chunks.size()) return fail(BCA_ERR_RANGE, "chunk index out of range");
-  const ChunkInfo& c = p->chunks[i];
+  const Table* t = pick_table(p, which);
+  if (!t) return p ? BCA_ERR_RANGE : BCA_ERR_NULL;
+  if (i >= t->chunks.size()) return fail(BCA_ERR_RANGE, "chunk index out of range");
+  const ChunkInfo& c = t->chunks[i];
   if (tensor) *tensor = c.tensor;
   if (begin) *begin = c.begin;
   if (len) *len = c.len;
@@ -315,11 +437,60 @@ int bca_plan_chunk_info(const bca_plan* p, uint32_t i, uint32_t* tensor, uint64_
   return BCA_OK;
 }
 
-int bca_plan_bucket_chunks(const bca_plan* p, uint32_t b, uint32_t* first, uint32_t* count) {
-  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+int bca_plan_bucket_chunks(const bca_plan* p, int which, uint32_t b, uint32_t* first, uint32_t* count) {
+  const Table* t = pick_table(p, which);
+  if (!t) return p ? BCA_ERR_RANGE : BCA_ERR_NULL;
   if (b >= p->n_buckets) return fail(BCA_ERR_RANGE, "bucket index out of range");
-  if (first) *first = p->bucket_chunk_off[b];
-  if (count) *count = p->bucket_chunk_off[b + 1] - p->bucket_chunk_off[b];
+  if (first) *first = t->bucket_off[b];
+  if (count) *count = t->bucket_off[b + 1] - t->bucket_off[b];
+  return BCA_OK;
+}
+
+// Events one profiled fused call records: one before the first kernel and one after each.
+static size_t events_per_call(const bca_plan* p) {
+  return (p->tune_flags & BCA_TUNE_MULTI_LAUNCH) ? 1 + 3 * p->groups.size() : 3;
+}
+
+int bca_plan_profile(bca_plan* p, uint32_t max_calls) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan");
+  if (max_calls > 65536) return fail(BCA_ERR_RANGE, "at most 65536 profiled calls");
+  DeviceGuard g(p->device);
+  (void)hipDeviceSynchronize();
+  free_profile(p);
+  const size_t per_call = events_per_call(p);
+  for (size_t i = 0; i < max_calls * per_call; ++i) {
+    hipEvent_t ev;
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) {
+      free_profile(p);
+      return fail_hip(e, "hipEventCreate");
+    }
+    p->prof_events.push_back(ev);
+  }
+  return BCA_OK;
+}
+
+int bca_plan_profile_read(bca_plan* p, double* ms, uint32_t* n_calls) {
+  if (!p || !ms || !n_calls) return fail(BCA_ERR_NULL, "NULL argument");
+  ms[0] = ms[1] = ms[2] = 0.0;
+  *n_calls = 0;
+  if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan");
+  DeviceGuard g(p->device);
+  const size_t per_call = events_per_call(p);
+  for (uint32_t c = 0; c < p->prof_calls; ++c) {
+    hipEvent_t* ev = &p->prof_events[(size_t)c * per_call];
+    hipError_t e = hipEventSynchronize(ev[per_call - 1]);
+    for (size_t k = 0; k + 1 < per_call && e == hipSuccess; ++k) {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, ev[k], ev[k + 1]);
+      // multi-launch: squared norm, finalize, Adam in turn; single launch: prepare, then the step kernel
+      ms[per_call == 3 ? (k == 0 ? 0 : 2) : k % 3] += t;
+    }
+    if (e != hipSuccess) return fail_hip(e, "reading profile events");
+  }
+  *n_calls = p->prof_calls;
+  p->prof_calls = 0;
   return BCA_OK;
 }
 
@@ -331,11 +502,14 @@ int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void*
   if (b0 == b1) return BCA_OK;
   DeviceGuard g(p->device);
   hipStream_t s = (hipStream_t)stream;
-  const uint32_t c0 = p->bucket_chunk_off[b0], n = p->bucket_chunk_off[b1] - c0;
-  hipError_t e = launch_sqnorm(p->grad_dtype, p->d_table, c0, n, p->d_partials, nullptr,
-                               pick_grid(p->grid_norm, 2048, n), s);
+  const Table& T = p->norm_tab;
+  const uint32_t c0 = T.bucket_off[b0], n = T.bucket_off[b1] - c0;
+  // Called per bucket as buckets become ready, bucket_clip_apply follows shortly:
+  // keep the gradients cacheable.
+  hipError_t e = launch_sqnorm(p->grad_dtype, T.d_chunks, c0, n, p->d_partials, nullptr,
+                               make_launch(p, p->grid_norm, n, true), s);
   if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
-  e = launch_finalize(p->d_partials, p->d_bucket_chunk_off, b0, b1, nullptr, norms, nullptr, nullptr, s);
+  e = launch_finalize(p->d_partials, T.d_bucket_off, b0, b1, nullptr, norms, nullptr, nullptr, s);
   if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
   return BCA_OK;
 }
@@ -353,8 +527,9 @@ int bucket_clip_apply(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresh
   hipError_t e = launch_coefs(b0, b1, thresholds, norms, cf, status, s);
   if (e != hipSuccess) return fail_hip(e, "launching the coefficient kernel");
   if (b0 == b1) return BCA_OK;
-  const uint32_t c0 = p->bucket_chunk_off[b0], n = p->bucket_chunk_off[b1] - c0;
-  e = launch_scale(p->grad_dtype, p->d_table, c0, n, cf, pick_grid(p->grid_apply, 2048, n), s);
+  const Table& T = p->apply_tab;
+  const uint32_t c0 = T.bucket_off[b0], n = T.bucket_off[b1] - c0;
+  e = launch_scale(p->grad_dtype, T.d_chunks, c0, n, cf, make_launch(p, p->grid_apply, n, true), s);
   if (e != hipSuccess) return fail_hip(e, "launching the scale kernel");
   return BCA_OK;
 }
@@ -365,9 +540,10 @@ int adam_step(bca_plan* p, const bca_adam* hp, uint64_t step, void* stream) {
   if (int rc = make_adam_constants(hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
   DeviceGuard g(p->device);
-  const uint32_t n = (uint32_t)p->chunks.size();
-  hipError_t e = launch_adam(p->grad_dtype, p->d_table, 0, n, nullptr, false, nullptr, k,
-                             pick_grid(p->grid_apply, 2048, n), (hipStream_t)stream);
+  const Table& T = p->apply_tab;
+  const uint32_t n = (uint32_t)T.chunks.size();
+  hipError_t e = launch_adam(p->grad_dtype, T.d_chunks, 0, n, nullptr, false, nullptr, k,
+                             make_launch(p, p->grid_apply, n, false), (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(e, "launching the Adam kernel");
   return BCA_OK;
 }
@@ -380,19 +556,62 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
   AdamK k;
   if (int rc = make_adam_constants(hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
+  const bool skip = (flags & BCA_SKIP_STEP_ON_NONFINITE) != 0;
+  const bool multi = (p->tune_flags & BCA_TUNE_MULTI_LAUNCH) != 0;
   DeviceGuard g(p->device);
   hipStream_t s = (hipStream_t)stream;
-  const uint32_t n = (uint32_t)p->chunks.size();
   float* nm = norms ? norms : p->d_norms;
   float* cf = coefs ? coefs : p->d_coefs;
   int32_t* st = status ? status : p->d_status;
-  hipError_t e = launch_sqnorm(p->grad_dtype, p->d_table, 0, n, p->d_partials, st, pick_grid(p->grid_norm, 2048, n), s);
-  if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
-  e = launch_finalize(p->d_partials, p->d_bucket_chunk_off, 0, p->n_buckets, thresholds, nm, cf, st, s);
-  if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
-  e = launch_adam(p->grad_dtype, p->d_table, 0, n, cf, (flags & BCA_WRITE_BACK_GRADS) != 0,
-                  (flags & BCA_SKIP_STEP_ON_NONFINITE) ? st : nullptr, k, pick_grid(p->grid_apply, 2048, n), s);
-  if (e != hipSuccess) return fail_hip(e, "launching the Adam kernel");
+  const size_t per_call = events_per_call(p);
+  hipEvent_t* ev = nullptr;  // events of this call when profiling has room left
+  if (!(skip && !multi) && (size_t)(p->prof_calls + 1) * per_call <= p->prof_events.size())
+    ev = &p->prof_events[(size_t)p->prof_calls++ * per_call];
+
+  if (!multi && !skip) {
+    // One launch for the whole step (plus the tiny reset kernel).
+    StepState ss;
+    ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
+    ss.norm_bucket_off = p->norm_tab.d_bucket_off;
+    ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+    if (ev) (void)hipEventRecord(ev[0], s);
+    hipError_t e = launch_step(p->grad_dtype, ss, p->n_buckets, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cf,
+                               st, (flags & BCA_WRITE_BACK_GRADS) != 0, k, p->unroll_apply,
+                               (p->tune_flags & BCA_TUNE_TICKETS) != 0, ev ? ev[1] : nullptr, s);
+    if (e != hipSuccess) return fail_hip(e, "launching the fused step kernel");
+    if (ev) (void)hipEventRecord(ev[2], s);
+    return BCA_OK;
+  }
+
+  // Several launches.  The skip decision covers all buckets, so that mode takes one
+  // group: all norms first, then one Adam sweep that checks the status word.
+  std::vector<std::pair<uint32_t, uint32_t>> one_group(1, std::make_pair(0u, p->n_buckets));
+  const auto& groups = skip ? one_group : p->groups;
+  if (ev) (void)hipEventRecord(*ev++, s);
+  // With groups, a group's gradients are read twice in quick succession (norm,
+  // then Adam) and are kept cacheable; everything else streams.
+  const bool keep = groups.size() > 1;
+  bool first = true;
+  for (const auto& gr : groups) {
+    const uint32_t b0 = gr.first, b1 = gr.second;
+    const Table& TN = p->norm_tab;
+    const Table& TA = p->apply_tab;
+    const uint32_t cn0 = TN.bucket_off[b0], nn = TN.bucket_off[b1] - cn0;
+    const uint32_t ca0 = TA.bucket_off[b0], na = TA.bucket_off[b1] - ca0;
+    // the first squared-norm launch of a call also clears the status word
+    hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, cn0, nn, p->d_partials, first ? st : nullptr,
+                                 make_launch(p, p->grid_norm, nn, keep), s);
+    if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
+    if (ev) (void)hipEventRecord(*ev++, s);
+    e = launch_finalize(p->d_partials, TN.d_bucket_off, b0, b1, thresholds, nm, cf, st, s);
+    if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
+    if (ev) (void)hipEventRecord(*ev++, s);
+    e = launch_adam(p->grad_dtype, TA.d_chunks, ca0, na, cf, (flags & BCA_WRITE_BACK_GRADS) != 0, skip ? st : nullptr,
+                    k, make_launch(p, p->grid_apply, na, keep), s);
+    if (e != hipSuccess) return fail_hip(e, "launching the Adam kernel");
+    if (ev) (void)hipEventRecord(*ev++, s);
+    first = false;
+  }
   return BCA_OK;
 }
 

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "bca.h"
@@ -14,9 +15,9 @@
 namespace bca {
 
 // One unit of work: at most chunk_elems consecutive elements of one tensor, all
-// in one bucket.  Chunks are stored bucket by bucket, so chunk index == slot of
-// that chunk's partial sum, and a bucket's partials are contiguous.  The four
-// addresses are filled in by bca_plan_bind.
+// in one bucket.  Chunks are stored bucket by bucket, so a bucket's chunks (and
+// their partial sums) are contiguous.  The four addresses are filled in by
+// bca_plan_bind.
 struct alignas(16) Chunk {
   uint64_t g, p, m, v;  // device byte addresses of the chunk's first element
   uint32_t len;         // elements
@@ -32,6 +33,17 @@ struct ChunkInfo {  // host-side description, independent of addresses
   uint32_t bucket;
 };
 
+// One cut of the layout into chunks.  A plan holds two: a coarse one for the
+// squared-norm pass (fewer partial sums) and a fine one for the passes that
+// read and write (scale, Adam), where short-lived workgroups stream best.
+struct Table {
+  uint32_t chunk_elems = 0;
+  std::vector<ChunkInfo> chunks;     // bucket-major
+  std::vector<uint32_t> bucket_off;  // [n_buckets + 1] first chunk of each bucket
+  Chunk* d_chunks = nullptr;         // device copy with addresses (after bind)
+  uint32_t* d_bucket_off = nullptr;
+};
+
 // Adam constants, computed in fp64 on the host and rounded once to fp32.
 struct AdamK {
   float b1, omb1;    // beta1, 1 - beta1
@@ -45,25 +57,59 @@ struct AdamK {
 constexpr uint32_t kBlock = 256;          // threads per workgroup (4 wavefronts)
 constexpr uint32_t kWaves = kBlock / 64;  // wavefronts per workgroup
 constexpr uint32_t kSlice = 64;           // chunk-table entries staged in LDS at a time
-constexpr uint32_t kDefaultChunk = 16384;
+constexpr uint32_t kDefaultChunkNorm = 65536;
+constexpr uint32_t kDefaultChunkApply = 1024;
+// Buckets are pipelined in groups of about this many elements (at least one bucket):
+// large enough that a group's norms are done before its Adam items start, small enough
+// that two groups' gradients stay in the Infinity Cache (measured optimum on MI355X).
+constexpr uint64_t kDefaultGroupElems = 8ull << 20;
+
+// How a streaming kernel is launched.
+struct Launch {
+  uint32_t grid;    // workgroups
+  uint32_t unroll;  // 128-bit accesses in flight per lane and array in the scale / Adam sweeps: 1, 2 or 4
+  bool staged;      // persistent grid staging its table entries in LDS (else one uniform entry load per chunk)
+  bool g_keep;      // gradients are loaded with the normal (cacheable) policy because they are read again soon
+};
+
+// Device-side state of the single-launch fused step (k_prepare / k_step).
+// Control words, each in its own 128-byte line: eight ticket counters (one per XCD) at
+// kCtlTicket + 32 y, the epoch, the abort flag.
+enum : uint32_t { kCtlTicket = 0, kCtlEpoch = 256, kCtlAbort = 288, kCtlWords = 320 };
+constexpr uint32_t kItemNorm = 0u, kItemAdam = 1u, kItemEmpty = 2u;  // work item kinds, in bits 30..31 of an item
+struct StepState {
+  const Chunk* norm_tab;
+  const Chunk* apply_tab;
+  const uint32_t* norm_bucket_off;  // [B + 1] chunks of the norm table per bucket
+  double* partials;                 // kWaves per norm chunk
+  uint32_t* arrived;                // [B] squared-norm workgroups done per bucket
+  unsigned long long* ready;        // [B] (epoch << 32) | bits of the bucket's coefficient
+  uint32_t* ctl;                    // [kCtlWords] ticket counter, epoch
+};
 
 // Kernel launchers (bca_kernels.hip).  All enqueue on `stream` and return the
-// launch's hipError_t.  c0/n: first chunk and number of chunks.
+// launch's hipError_t.  c0/n: first chunk and number of chunks.  partials holds
+// kWaves doubles per chunk of the norm table.
 hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, double* partials, int32_t* status,
-                         uint32_t grid, hipStream_t stream);
+                         const Launch& L, hipStream_t stream);
 // norms/coefs/status may alias plan scratch.  thresholds == nullptr: norms only.
 hipError_t launch_finalize(const double* partials, const uint32_t* bucket_chunk_off, uint32_t b0, uint32_t b1,
                            const float* thresholds, float* norms, float* coefs, int32_t* status,
                            hipStream_t stream);
 hipError_t launch_coefs(uint32_t b0, uint32_t b1, const float* thresholds, const float* norms, float* coefs,
                         int32_t* status, hipStream_t stream);
-hipError_t launch_zero_status(int32_t* status, hipStream_t stream);
-hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, uint32_t grid,
+hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, const Launch& L,
                         hipStream_t stream);
 // coefs == nullptr: plain Adam on the stored gradient.  skip_status != nullptr:
 // the kernel returns at once if (*skip_status & BCA_STATUS_NONFINITE).
 hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
-                       const int32_t* skip_status, const AdamK& k, uint32_t grid, hipStream_t stream);
+                       const int32_t* skip_status, const AdamK& k, const Launch& L, hipStream_t stream);
+
+// The whole fused step: k_prepare, then one k_step workgroup per work item.  `between`
+// (may be null) is recorded between the two kernels.
+hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
+                       const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
+                       const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream);
 
 void set_error(const std::string& msg);
 
@@ -73,19 +119,28 @@ struct bca_plan {
   int device = -1;  // -1: host-only
   int grad_dtype = BCA_GRAD_F32;
   uint32_t n_tensors = 0, n_buckets = 0;
-  uint32_t chunk_elems = bca::kDefaultChunk;
-  uint32_t grid_norm = 0, grid_apply = 0;
+  uint32_t grid_norm = 0, grid_apply = 0;  // 0: one workgroup per chunk
+  uint32_t unroll_apply = 1;
+  uint32_t tune_flags = 0;
   bool bound = false;
   std::vector<uint64_t> tensor_numel;
-  std::vector<bca::ChunkInfo> chunks;        // bucket-major
-  std::vector<uint32_t> bucket_chunk_off;    // [n_buckets + 1]
+  bca::Table norm_tab, apply_tab;
+  // the fused call walks the buckets in groups [first, last)
+  std::vector<std::pair<uint32_t, uint32_t>> groups;
+  // work list of the single-launch step: (kind << 30) | index, in pipeline order
+  std::vector<uint32_t> work;
+  uint32_t* d_work = nullptr;
+  uint32_t* d_arrived = nullptr;
+  unsigned long long* d_ready = nullptr;
+  uint32_t* d_ctl = nullptr;
   // device memory owned by the plan
-  bca::Chunk* d_table = nullptr;
   double* d_partials = nullptr;
-  uint32_t* d_bucket_chunk_off = nullptr;
   float* d_norms = nullptr;
   float* d_coefs = nullptr;
   int32_t* d_status = nullptr;
+  // per-kernel timing of the fused call: 1 + 3 * groups events per profiled call
+  std::vector<hipEvent_t> prof_events;
+  uint32_t prof_calls = 0;
 };
 
 #endif  // BCA_INTERNAL_H_

@@ -1,19 +1,22 @@
 // HIP kernels for gfx950 (MI355X): squared-norm partials, per-bucket finalize,
 // in-place scale, and the (optionally clip-fused) Adam sweep.
 //
-// All four streaming kernels are table driven: the host cuts the bucket layout
-// into chunks (<= chunk_elems consecutive elements of one tensor in one bucket,
-// bca_internal.h) and every workgroup of a persistent grid walks a static,
-// interleaved share of that table (chunk c0 + w, c0 + w + G, ...), staging its
-// entries in LDS.  Neighbouring workgroups therefore stream through
-// neighbouring memory at the same time, and which workgroup handles a chunk
-// never changes a result: a chunk's partial sum depends only on the chunk.
+// All streaming kernels are table driven: the host cuts the bucket layout into
+// chunks (<= chunk_elems consecutive elements of one tensor in one bucket,
+// bca_internal.h) and workgroup w of a grid of G walks chunks c0+w, c0+w+G, ...
+// Neighbouring workgroups therefore stream through neighbouring memory at the
+// same time, and which workgroup handles a chunk never changes a result: a
+// chunk's partial sums depend only on the chunk.  Two ways to fetch the table
+// are compiled (STAGED): a persistent grid that copies its share of entries
+// into LDS in slices, or uniform (scalar) loads of one entry per iteration,
+// which is what a grid of one workgroup per chunk uses.
 //
 // Memory access: 128-bit loads/stores, lane-contiguous (a wavefront touches
 // 1 KiB per instruction per array), several independent loads in flight per
-// lane before first use.  A chunk whose arrays are not mutually 16-byte
-// congruent falls back to element-wise access.  No MFMA: nothing here is a
-// contraction; the path is bound by HBM bandwidth.
+// lane before first use, streaming (non-temporal) hints on data touched once.
+// A chunk whose arrays are not mutually 16-byte congruent falls back to
+// element-wise access.  No MFMA: nothing here is a contraction; the path is
+// bound by HBM bandwidth.
 //
 // Arithmetic follows the paper's definitions: clipping-by-norm (Sec. 2.3)
 // applied per bucket (Sec. 4.2, Alg. 1) and Adam (Alg. 1, last line; Kingma &
@@ -22,6 +25,8 @@
 // paths produce the same bits.
 
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "bca_internal.h"
 
@@ -32,7 +37,33 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// ---- chunk-table slice in LDS ------------------------------------------------
+// ---- streaming accesses ---------------------------------------------------------
+// NT = non-temporal: data that is touched once per launch is loaded and stored
+// with the streaming hint, which raises HBM throughput on gfx950 and keeps such
+// lines from displacing reusable ones in L2 / Infinity Cache.
+template <bool NT, typename T>
+__device__ __forceinline__ T ldv(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void stv(T* p, T x) {
+  if constexpr (NT) __builtin_nontemporal_store(x, p);
+  else *p = x;
+}
+
+// ---- chunk table access -----------------------------------------------------------
+
+struct Entry {  // one chunk, in registers (uniform across the workgroup)
+  uint64_t g, p, m, v;
+  uint32_t len, bucket;
+};
+
+__device__ __forceinline__ Entry read_entry(const Chunk* e) {
+  Entry r;
+  r.g = e->g, r.p = e->p, r.m = e->m, r.v = e->v, r.len = e->len, r.bucket = e->bucket;
+  return r;
+}
 
 // Number of chunks workgroup w of G owns out of n under interleaved assignment.
 __device__ __forceinline__ uint32_t my_chunk_count(uint32_t n, uint32_t w, uint32_t G) {
@@ -51,6 +82,25 @@ __device__ __forceinline__ void stage_slice(Chunk* s_tab, const Chunk* table, ui
   }
 }
 
+// Calls body(entry, chunk_index) for every chunk of this workgroup.
+template <bool STAGED, typename F>
+__device__ __forceinline__ void for_each_chunk(const Chunk* __restrict__ table, uint32_t c0, uint32_t n, F body) {
+  const uint32_t w = blockIdx.x, Gn = gridDim.x;
+  if constexpr (STAGED) {
+    __shared__ Chunk s_tab[kSlice];
+    const uint32_t mine = my_chunk_count(n, w, Gn);
+    for (uint32_t first = 0; first < mine; first += kSlice) {
+      const uint32_t cnt = min(kSlice, mine - first);
+      stage_slice(s_tab, table, c0, w, Gn, first, cnt);
+      __syncthreads();
+      for (uint32_t e = 0; e < cnt; ++e) body(read_entry(&s_tab[e]), c0 + w + (first + e) * Gn);
+      __syncthreads();
+    }
+  } else {
+    for (uint32_t i = w; i < n; i += Gn) body(read_entry(&table[c0 + i]), c0 + i);
+  }
+}
+
 // ---- gradient access by storage type -----------------------------------------
 
 template <int GDT>
@@ -59,11 +109,13 @@ struct Grad;
 template <>
 struct Grad<BCA_GRAD_F32> {
   typedef float elem;
+  template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
-    return reinterpret_cast<const f32x4*>(base)[vec];
+    return ldv<NT>(reinterpret_cast<const f32x4*>(base) + vec);
   }
+  template <bool NT>
   static __device__ __forceinline__ void store4(void* base, uint32_t vec, f32x4 x) {
-    reinterpret_cast<f32x4*>(base)[vec] = x;
+    stv<NT>(reinterpret_cast<f32x4*>(base) + vec, x);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
     return reinterpret_cast<const float*>(base)[i];
@@ -77,16 +129,18 @@ template <>
 struct Grad<BCA_GRAD_F16> {
   typedef _Float16 elem;
   // fp16 -> fp32 is exact (subnormals included); fp32 -> fp16 rounds to nearest even.
+  template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
-    const f16x4 h = reinterpret_cast<const f16x4*>(base)[vec];
+    const f16x4 h = ldv<NT>(reinterpret_cast<const f16x4*>(base) + vec);
     f32x4 r;
     r.x = (float)h.x, r.y = (float)h.y, r.z = (float)h.z, r.w = (float)h.w;
     return r;
   }
+  template <bool NT>
   static __device__ __forceinline__ void store4(void* base, uint32_t vec, f32x4 x) {
     f16x4 h;
     h.x = (_Float16)x.x, h.y = (_Float16)x.y, h.z = (_Float16)x.z, h.w = (_Float16)x.w;
-    reinterpret_cast<f16x4*>(base)[vec] = h;
+    stv<NT>(reinterpret_cast<f16x4*>(base) + vec, h);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
     return (float)reinterpret_cast<const _Float16*>(base)[i];
@@ -97,17 +151,13 @@ struct Grad<BCA_GRAD_F16> {
 };
 
 // Number of leading elements to handle one by one so that what follows can be
-// accessed as aligned vectors of `vec_elems` elements in every listed array, or
-// `len` if no such head exists (mutually incongruent or misaligned addresses).
-// g_addr uses gsize-byte elements, the fp32 arrays 4-byte elements.
+// accessed as aligned vectors (g in g_vec_bytes pieces, the fp32 arrays in 16-byte
+// pieces), or `len` if no such head exists (mutually incongruent addresses).
 __device__ __forceinline__ uint32_t vector_head(uint32_t len, uint64_t g_addr, uint32_t gsize, uint32_t g_vec_bytes,
                                                 bool with_state, uint64_t p, uint64_t m, uint64_t v) {
-  const uint32_t vec_elems = g_vec_bytes / gsize;
-  // smallest h in [0, vec_elems) with (g_addr + h*gsize) % g_vec_bytes == 0
   const uint32_t mis = (uint32_t)(g_addr & (g_vec_bytes - 1));
   if (mis % gsize) return len;
   const uint32_t h = ((g_vec_bytes - mis) & (g_vec_bytes - 1)) / gsize;
-  (void)vec_elems;
   if (with_state) {
     const uint64_t sh = (uint64_t)h * 4u;
     if (((p + sh) | (m + sh) | (v + sh)) & 15u) return len;
@@ -125,104 +175,96 @@ __device__ __forceinline__ double wave_sum(double x) {
 
 // ---- squared-norm partials ------------------------------------------------------
 
-// One partial (fp64) per chunk: sum over the chunk of g^2.  Per lane the squares
-// are accumulated in fp32 (four independent accumulators, at most
-// chunk_elems/1024 terms each), then combined in fp64: lanes by butterfly
-// shuffles, the four wavefronts through LDS in index order.
-template <int GDT>
-__global__ __launch_bounds__(kBlock) void k_sqnorm(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
-                                                    double* __restrict__ partials, int32_t* status) {
-  __shared__ Chunk s_tab[kSlice];
-  __shared__ double s_part[kSlice][kWaves];
+// Sum of g^2 over the part of a chunk this wavefront reads, in fp64 (same value
+// in every lane).  Per lane the squares are accumulated in fp32 (four independent
+// accumulators, at most chunk_elems/1024 terms each), then the lanes are combined
+// in fp64 by butterfly shuffles.  Wavefronts never wait for each other.
+template <int GDT, bool NT>
+__device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
   typedef Grad<GDT> G;
   constexpr uint32_t gsize = sizeof(typename G::elem);
   constexpr uint32_t VE = 16u / gsize;  // elements per 128-bit load: 4 (fp32) or 8 (fp16)
   constexpr uint32_t U = 8;             // loads in flight per lane
+  const uint32_t tid = threadIdx.x;
+  const uint64_t ga = en.g;
+  const uint32_t len = en.len;
+  const uint32_t head = vector_head(len, ga, gsize, 16u, false, 0, 0, 0);
+  const uint32_t nvec = (len - head) / VE;
+  const uint32_t tail0 = head + nvec * VE;
+  const void* gbase = reinterpret_cast<const void*>(ga);
+  const void* gv = reinterpret_cast<const void*>(ga + (uint64_t)head * gsize);
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 
-  const uint32_t w = blockIdx.x, Gn = gridDim.x, tid = threadIdx.x;
-  if (status != nullptr && w == 0 && tid == 0) *status = 0;  // finalize ORs into it later on this stream
-  const uint32_t mine = my_chunk_count(n, w, Gn);
-
-  for (uint32_t first = 0; first < mine; first += kSlice) {
-    const uint32_t cnt = min(kSlice, mine - first);
-    stage_slice(s_tab, table, c0, w, Gn, first, cnt);
-    __syncthreads();
-    for (uint32_t e = 0; e < cnt; ++e) {
-      const uint64_t ga = s_tab[e].g;
-      const uint32_t len = s_tab[e].len;
-      const uint32_t head = vector_head(len, ga, gsize, 16u, false, 0, 0, 0);
-      const uint32_t nvec = (len - head) / VE;
-      const uint32_t tail0 = head + nvec * VE;
-      const void* gbase = reinterpret_cast<const void*>(ga);
-      const void* gv = reinterpret_cast<const void*>(ga + (uint64_t)head * gsize);
-      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-
-      for (uint32_t base = 0; base < nvec; base += kBlock * U) {
-        const uint32_t j0 = base + tid;
-        if (base + kBlock * U <= nvec) {
+  for (uint32_t base = 0; base < nvec; base += kBlock * U) {
+    const uint32_t j0 = base + tid;
+    if (base + kBlock * U <= nvec) {
+      if constexpr (GDT == BCA_GRAD_F32) {
+        f32x4 x[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(reinterpret_cast<const f32x4*>(gv) + j0 + u * kBlock);
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+          a0 = __fmaf_rn(x[u].x, x[u].x, a0), a1 = __fmaf_rn(x[u].y, x[u].y, a1);
+          a2 = __fmaf_rn(x[u].z, x[u].z, a2), a3 = __fmaf_rn(x[u].w, x[u].w, a3);
+        }
+      } else {
+        f16x8 x[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(reinterpret_cast<const f16x8*>(gv) + j0 + u * kBlock);
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+          const float f0 = (float)x[u][0], f1 = (float)x[u][1], f2 = (float)x[u][2], f3 = (float)x[u][3];
+          const float f4 = (float)x[u][4], f5 = (float)x[u][5], f6 = (float)x[u][6], f7 = (float)x[u][7];
+          a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1), a2 = __fmaf_rn(f2, f2, a2);
+          a3 = __fmaf_rn(f3, f3, a3), a0 = __fmaf_rn(f4, f4, a0), a1 = __fmaf_rn(f5, f5, a1);
+          a2 = __fmaf_rn(f6, f6, a2), a3 = __fmaf_rn(f7, f7, a3);
+        }
+      }
+    } else {
+      for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t j = j0 + u * kBlock;
+        if (j < nvec) {
           if constexpr (GDT == BCA_GRAD_F32) {
-            f32x4 x[U];
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u) x[u] = reinterpret_cast<const f32x4*>(gv)[j0 + u * kBlock];
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u) {
-              a0 = __fmaf_rn(x[u].x, x[u].x, a0), a1 = __fmaf_rn(x[u].y, x[u].y, a1);
-              a2 = __fmaf_rn(x[u].z, x[u].z, a2), a3 = __fmaf_rn(x[u].w, x[u].w, a3);
-            }
+            const f32x4 x = ldv<NT>(reinterpret_cast<const f32x4*>(gv) + j);
+            a0 = __fmaf_rn(x.x, x.x, a0), a1 = __fmaf_rn(x.y, x.y, a1);
+            a2 = __fmaf_rn(x.z, x.z, a2), a3 = __fmaf_rn(x.w, x.w, a3);
           } else {
-            f16x8 x[U];
+            const f16x8 x = ldv<NT>(reinterpret_cast<const f16x8*>(gv) + j);
 #pragma unroll
-            for (uint32_t u = 0; u < U; ++u) x[u] = reinterpret_cast<const f16x8*>(gv)[j0 + u * kBlock];
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u) {
-              const float f0 = (float)x[u][0], f1 = (float)x[u][1], f2 = (float)x[u][2], f3 = (float)x[u][3];
-              const float f4 = (float)x[u][4], f5 = (float)x[u][5], f6 = (float)x[u][6], f7 = (float)x[u][7];
-              a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1), a2 = __fmaf_rn(f2, f2, a2);
-              a3 = __fmaf_rn(f3, f3, a3), a0 = __fmaf_rn(f4, f4, a0), a1 = __fmaf_rn(f5, f5, a1);
-              a2 = __fmaf_rn(f6, f6, a2), a3 = __fmaf_rn(f7, f7, a3);
-            }
-          }
-        } else {
-          for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t j = j0 + u * kBlock;
-            if (j < nvec) {
-              if constexpr (GDT == BCA_GRAD_F32) {
-                const f32x4 x = reinterpret_cast<const f32x4*>(gv)[j];
-                a0 = __fmaf_rn(x.x, x.x, a0), a1 = __fmaf_rn(x.y, x.y, a1);
-                a2 = __fmaf_rn(x.z, x.z, a2), a3 = __fmaf_rn(x.w, x.w, a3);
-              } else {
-                const f16x8 x = reinterpret_cast<const f16x8*>(gv)[j];
-#pragma unroll
-                for (int q = 0; q < 8; q += 4) {
-                  const float f0 = (float)x[q], f1 = (float)x[q + 1], f2 = (float)x[q + 2], f3 = (float)x[q + 3];
-                  a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1);
-                  a2 = __fmaf_rn(f2, f2, a2), a3 = __fmaf_rn(f3, f3, a3);
-                }
-              }
+            for (int q = 0; q < 8; q += 4) {
+              const float f0 = (float)x[q], f1 = (float)x[q + 1], f2 = (float)x[q + 2], f3 = (float)x[q + 3];
+              a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1);
+              a2 = __fmaf_rn(f2, f2, a2), a3 = __fmaf_rn(f3, f3, a3);
             }
           }
         }
       }
-      // head and tail elements one by one (fewer than VE each unless the chunk is unaligned throughout)
-      for (uint32_t i = tid; i < head; i += kBlock) {
-        const float x = G::load1(gbase, i);
-        a0 = __fmaf_rn(x, x, a0);
-      }
-      for (uint32_t i = tail0 + tid; i < len; i += kBlock) {
-        const float x = G::load1(gbase, i);
-        a1 = __fmaf_rn(x, x, a1);
-      }
-      const double lane = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
-      const double ws = wave_sum(lane);
-      if ((tid & 63u) == 0) s_part[e][tid >> 6] = ws;
     }
-    __syncthreads();
-    for (uint32_t e = tid; e < cnt; e += kBlock) {
-      const uint64_t ci = (uint64_t)c0 + w + (uint64_t)(first + e) * Gn;
-      partials[ci] = ((s_part[e][0] + s_part[e][1]) + s_part[e][2]) + s_part[e][3];
-    }
-    __syncthreads();
   }
+  // head and tail elements one by one (fewer than VE each unless the chunk is unaligned throughout)
+  for (uint32_t i = tid; i < head; i += kBlock) {
+    const float x = G::load1(gbase, i);
+    a0 = __fmaf_rn(x, x, a0);
+  }
+  for (uint32_t i = tail0 + tid; i < len; i += kBlock) {
+    const float x = G::load1(gbase, i);
+    a1 = __fmaf_rn(x, x, a1);
+  }
+  const double lane = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
+  return wave_sum(lane);
+}
+
+// kWaves partials (fp64) per chunk, one per wavefront.  The finalize pass adds a
+// bucket's partials in a fixed order.
+template <int GDT, bool NT, bool STAGED>
+__global__ __launch_bounds__(kBlock) void k_sqnorm(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
+                                                    double* __restrict__ partials, int32_t* status) {
+  const uint32_t tid = threadIdx.x;
+  if (status != nullptr && blockIdx.x == 0 && tid == 0) *status = 0;  // finalize ORs into it later on this stream
+  for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t ci) {
+    const double ws = sqnorm_chunk<GDT, NT>(en);
+    if ((tid & 63u) == 0) partials[(uint64_t)ci * kWaves + (tid >> 6)] = ws;
+  });
 }
 
 // ---- clip coefficient -----------------------------------------------------------
@@ -240,22 +282,24 @@ __device__ __forceinline__ float clip_coef(float norm, float c, int32_t& status)
   return 1.f;
 }
 
-// One wavefront per bucket: lanes take the bucket's partials in strides of 64 in
-// fp64, then a butterfly.  Same order on every run, so norms are reproducible.
+// One workgroup per bucket: threads take the bucket's partials in strides of 256
+// in fp64, lanes are combined by a butterfly, the four wavefronts through LDS in
+// index order.  Same order on every run, so norms are reproducible.
 __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ partials,
                                                       const uint32_t* __restrict__ bucket_chunk_off, uint32_t b0,
-                                                      uint32_t b1, const float* __restrict__ thresholds,
-                                                      float* __restrict__ norms, float* __restrict__ coefs,
-                                                      int32_t* status) {
-  const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t b = b0 + blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (b >= b1) return;
-  const uint32_t lo = bucket_chunk_off[b], hi = bucket_chunk_off[b + 1];
+                                                      const float* __restrict__ thresholds, float* __restrict__ norms,
+                                                      float* __restrict__ coefs, int32_t* status) {
+  __shared__ double s_w[kWaves];
+  const uint32_t b = b0 + blockIdx.x;
+  const uint64_t lo = (uint64_t)bucket_chunk_off[b] * kWaves, hi = (uint64_t)bucket_chunk_off[b + 1] * kWaves;
   double s = 0.0;
-  for (uint32_t i = lo + lane; i < hi; i += 64u) s += partials[i];
+  for (uint64_t i = lo + threadIdx.x; i < hi; i += kBlock) s += partials[i];
   s = wave_sum(s);
-  if (lane == 0) {
-    const float norm = (float)sqrt(s);
+  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+    const float norm = (float)sqrt(tot);
     norms[b] = norm;
     if (thresholds != nullptr) {
       int32_t st = 0;
@@ -285,49 +329,40 @@ __global__ __launch_bounds__(kBlock) void k_coefs(uint32_t b0, uint32_t b1, cons
 
 // G_b <- coef_b * G_b for clipped buckets (Alg. 1, the assignment under the if);
 // buckets with coef_b == 1 are not read at all.
-template <int GDT>
+template <int GDT, uint32_t U, bool NT, bool STAGED>
 __global__ __launch_bounds__(kBlock) void k_scale(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
                                                    const float* __restrict__ coefs) {
-  __shared__ Chunk s_tab[kSlice];
   typedef Grad<GDT> G;
   constexpr uint32_t gsize = sizeof(typename G::elem);
-  constexpr uint32_t U = 4;
-  const uint32_t w = blockIdx.x, Gn = gridDim.x, tid = threadIdx.x;
-  const uint32_t mine = my_chunk_count(n, w, Gn);
-  for (uint32_t first = 0; first < mine; first += kSlice) {
-    const uint32_t cnt = min(kSlice, mine - first);
-    stage_slice(s_tab, table, c0, w, Gn, first, cnt);
-    __syncthreads();
-    for (uint32_t e = 0; e < cnt; ++e) {
-      const float coef = coefs[s_tab[e].bucket];
-      if (coef == 1.f) continue;
-      const uint64_t ga = s_tab[e].g;
-      const uint32_t len = s_tab[e].len;
-      const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, false, 0, 0, 0);
-      const uint32_t nvec = (len - head) / 4u;
-      const uint32_t tail0 = head + nvec * 4u;
-      void* gbase = reinterpret_cast<void*>(ga);
-      void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
-      for (uint32_t base = 0; base < nvec; base += kBlock * U) {
-        const uint32_t j0 = base + tid;
-        if (base + kBlock * U <= nvec) {
-          f32x4 x[U];
+  const uint32_t tid = threadIdx.x;
+  for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t) {
+    const float coef = coefs[en.bucket];
+    if (coef == 1.f) return;
+    const uint64_t ga = en.g;
+    const uint32_t len = en.len;
+    const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, false, 0, 0, 0);
+    const uint32_t nvec = (len - head) / 4u;
+    const uint32_t tail0 = head + nvec * 4u;
+    void* gbase = reinterpret_cast<void*>(ga);
+    void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
+    for (uint32_t base = 0; base < nvec; base += kBlock * U) {
+      const uint32_t j0 = base + tid;
+      if (base + kBlock * U <= nvec) {
+        f32x4 x[U];
 #pragma unroll
-          for (uint32_t u = 0; u < U; ++u) x[u] = G::load4(gv, j0 + u * kBlock);
+        for (uint32_t u = 0; u < U; ++u) x[u] = G::template load4<NT>(gv, j0 + u * kBlock);
 #pragma unroll
-          for (uint32_t u = 0; u < U; ++u) G::store4(gv, j0 + u * kBlock, x[u] * coef);
-        } else {
-          for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t j = j0 + u * kBlock;
-            if (j < nvec) G::store4(gv, j, G::load4(gv, j) * coef);
-          }
+        for (uint32_t u = 0; u < U; ++u) G::template store4<NT>(gv, j0 + u * kBlock, x[u] * coef);
+      } else {
+        for (uint32_t u = 0; u < U; ++u) {
+          const uint32_t j = j0 + u * kBlock;
+          if (j < nvec) G::template store4<NT>(gv, j, G::template load4<NT>(gv, j) * coef);
         }
       }
-      for (uint32_t i = tid; i < head; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
-      for (uint32_t i = tail0 + tid; i < len; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
     }
-    __syncthreads();
-  }
+    for (uint32_t i = tid; i < head; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
+    for (uint32_t i = tail0 + tid; i < len; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
+  });
 }
 
 // ---- Adam -----------------------------------------------------------------------
@@ -355,87 +390,247 @@ __device__ __forceinline__ void adam4(f32x4 g, f32x4& p, f32x4& m, f32x4& v, con
   }
 }
 
-// The read-modify-write sweep.  FUSED: ghat = coef_b * g is formed in registers
-// (one fp32 multiply, so it equals what k_scale would have stored for fp32
-// gradients); WB: ghat, rounded to the gradient type, also replaces g.
-template <int GDT, bool FUSED, bool WB>
+// The read-modify-write sweep over one chunk.  coef != 1 only on the fused path:
+// ghat = coef_b * g is formed in registers (one fp32 multiply, so it equals what
+// k_scale would have stored for fp32 gradients); WB: ghat, rounded to the gradient
+// type, also replaces g.  p, m, v are touched once per sweep and always stream;
+// GNT says whether g streams too.
+template <int GDT, bool FUSED, bool WB, uint32_t U, bool GNT>
+__device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const AdamK& k) {
+  typedef Grad<GDT> G;
+  constexpr uint32_t gsize = sizeof(typename G::elem);
+  constexpr bool NT = true;
+  const uint32_t tid = threadIdx.x;
+  const uint64_t ga = en.g, pa = en.p, ma = en.m, va = en.v;
+  const uint32_t len = en.len;
+  const bool wb = WB && coef != 1.f;
+  const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, true, pa, ma, va);
+  const uint32_t nvec = (len - head) / 4u;
+  const uint32_t tail0 = head + nvec * 4u;
+  void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
+  f32x4* pv = reinterpret_cast<f32x4*>(pa + (uint64_t)head * 4u);
+  f32x4* mv = reinterpret_cast<f32x4*>(ma + (uint64_t)head * 4u);
+  f32x4* vv = reinterpret_cast<f32x4*>(va + (uint64_t)head * 4u);
+
+  for (uint32_t base = 0; base < nvec; base += kBlock * U) {
+    const uint32_t j0 = base + tid;
+    if (base + kBlock * U <= nvec) {
+      f32x4 g[U], p[U], m[U], v[U];
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) g[u] = G::template load4<GNT>(gv, j0 + u * kBlock);
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) p[u] = ldv<NT>(pv + j0 + u * kBlock);
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) m[u] = ldv<NT>(mv + j0 + u * kBlock);
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) v[u] = ldv<NT>(vv + j0 + u * kBlock);
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) {
+        if constexpr (FUSED) g[u] = g[u] * coef;
+        adam4(g[u], p[u], m[u], v[u], k);
+        const uint32_t j = j0 + u * kBlock;
+        stv<NT>(pv + j, p[u]), stv<NT>(mv + j, m[u]), stv<NT>(vv + j, v[u]);
+        if (wb) G::template store4<GNT>(gv, j, g[u]);
+      }
+    } else {
+      for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t j = j0 + u * kBlock;
+        if (j < nvec) {
+          f32x4 g = G::template load4<GNT>(gv, j), p = ldv<NT>(pv + j), m = ldv<NT>(mv + j), v = ldv<NT>(vv + j);
+          if constexpr (FUSED) g = g * coef;
+          adam4(g, p, m, v, k);
+          stv<NT>(pv + j, p), stv<NT>(mv + j, m), stv<NT>(vv + j, v);
+          if (wb) G::template store4<GNT>(gv, j, g);
+        }
+      }
+    }
+  }
+  // head and tail, element-wise
+  void* gbase = reinterpret_cast<void*>(ga);
+  float* p1 = reinterpret_cast<float*>(pa);
+  float* m1 = reinterpret_cast<float*>(ma);
+  float* v1 = reinterpret_cast<float*>(va);
+  for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
+    const uint32_t i = r < head ? r : tail0 + (r - head);
+    float g = G::load1(gbase, i), p = p1[i], m = m1[i], v = v1[i];
+    if constexpr (FUSED) g = g * coef;
+    adam1(g, p, m, v, k);
+    p1[i] = p, m1[i] = m, v1[i] = v;
+    if (wb) G::store1(gbase, i, g);
+  }
+}
+
+template <int GDT, bool FUSED, bool WB, uint32_t U, bool GNT, bool STAGED>
 __global__ __launch_bounds__(kBlock) void k_adam(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
                                                   const float* __restrict__ coefs, const int32_t* skip_status,
                                                   const AdamK k) {
-  __shared__ Chunk s_tab[kSlice];
-  typedef Grad<GDT> G;
-  constexpr uint32_t gsize = sizeof(typename G::elem);
-  constexpr uint32_t U = 4;
   if (skip_status != nullptr && (*skip_status & BCA_STATUS_NONFINITE)) return;
-  const uint32_t w = blockIdx.x, Gn = gridDim.x, tid = threadIdx.x;
-  const uint32_t mine = my_chunk_count(n, w, Gn);
-  for (uint32_t first = 0; first < mine; first += kSlice) {
-    const uint32_t cnt = min(kSlice, mine - first);
-    stage_slice(s_tab, table, c0, w, Gn, first, cnt);
-    __syncthreads();
-    for (uint32_t e = 0; e < cnt; ++e) {
-      const uint64_t ga = s_tab[e].g, pa = s_tab[e].p, ma = s_tab[e].m, va = s_tab[e].v;
-      const uint32_t len = s_tab[e].len;
-      float coef = 1.f;
-      if constexpr (FUSED) coef = coefs[s_tab[e].bucket];
-      const bool wb = WB && coef != 1.f;
-      const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, true, pa, ma, va);
-      const uint32_t nvec = (len - head) / 4u;
-      const uint32_t tail0 = head + nvec * 4u;
-      void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
-      f32x4* pv = reinterpret_cast<f32x4*>(pa + (uint64_t)head * 4u);
-      f32x4* mv = reinterpret_cast<f32x4*>(ma + (uint64_t)head * 4u);
-      f32x4* vv = reinterpret_cast<f32x4*>(va + (uint64_t)head * 4u);
+  for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t) {
+    float coef = 1.f;
+    if constexpr (FUSED) coef = coefs[en.bucket];
+    adam_chunk<GDT, FUSED, WB, U, GNT>(en, coef, k);
+  });
+}
 
-      for (uint32_t base = 0; base < nvec; base += kBlock * U) {
-        const uint32_t j0 = base + tid;
-        if (base + kBlock * U <= nvec) {
-          f32x4 g[U], p[U], m[U], v[U];
-#pragma unroll
-          for (uint32_t u = 0; u < U; ++u) g[u] = G::load4(gv, j0 + u * kBlock);
-#pragma unroll
-          for (uint32_t u = 0; u < U; ++u) p[u] = pv[j0 + u * kBlock];
-#pragma unroll
-          for (uint32_t u = 0; u < U; ++u) m[u] = mv[j0 + u * kBlock];
-#pragma unroll
-          for (uint32_t u = 0; u < U; ++u) v[u] = vv[j0 + u * kBlock];
-#pragma unroll
-          for (uint32_t u = 0; u < U; ++u) {
-            if constexpr (FUSED) g[u] = g[u] * coef;
-            adam4(g[u], p[u], m[u], v[u], k);
-            const uint32_t j = j0 + u * kBlock;
-            pv[j] = p[u], mv[j] = m[u], vv[j] = v[u];
-            if (wb) G::store4(gv, j, g[u]);
-          }
-        } else {
-          for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t j = j0 + u * kBlock;
-            if (j < nvec) {
-              f32x4 g = G::load4(gv, j), p = pv[j], m = mv[j], v = vv[j];
-              if constexpr (FUSED) g = g * coef;
-              adam4(g, p, m, v, k);
-              pv[j] = p, mv[j] = m, vv[j] = v;
-              if (wb) G::store4(gv, j, g);
-            }
-          }
+// ---- the whole fused step in one launch ----------------------------------------------
+//
+// Work items (one per workgroup) are listed by the host in an order that
+// pipelines bucket groups:  N(g0) N(g1) A(g0) N(g2) A(g1) ... A(last), where N(g)
+// are the squared-norm chunks of group g's buckets and A(g) the Adam chunks.  A
+// group's gradients are read by N(g), stay in the Infinity Cache (everything
+// else streams past it with non-temporal accesses), and are read again by A(g)
+// one group later, so HBM sees the gradients once.
+//
+// Items are handed out through a ticket counter, so an item is only ever held by
+// a running workgroup and items are started in list order.  An Adam item needs
+// its bucket's coefficient; it waits on that bucket's ready word, which is set
+// by whichever squared-norm workgroup of the bucket finishes last (it adds the
+// bucket's partials in the fixed order of k_finalize, so results do not depend
+// on who that is).  All squared-norm items of a bucket precede its Adam items in
+// the list, hence are held by running workgroups that wait for nothing: every
+// wait ends.  The wait is bounded all the same; on expiry the item is skipped and
+// BCA_STATUS_TIMEOUT is reported.
+
+constexpr uint32_t kSpinLimit = 1u << 18;  // polls of a ready word before an Adam item gives up (about a second)
+
+// Resets the per-call state: takes a new epoch, clears the ticket, the arrival
+// counters and the caller's status word (k_step only ORs into it).
+__global__ __launch_bounds__(kBlock) void k_prepare(StepState st, uint32_t n_buckets, int32_t* status) {
+  for (uint32_t b = threadIdx.x; b < n_buckets; b += kBlock) st.arrived[b] = 0u;
+  if (threadIdx.x == 0) {
+    for (uint32_t y = 0; y < 8u; ++y) st.ctl[kCtlTicket + 32u * y] = 0u;
+    st.ctl[kCtlAbort] = 0u;
+    st.ctl[kCtlEpoch] = st.ctl[kCtlEpoch] + 1u;
+    *status = 0;
+  }
+}
+
+template <int GDT, bool WB, uint32_t U, bool TICKETS>
+__global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
+                                                  const float* __restrict__ thresholds, float* __restrict__ norms,
+                                                  float* __restrict__ coefs, int32_t* status, const AdamK k) {
+  __shared__ uint32_t s_item;
+  __shared__ uint32_t s_flag;
+  __shared__ float s_coef;
+  __shared__ double s_w[kWaves];
+  const uint32_t tid = threadIdx.x;
+  uint32_t ticket;
+  if constexpr (TICKETS) {
+    // Eight ticket counters, one per XCD: item 8 t + y is the t-th item of list y.  A
+    // workgroup draws from its own XCD's list and moves on to the next list when that
+    // one is used up, so every list is started strictly in order and every item is
+    // taken by exactly one of the n_work workgroups.
+    if (tid == 0) {
+      const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;  // HW_REG_XCC_ID[3:0]
+      uint32_t it = 0xffffffffu;
+      for (uint32_t a = 0; a < 8u; ++a) {
+        const uint32_t y = (xcc + a) & 7u;
+        const uint32_t t = atomicAdd(&st.ctl[kCtlTicket + 32u * y], 1u);
+        if ((uint64_t)t * 8u + y < n_work) {
+          it = t * 8u + y;
+          break;
         }
       }
-      // head and tail, element-wise
-      void* gbase = reinterpret_cast<void*>(ga);
-      float* p1 = reinterpret_cast<float*>(pa);
-      float* m1 = reinterpret_cast<float*>(ma);
-      float* v1 = reinterpret_cast<float*>(va);
-      for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
-        const uint32_t i = r < head ? r : tail0 + (r - head);
-        float g = G::load1(gbase, i), p = p1[i], m = m1[i], v = v1[i];
-        if constexpr (FUSED) g = g * coef;
-        adam1(g, p, m, v, k);
-        p1[i] = p, m1[i] = m, v1[i] = v;
-        if (wb) G::store1(gbase, i, g);
+      s_item = it;
+    }
+    __syncthreads();
+    ticket = s_item;
+  } else {
+    ticket = blockIdx.x;
+  }
+  if (ticket >= n_work) return;
+  const uint32_t epoch = st.ctl[kCtlEpoch];  // written by k_prepare, constant during this launch
+  const uint32_t item = work[ticket];
+  const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
+
+  if (kind == kItemAdam) {
+    const Entry en = read_entry(&st.apply_tab[idx]);
+    if (tid == 0) {
+      // wait for the bucket's ready word: (epoch << 32) | bits of the coefficient
+      unsigned long long r = 0;
+      uint32_t polls = 0;
+      for (;;) {
+        r = __hip_atomic_load(&st.ready[en.bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(r >> 32) == epoch || ++polls > kSpinLimit) break;
+        // once one wait has expired every other waiter gives up at its next look
+        if ((polls & 63u) == 0 &&
+            __hip_atomic_load(&st.ctl[kCtlAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
+          break;
+        __builtin_amdgcn_s_sleep(8);
+      }
+      const bool ok = (uint32_t)(r >> 32) == epoch;
+      s_flag = ok ? 1u : 0u;
+      s_coef = __uint_as_float((uint32_t)r);
+      if (!ok) {
+        __hip_atomic_store(&st.ctl[kCtlAbort], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        atomicOr(status, BCA_STATUS_TIMEOUT);
       }
     }
     __syncthreads();
+    if (s_flag) adam_chunk<GDT, true, WB, U, false>(en, s_coef, k);
+    return;
   }
+
+  // squared-norm item, or the stand-in for a bucket without elements
+  uint32_t b = idx;
+  if (kind == kItemNorm) {
+    const Entry en = read_entry(&st.norm_tab[idx]);
+    b = en.bucket;
+    const double ws = sqnorm_chunk<GDT, false>(en);
+    if ((tid & 63u) == 0)
+      __hip_atomic_store(&st.partials[(uint64_t)idx * kWaves + (tid >> 6)], ws, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    // The partial was stored write-through at device scope; once the store has
+    // completed (the workgroup-scope fence waits for it) it is visible to every
+    // device-scope load, so the arrival may be counted.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t total = st.norm_bucket_off[b + 1] - st.norm_bucket_off[b];
+      const uint32_t old = atomicAdd(&st.arrived[b], 1u);
+      s_flag = (old + 1u == total) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_flag) return;  // the last to arrive goes on; its loads below are device-scope and bypass L2
+  }
+
+  // add the bucket's partials in the fixed order of k_finalize
+  const uint64_t lo = (uint64_t)st.norm_bucket_off[b] * kWaves, hi = (uint64_t)st.norm_bucket_off[b + 1] * kWaves;
+  double s = 0.0;
+  for (uint64_t i = lo + tid; i < hi; i += kBlock)
+    s += __hip_atomic_load(&st.partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  s = wave_sum(s);
+  if ((tid & 63u) == 0) s_w[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+    const float norm = (float)sqrt(tot);
+    int32_t bst = 0;
+    const float coef = clip_coef(norm, thresholds[b], bst);
+    norms[b] = norm;
+    coefs[b] = coef;
+    if (bst) atomicOr(status, bst);
+    const unsigned long long word = ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(coef);
+    __hip_atomic_store(&st.ready[b], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// Compile-time variants are picked from run-time switches through these helpers.
+template <typename F>
+void pick2(bool a, bool b, F f) {
+  if (a) {
+    if (b) f(std::true_type{}, std::true_type{});
+    else f(std::true_type{}, std::false_type{});
+  } else {
+    if (b) f(std::false_type{}, std::true_type{});
+    else f(std::false_type{}, std::false_type{});
+  }
+}
+template <typename F>
+void pick_unroll(uint32_t u, F f) {
+  if (u == 1) f(std::integral_constant<uint32_t, 1>{});
+  else if (u == 2) f(std::integral_constant<uint32_t, 2>{});
+  else f(std::integral_constant<uint32_t, 4>{});
 }
 
 }  // namespace
@@ -443,12 +638,40 @@ __global__ __launch_bounds__(kBlock) void k_adam(const Chunk* __restrict__ table
 // ---- launchers --------------------------------------------------------------------
 
 hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, double* partials, int32_t* status,
-                         uint32_t grid, hipStream_t stream) {
+                         const Launch& L, hipStream_t stream) {
   if (n == 0 && status == nullptr) return hipSuccess;  // with a status word the launch still has to clear it
-  if (gdt == BCA_GRAD_F32)
-    hipLaunchKernelGGL(k_sqnorm<BCA_GRAD_F32>, dim3(grid), dim3(kBlock), 0, stream, table, c0, n, partials, status);
-  else
-    hipLaunchKernelGGL(k_sqnorm<BCA_GRAD_F16>, dim3(grid), dim3(kBlock), 0, stream, table, c0, n, partials, status);
+  pick2(!L.g_keep, L.staged, [&](auto nt, auto st) {
+    constexpr bool NT = decltype(nt)::value, ST = decltype(st)::value;
+    if (gdt == BCA_GRAD_F32)
+      hipLaunchKernelGGL((k_sqnorm<BCA_GRAD_F32, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n,
+                         partials, status);
+    else
+      hipLaunchKernelGGL((k_sqnorm<BCA_GRAD_F16, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n,
+                         partials, status);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
+                       const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
+                       const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream) {
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(kBlock), 0, stream, st, n_buckets, status);
+  hipError_t e = hipGetLastError();
+  if (between != nullptr) (void)hipEventRecord(between, stream);
+  if (e != hipSuccess || n_work == 0) return e;
+  pick_unroll(unroll, [&](auto uu) {
+    constexpr uint32_t U = decltype(uu)::value;
+    pick2(gdt == BCA_GRAD_F32, write_back, [&](auto f32, auto wb) {
+      constexpr int GDT = decltype(f32)::value ? BCA_GRAD_F32 : BCA_GRAD_F16;
+      constexpr bool WB = decltype(wb)::value;
+      if (tickets)
+        hipLaunchKernelGGL((k_step<GDT, WB, U, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                           thresholds, norms, coefs, status, k);
+      else
+        hipLaunchKernelGGL((k_step<GDT, WB, U, false>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                           thresholds, norms, coefs, status, k);
+    });
+  });
   return hipGetLastError();
 }
 
@@ -456,8 +679,7 @@ hipError_t launch_finalize(const double* partials, const uint32_t* bucket_chunk_
                            const float* thresholds, float* norms, float* coefs, int32_t* status,
                            hipStream_t stream) {
   if (b1 <= b0) return hipSuccess;
-  const uint32_t grid = (b1 - b0 + kWaves - 1) / kWaves;
-  hipLaunchKernelGGL(k_finalize, dim3(grid), dim3(kBlock), 0, stream, partials, bucket_chunk_off, b0, b1, thresholds,
+  hipLaunchKernelGGL(k_finalize, dim3(b1 - b0), dim3(kBlock), 0, stream, partials, bucket_chunk_off, b0, thresholds,
                      norms, coefs, status);
   return hipGetLastError();
 }
@@ -468,36 +690,49 @@ hipError_t launch_coefs(uint32_t b0, uint32_t b1, const float* thresholds, const
   return hipGetLastError();
 }
 
-hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, uint32_t grid,
+hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, const Launch& L,
                         hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  if (gdt == BCA_GRAD_F32)
-    hipLaunchKernelGGL(k_scale<BCA_GRAD_F32>, dim3(grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
-  else
-    hipLaunchKernelGGL(k_scale<BCA_GRAD_F16>, dim3(grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
+  // The scaled gradients are about to be read again (by the all-reduce or by Adam): plain stores.
+  pick_unroll(L.unroll, [&](auto uu) {
+    constexpr uint32_t U = decltype(uu)::value;
+    pick2(gdt == BCA_GRAD_F32, L.staged, [&](auto f32, auto st) {
+      constexpr int GDT = decltype(f32)::value ? BCA_GRAD_F32 : BCA_GRAD_F16;
+      constexpr bool ST = decltype(st)::value;
+      hipLaunchKernelGGL((k_scale<GDT, U, false, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
+    });
+  });
   return hipGetLastError();
 }
 
-template <int GDT>
-static hipError_t launch_adam_t(const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
-                                const int32_t* skip_status, const AdamK& k, uint32_t grid, hipStream_t stream) {
+template <int GDT, uint32_t U, bool GNT, bool ST>
+static void launch_adam_t(const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
+                          const int32_t* skip_status, const AdamK& k, uint32_t grid, hipStream_t stream) {
   if (coefs == nullptr)
-    hipLaunchKernelGGL((k_adam<GDT, false, false>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n, coefs,
-                       skip_status, k);
+    hipLaunchKernelGGL((k_adam<GDT, false, false, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+                       coefs, skip_status, k);
   else if (!write_back)
-    hipLaunchKernelGGL((k_adam<GDT, true, false>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n, coefs,
-                       skip_status, k);
+    hipLaunchKernelGGL((k_adam<GDT, true, false, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+                       coefs, skip_status, k);
   else
-    hipLaunchKernelGGL((k_adam<GDT, true, true>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n, coefs,
-                       skip_status, k);
-  return hipGetLastError();
+    hipLaunchKernelGGL((k_adam<GDT, true, true, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+                       coefs, skip_status, k);
 }
 
 hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
-                       const int32_t* skip_status, const AdamK& k, uint32_t grid, hipStream_t stream) {
+                       const int32_t* skip_status, const AdamK& k, const Launch& L, hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  return gdt == BCA_GRAD_F32 ? launch_adam_t<BCA_GRAD_F32>(table, c0, n, coefs, write_back, skip_status, k, grid, stream)
-                             : launch_adam_t<BCA_GRAD_F16>(table, c0, n, coefs, write_back, skip_status, k, grid, stream);
+  pick_unroll(L.unroll, [&](auto uu) {
+    constexpr uint32_t U = decltype(uu)::value;
+    pick2(!L.g_keep, L.staged, [&](auto gnt, auto st) {
+      constexpr bool GNT = decltype(gnt)::value, ST = decltype(st)::value;
+      if (gdt == BCA_GRAD_F32)
+        launch_adam_t<BCA_GRAD_F32, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
+      else
+        launch_adam_t<BCA_GRAD_F16, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
+    });
+  });
+  return hipGetLastError();
 }
 
 }  // namespace bca

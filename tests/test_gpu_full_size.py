@@ -1,0 +1,99 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (library defaults): BERT-Base (25 MiB buckets),
+BERT-Large (50 MiB buckets, warm state), BERT-Large with fp16 gradients (1 MiB
+buckets) and 20 consecutive steps of BERT-Large with 4 MiB buckets.  The oracle
+finishes one BERT-Large step in a few seconds, so every element is compared."""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2402_02447_amd as B
+import workloads as W
+from gpu_util import Device, bits_equal, check_norms, check_state, f64, hp_kwargs, hyper, to_host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def full_fused(w, flags=0):
+    lay = w.layout
+    t0 = time.time()
+    g, p, m, v = w.grads(), w.params(), w.exp_avg(), w.exp_avg_sq()
+    print(f"[{w.name}] generated {lay.n_elements} elements in {time.time() - t0:.1f}s", flush=True)
+    dev = Device(lay, g, p, m, v)
+    assert dev.plan.n_groups >= 1
+    dthr = dev.thresholds(w.thresholds)
+    dev.plan.bucket_clip_adam(dthr, hyper(w.hyper), w.first_step, flags, dev.norms, dev.coefs, dev.status)
+    dev.sync()
+    t0 = time.time()
+    og = [x.copy() for x in g] if flags & B.BCA_WRITE_BACK_GRADS else g
+    op, om, ov = f64(p), f64(m), f64(v)
+    onorm, ocoef, ost = oracle.bucket_clip_adam(lay, og, op, om, ov, w.thresholds, step=w.first_step,
+                                                write_back=bool(flags & B.BCA_WRITE_BACK_GRADS), **hp_kwargs(w.hyper))
+    print(f"[{w.name}] oracle step {time.time() - t0:.1f}s", flush=True)
+    rel = check_norms(dev.norms.cpu().numpy(), onorm)
+    gcoef = dev.coefs.cpu().numpy()
+    assert np.allclose(gcoef, ocoef, rtol=2e-5, atol=0)
+    assert int(dev.status.item()) == ost == 0
+    rp = check_state("p", to_host(dev.p), op)
+    rm = check_state("m", to_host(dev.m), om)
+    rv = check_state("v", to_host(dev.v), ov, strict_rel=True)
+    print(f"[{w.name}] norm rel {rel:.2e}; p {rp}; m {rm}; v {rv}; clipped {int((ocoef < 1).sum())}/{lay.n_buckets}",
+          flush=True)
+    if not flags & B.BCA_WRITE_BACK_GRADS:
+        assert bits_equal(to_host(dev.g), g)
+    dev.close()
+    return ocoef
+
+
+def test_bert_base_25mib_full_size():
+    coefs = full_fused(W.config_bert_base())
+    assert (coefs < 1).all()            # norm ~ 2.56 > 1: every bucket clips
+
+
+def test_bert_large_50mib_full_size():
+    w = W.config_bert_large()
+    coefs = full_fused(w)
+    assert (coefs < 1).all() and coefs[w.hot_buckets].max() < 0.01 < coefs.max()
+
+
+def test_bert_large_fp16_1mib_full_size():
+    w = W.config_bert_large_fp16()
+    coefs = full_fused(w)
+    assert (coefs < 1).mean() > 0.9     # threshold 1/sqrt(B): nearly every bucket clips
+
+
+def test_bert_large_4mib_20_steps_full_size():
+    w = W.config_bert_large_multistep()
+    lay = w.layout
+    p, m, v = w.params(), w.exp_avg(), w.exp_avg_sq()
+    dev = Device(lay, w.grads(0), p, m, v)
+    dthr = dev.thresholds(w.thresholds)
+    op, om, ov = f64(p), f64(m), f64(v)
+    del p, m, v
+    worst = {"p": 0.0, "m": 0.0, "v": 0.0}
+    clipped = 0
+    for k in range(w.n_steps):
+        t0 = time.time()
+        g = w.grads(k)
+        dev.set_grads(g)
+        step = w.first_step + k
+        dev.plan.bucket_clip_adam(dthr, hyper(w.hyper), step, 0, dev.norms, dev.coefs, dev.status)
+        dev.sync()
+        onorm, ocoef, ost = oracle.bucket_clip_adam(lay, g, op, om, ov, w.thresholds, step=step, **hp_kwargs(w.hyper))
+        assert int(dev.status.item()) == ost == 0
+        check_norms(dev.norms.cpu().numpy(), onorm)
+        clipped += int((ocoef < 1).sum())
+        rp = check_state(f"p@{step}", to_host(dev.p), op)
+        rm = check_state(f"m@{step}", to_host(dev.m), om)
+        rv = check_state(f"v@{step}", to_host(dev.v), ov, strict_rel=True)
+        worst["p"] = max(worst["p"], rp["max_rel_big"])
+        worst["m"] = max(worst["m"], rm["max_abs_small"])
+        worst["v"] = max(worst["v"], rv["max_rel_all"])
+        print(f"[20 steps] step {step}: p rel {rp['max_rel_big']:.2e} abs {rp['max_abs_small']:.2e}; "
+              f"m abs {rm['max_abs_small']:.2e}; v rel {rv['max_rel_all']:.2e}; {time.time() - t0:.1f}s", flush=True)
+    frac = clipped / (w.n_steps * lay.n_buckets)
+    assert 0.4 < frac < 0.6, frac        # about half of the buckets clip
+    print("[20 steps] worst", worst, flush=True)
+    dev.close()

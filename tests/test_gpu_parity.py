@@ -128,7 +128,7 @@ def test_tiny_fused_write_back_and_other_chunk_sizes():
     p, m, v = state_of(w)
     for chunk in (1024, 4096, 65536):
         run_fused(w.layout, w.grads(), p, m, v, w.thresholds, w.hyper, w.first_step, B.BCA_WRITE_BACK_GRADS,
-                  chunk_elems=chunk)
+                  chunk_norm=chunk, chunk_apply=chunk)
 
 
 def test_norms_closed_form_on_device():
@@ -190,8 +190,15 @@ def test_adversarial_layouts_fused_and_unfused(name, dtype):
     for flags in (0, B.BCA_WRITE_BACK_GRADS):
         run_fused(lay, g, p, m, v, thr, hp, 3, flags, offsets=offsets)
     run_unfused(lay, g, p, m, v, thr, hp, 3, offsets=offsets)
-    if dtype == "f32":
-        run_fused(lay, g, p, m, v, thr, hp, 3, 0, offsets=offsets, chunk_elems=1024, grid_norm=3, grid_apply=5)
+    # other launch shapes: tiny persistent grids, LDS-staged table, bucket groups, other unrolls
+    run_fused(lay, g, p, m, v, thr, hp, 3, 0, offsets=offsets, chunk_norm=1024, chunk_apply=1024, grid_norm=3,
+              grid_apply=5, unroll_apply=1)
+    run_fused(lay, g, p, m, v, thr, hp, 3, B.BCA_WRITE_BACK_GRADS, offsets=offsets, chunk_norm=2048, chunk_apply=2048,
+              grid_norm=2, grid_apply=3, unroll_apply=2, group_bytes=20_000,
+              tune_flags=B.BCA_TUNE_MULTI_LAUNCH | B.BCA_TUNE_STAGE_TABLE_LDS)
+    run_fused(lay, g, p, m, v, thr, hp, 3, 0, offsets=offsets, group_bytes=20_000, tune_flags=B.BCA_TUNE_MULTI_LAUNCH)
+    run_fused(lay, g, p, m, v, thr, hp, 3, B.BCA_WRITE_BACK_GRADS, offsets=offsets, group_bytes=20_000, chunk_norm=4096,
+              chunk_apply=2048)
 
 
 def test_empty_bucket_range_is_a_noop():
@@ -273,8 +280,19 @@ def test_fused_equals_unfused_bitwise_for_fp32_and_runs_are_reproducible():
     norms = oracle.bucket_norms(w.layout, g)
     thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
     results = []
-    for mode in ("fused", "fused", "unfused", "fused_other_grid"):
-        tuning = dict(grid_norm=7, grid_apply=13, chunk_elems=16384) if mode == "fused_other_grid" else {}
+    ML = B.BCA_TUNE_MULTI_LAUNCH
+    for mode in ("fused", "fused", "unfused", "one_group", "multi", "multi_other_grid", "multi_staged", "multi_one_group"):
+        tuning = {}
+        if mode == "one_group":
+            tuning = dict(group_bytes=1 << 40)
+        elif mode == "multi":
+            tuning = dict(tune_flags=ML, group_bytes=300_000)
+        elif mode == "multi_other_grid":    # same chunk cuts, other workgroup assignment and unroll
+            tuning = dict(tune_flags=ML, grid_norm=7, grid_apply=13, unroll_apply=2, chunk_apply=4096)
+        elif mode == "multi_staged":
+            tuning = dict(grid_norm=16, grid_apply=32, tune_flags=ML | B.BCA_TUNE_STAGE_TABLE_LDS)
+        elif mode == "multi_one_group":
+            tuning = dict(tune_flags=ML, group_bytes=1 << 40)
         dev = Device(w.layout, g, p, m, v, **tuning)
         dthr = dev.thresholds(thr)
         if mode.startswith("fused"):

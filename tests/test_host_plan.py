@@ -27,37 +27,38 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert L.bca_version() >= 1
 
 
-def host_plan(layout, **kw):
-    return B.Plan.from_layout(layout, device=-1, **kw)
+def host_plan(layout, grad_dtype=0, **kw):
+    return B.Plan.from_layout(layout, grad_dtype, device=-1, **kw)
 
 
+@pytest.mark.parametrize("table", [B.BCA_TABLE_NORM, B.BCA_TABLE_APPLY])
 @pytest.mark.parametrize("chunk", [1024, 4096, 16384])
-def test_chunk_table_partitions_the_layout(chunk):
+def test_chunk_table_partitions_the_layout(chunk, table):
     numels = W.scaled_bert_numels(64, 2, 256, vocab=1000, max_pos=32) + [0, 7, 1]
     lay = W.layout_flat_split(numels, 50_000)
-    p = host_plan(lay, chunk_elems=chunk)
+    p = host_plan(lay, chunk_norm=chunk, chunk_apply=chunk)
     assert p.n_buckets == lay.n_buckets
     seen = [np.zeros(n, np.int8) for n in numels]
     prev_bucket = 0
     per_bucket = np.zeros(lay.n_buckets, np.int64)
-    for i in range(p.n_chunks):
-        t, beg, ln, b = p.chunk_info(i)
+    for i in range(p.n_chunks(table)):
+        t, beg, ln, b = p.chunk_info(i, table)
         assert 0 < ln <= chunk
         assert b >= prev_bucket                        # bucket-major order
         prev_bucket = b
         assert beg // chunk == (beg + ln - 1) // chunk  # never straddles a multiple of the chunk size
         seen[t][beg:beg + ln] += 1
         per_bucket[b] += ln
-        f, n = p.bucket_chunks(b)
+        f, n = p.bucket_chunks(b, table)
         assert f <= i < f + n
     assert all((s == 1).all() for s in seen)
     assert np.array_equal(per_bucket, lay.bucket_numel())
     # chunks stay inside their segment's bucket: elements of bucket b per the layout
     for b in range(lay.n_buckets):
-        f, n = p.bucket_chunks(b)
+        f, n = p.bucket_chunks(b, table)
         cover = {}
         for i in range(f, f + n):
-            t, beg, ln, bb = p.chunk_info(i)
+            t, beg, ln, bb = p.chunk_info(i, table)
             assert bb == b
             cover.setdefault(t, []).append((beg, ln))
         want = {}
@@ -70,11 +71,22 @@ def test_chunk_table_partitions_the_layout(chunk):
             assert min(bg for bg, _ in cover[t]) == min(bg for bg, _ in want[t])
 
 
-def test_chunk_counts_of_the_bert_large_configs():
-    for make, lo, hi in [(W.config_bert_large, 20_455, 21_300), (W.config_bert_large_fp16, 20_455, 23_500)]:
+def test_chunk_counts_and_groups_of_the_bert_large_configs():
+    N = 335_141_888
+    for make in (W.config_bert_large, W.config_bert_large_fp16):
         w = make()
         p = host_plan(w.layout)
-        assert lo <= p.n_chunks <= hi           # ceil(N / 16384) = 20 456 plus cuts at tensor / bucket edges
+        # default cuts: 65 536 elements for the norm pass, 1 024 for the read-write passes
+        assert -(-N // 65536) <= p.n_chunks(B.BCA_TABLE_NORM) <= -(-N // 65536) + 2 * w.layout.n_segments
+        assert -(-N // 1024) <= p.n_chunks(B.BCA_TABLE_APPLY) <= -(-N // 1024) + 2 * w.layout.n_segments
+    w = W.config_bert_large()
+    assert host_plan(w.layout).n_groups == 26                          # default 8 Mi elements: one 50 MiB bucket per group
+    assert host_plan(w.layout, group_bytes=110 << 20).n_groups == 13   # two per group
+    assert host_plan(W.config_bert_large_multistep().layout).n_groups == 40    # 4 MiB buckets: eight per group
+    assert host_plan(W.config_bert_large_fp16().layout, grad_dtype=B.BCA_GRAD_F16).n_groups == 40
+    assert host_plan(w.layout, group_bytes=160 << 20).n_groups == 9    # three per group
+    assert host_plan(w.layout, group_bytes=1).n_groups == w.layout.n_buckets   # never less than one bucket per group
+    assert host_plan(w.layout, group_bytes=1 << 40).n_groups == 1
 
 
 def _raw_create(numel, off, segs, gdt=0, device=-1, tuning=None):
@@ -113,9 +125,10 @@ def test_layout_errors_are_reported_and_nothing_is_created():
     assert rc == -2
     rc, msg = _raw_create([10], [0, 1], [(0, 0, 10)], gdt=5)
     assert rc == -7
-    t = binding._Tuning(1000, 0, 0, 0)                                         # chunk size not a multiple of 1024
-    rc, msg = _raw_create([10], [0, 1], [(0, 0, 10)], tuning=C.byref(t))
-    assert rc == -3
+    for bad in (binding._Tuning(1000, 0, 0, 0, 0, 0, 0), binding._Tuning(0, 1000, 0, 0, 0, 0, 0),
+                binding._Tuning(0, 0, 0, 0, 3, 0, 0), binding._Tuning(0, 0, 0, 0, 0, 8, 0)):
+        rc, msg = _raw_create([10], [0, 1], [(0, 0, 10)], tuning=C.byref(bad))   # chunk not a multiple of 1024, ...
+        assert rc == -3
     # empty buckets, empty segments and empty tensors are legal
     assert _raw_create([10, 0], [0, 0, 3, 3], [(0, 0, 4), (1, 0, 0), (0, 4, 6)])[0] == 0
 
