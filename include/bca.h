@@ -183,6 +183,12 @@ int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, con
 int bca_plan_profile(bca_plan* plan, uint32_t max_calls);
 int bca_plan_profile_read(bca_plan* plan, double* ms /*HOST [3]*/, uint32_t* n_calls /*HOST*/);
 
+/* Plain copy of nbytes from src to dst (both DEVICE, 16-byte aligned, not
+ * overlapping) on the current device.  Not part of the method: a kernel with
+ * exactly known HBM traffic (nbytes read, nbytes written) against which hardware
+ * counter readings are calibrated. */
+int bca_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream);
+
 /* Message of the calling thread's last error; valid until its next call. */
 const char* bca_last_error(void);
 

@@ -28,7 +28,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
 EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_groups",
            "bca_plan_num_chunks",
            "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "adam_step",
-           "bucket_clip_adam", "bca_plan_profile", "bca_plan_profile_read", "bca_last_error", "bca_version"]
+           "bucket_clip_adam", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error", "bca_version"]
 
 
 class BcaError(RuntimeError):
@@ -108,6 +108,7 @@ def load_library():
     L.bucket_clip_adam.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp]
     L.bca_plan_profile.argtypes = [vp, u32]
     L.bca_plan_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]
+    L.bca_copy_bytes.argtypes = [vp, vp, u64, vp]
     L.bca_last_error.restype = C.c_char_p
     L.bca_version.restype = i32
     for name in EXPORTS:
@@ -135,6 +136,11 @@ def _stream(s) -> Optional[int]:
     if hasattr(s, "cuda_stream"):
         return int(s.cuda_stream) or None
     return int(s) or None
+
+
+def copy_bytes(dst, src, nbytes: int, stream=None) -> None:
+    """Plain device copy with exactly known traffic (counter calibration)."""
+    _check(load_library().bca_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
 def alg1_thresholds(c: float, n_buckets: int) -> np.ndarray:

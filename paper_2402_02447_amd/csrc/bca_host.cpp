@@ -494,6 +494,14 @@ int bca_plan_profile_read(bca_plan* p, double* ms, uint32_t* n_calls) {
   return BCA_OK;
 }
 
+int bca_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream) {
+  if (nbytes && (!dst || !src)) return fail(BCA_ERR_NULL, "NULL buffer");
+  if (((uintptr_t)dst | (uintptr_t)src) & 15u) return fail(BCA_ERR_ALIGN, "buffers must be 16-byte aligned");
+  hipError_t e = launch_copy(dst, src, nbytes, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "launching the copy kernel");
+  return BCA_OK;
+}
+
 int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   if (int rc = check_range(p, b0, b1)) return rc;

@@ -111,6 +111,8 @@ hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const u
                        const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
                        const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream);
 
+hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
+
 void set_error(const std::string& msg);
 
 }  // namespace bca

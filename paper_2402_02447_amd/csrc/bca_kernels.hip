@@ -26,6 +26,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "bca_internal.h"
@@ -615,6 +616,18 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
   }
 }
 
+// Plain device-to-device copy (16-byte pieces, then single bytes).  It exists so
+// that hardware counters can be calibrated against a kernel whose HBM traffic is
+// known exactly: nbytes read, nbytes written.
+__global__ __launch_bounds__(kBlock) void k_copy(uint8_t* __restrict__ dst, const uint8_t* __restrict__ src,
+                                                  uint64_t nbytes) {
+  const uint64_t nvec = nbytes / 16u;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride)
+    reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
+  for (uint64_t i = nvec * 16u + (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < nbytes; i += stride) dst[i] = src[i];
+}
+
 // Compile-time variants are picked from run-time switches through these helpers.
 template <typename F>
 void pick2(bool a, bool b, F f) {
@@ -649,6 +662,14 @@ hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, d
       hipLaunchKernelGGL((k_sqnorm<BCA_GRAD_F16, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n,
                          partials, status);
   });
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream) {
+  if (nbytes == 0) return hipSuccess;
+  const uint64_t want = (nbytes / 16u + kBlock - 1) / kBlock;
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(want, 1), 1u << 20);
+  hipLaunchKernelGGL(k_copy, dim3(grid), dim3(kBlock), 0, stream, (uint8_t*)dst, (const uint8_t*)src, nbytes);
   return hipGetLastError();
 }
 
