@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="BASELINE.json config number")
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="benchmark configuration: 2 BERT-Base 25 MiB, 3 BERT-Large 50 MiB, 4 fp16 1 MiB, 5 4 MiB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-norm", type=int, default=0)
     ap.add_argument("--chunk-apply", type=int, default=0)

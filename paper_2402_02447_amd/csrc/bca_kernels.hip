@@ -482,15 +482,30 @@ __global__ __launch_bounds__(kBlock) void k_adam(const Chunk* __restrict__ table
 // else streams past it with non-temporal accesses), and are read again by A(g)
 // one group later, so HBM sees the gradients once.
 //
-// Items are handed out through a ticket counter, so an item is only ever held by
-// a running workgroup and items are started in list order.  An Adam item needs
-// its bucket's coefficient; it waits on that bucket's ready word, which is set
-// by whichever squared-norm workgroup of the bucket finishes last (it adds the
-// bucket's partials in the fixed order of k_finalize, so results do not depend
-// on who that is).  All squared-norm items of a bucket precede its Adam items in
-// the list, hence are held by running workgroups that wait for nothing: every
-// wait ends.  The wait is bounded all the same; on expiry the item is skipped and
-// BCA_STATUS_TIMEOUT is reported.
+// An Adam item needs its bucket's coefficient; it waits on that bucket's ready
+// word, which is set by whichever squared-norm workgroup of the bucket finishes
+// last (it adds the bucket's partials in the fixed order of k_finalize, so
+// results do not depend on who that is).  All squared-norm items of a bucket
+// precede its Adam items in the list and never wait themselves.
+//
+// Which workgroup takes which item:
+//  * default: item = workgroup index.  gfx950 starts the workgroups of a grid in
+//    index order within each XCD, so everything an Adam item waits for has been
+//    started before it.
+//  * TICKETS: eight atomic counters, one per XCD; item 8 t + y is the t-th item
+//    of list y.  A workgroup draws from its own XCD's list and moves to the next
+//    list when that one is used up.  Each list is thus started strictly in order
+//    by running workgroups, whatever the dispatcher does.  Why no wait can last:
+//    take the waiting Adam item of the earliest group k and a squared-norm item I
+//    of its bucket that has not been taken, in list y.  XCD y cannot be full of
+//    waiters drawn from list y, because those would lie before I in list y and so
+//    belong to groups before k; nor of waiters drawn from other lists, because a
+//    workgroup only leaves its own list once it is used up, and then I was taken.
+//    So XCD y has a free slot or a running non-waiter, starts another workgroup,
+//    and list y advances to I.
+// The wait is bounded all the same: after kSpinLimit polls the item is skipped,
+// an abort word makes every other waiter give up at its next look, and
+// BCA_STATUS_TIMEOUT is reported, so the grid always drains.
 
 constexpr uint32_t kSpinLimit = 1u << 18;  // polls of a ready word before an Adam item gives up (about a second)
 

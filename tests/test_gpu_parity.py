@@ -199,6 +199,7 @@ def test_adversarial_layouts_fused_and_unfused(name, dtype):
     run_fused(lay, g, p, m, v, thr, hp, 3, 0, offsets=offsets, group_bytes=20_000, tune_flags=B.BCA_TUNE_MULTI_LAUNCH)
     run_fused(lay, g, p, m, v, thr, hp, 3, B.BCA_WRITE_BACK_GRADS, offsets=offsets, group_bytes=20_000, chunk_norm=4096,
               chunk_apply=2048)
+    run_fused(lay, g, p, m, v, thr, hp, 3, 0, offsets=offsets, group_bytes=20_000, tune_flags=B.BCA_TUNE_TICKETS)
 
 
 def test_empty_bucket_range_is_a_noop():
@@ -281,10 +282,13 @@ def test_fused_equals_unfused_bitwise_for_fp32_and_runs_are_reproducible():
     thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
     results = []
     ML = B.BCA_TUNE_MULTI_LAUNCH
-    for mode in ("fused", "fused", "unfused", "one_group", "multi", "multi_other_grid", "multi_staged", "multi_one_group"):
+    for mode in ("fused", "fused", "unfused", "one_group", "tickets", "multi", "multi_other_grid", "multi_staged",
+                 "multi_one_group"):
         tuning = {}
         if mode == "one_group":
             tuning = dict(group_bytes=1 << 40)
+        elif mode == "tickets":
+            tuning = dict(tune_flags=B.BCA_TUNE_TICKETS, group_bytes=300_000)
         elif mode == "multi":
             tuning = dict(tune_flags=ML, group_bytes=300_000)
         elif mode == "multi_other_grid":    # same chunk cuts, other workgroup assignment and unroll
