@@ -309,9 +309,10 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   build_table(&p->apply_tab, chunk_apply, n_buckets, bucket_seg_off, segments);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
   build_work(p);
-  if (p->apply_tab.chunks.size() >= (1ull << 30) || p->norm_tab.chunks.size() >= (1ull << 30)) {
+  // A launch holds at most 2^32 threads: with 256 per workgroup that is 2^24 workgroups.
+  if (p->work.size() >= (1ull << 24)) {
     delete p;
-    return fail(BCA_ERR_RANGE, "too many chunks; raise the chunk sizes");
+    return fail(BCA_ERR_RANGE, "too many chunks for one launch; raise chunk_norm / chunk_apply");
   }
 
   if (device >= 0) {
