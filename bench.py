@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # Bytes crossing the L2 <-> fabric boundary in one launch of the dominant kernel, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for libbca's plain copy kernel
-# (profiles/k_step_bert_large_fp32_50MiB_hbm_counters.txt).  Key: (config, write_back, single_launch).
-MEASURED_TRAFFIC_BYTES = {(3, False, True): 10835977229}
+# (profiles/k_step_bert_large_fp32_50MiB_hbm_counters.txt).  Key: (config, single_launch).
+MEASURED_TRAFFIC_BYTES = {(3, True): 10835977229}
 
 
 def parse():
@@ -43,7 +43,6 @@ def parse():
     ap.add_argument("--grid-norm", type=int, default=0)
     ap.add_argument("--grid-apply", type=int, default=0)
     ap.add_argument("--tune-flags", type=int, default=0)
-    ap.add_argument("--write-back", action="store_true")
     ap.add_argument("--oracle-steps", type=int, default=3)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many 1 GiB plain copies (k_copy) so that counter runs have a known reference")
@@ -104,7 +103,7 @@ def main():
     norms = torch.zeros(lay.n_buckets, dtype=torch.float32, device=dev)
     coefs = torch.zeros_like(norms)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    flags = B.BCA_WRITE_BACK_GRADS if a.write_back else 0
+    flags = 0        # gradients are read, never written: the timed steps keep clipping the same way
     stream = torch.cuda.current_stream()
 
     # host copies for the CPU baseline are taken before the state evolves
@@ -151,9 +150,32 @@ def main():
     plan.profile(0)
     ms_norm, ms_fin, ms_adam = ms_norm / n_prof, ms_fin / n_prof, ms_adam / n_prof
 
+    # ---- per-step spread: each step between two events on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for e0, e1 in evs:
+        e0.record(stream)
+        one_step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
+
+    # ---- practical ceiling on this machine: plain copy kernel, 1 GiB, read + written bytes
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+    dst = torch.empty_like(src)
+    B.copy_bytes(dst, src, 1 << 30, stream)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(stream)
+    for _ in range(5):
+        B.copy_bytes(dst, src, 1 << 30, stream)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
     gbytes = 2 if f16 else 4
     single = not (a.tune_flags & B.BCA_TUNE_MULTI_LAUNCH)
-    pmv_bytes = 24 + (gbytes if a.write_back else 0)      # p, m, v read and written (+ scaled g written back)
+    pmv_bytes = 24                                         # p, m, v read and written
     once_per_elt = pmv_bytes + gbytes                      # gradients counted once (second read served by cache)
     twice_per_elt = pmv_bytes + 2 * gbytes                 # gradients read by the norm pass and again by the Adam pass
     if single:
@@ -164,7 +186,7 @@ def main():
         kname = "k_adam (clip-fused Adam sweep, summed over bucket groups)"
         per_elt, ms_kernel = once_per_elt, ms_adam
     achieved = per_elt * N / (ms_kernel * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((a.config, bool(a.write_back), single))
+    traffic = MEASURED_TRAFFIC_BYTES.get((a.config, single))
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "bytes_per_elt": per_elt,
                 "ms_per_launch": round(ms_kernel, 4),
@@ -175,6 +197,8 @@ def main():
     extras = {
         "kernels_ms": ({"k_prepare": round(ms_norm, 4), "k_step": round(ms_adam, 4)} if single else
                        {"k_sqnorm": round(ms_norm, 4), "k_finalize": round(ms_fin, 4), "k_adam": round(ms_adam, 4)}),
+        "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
+        "plain_copy_kernel_GBps": round(copy_gbps, 1),
         "step_GBps_g_read_once": round(once_per_elt * N / (ms_per_step * 1e-3) / 1e9, 1),
         "step_GBps_g_read_twice": round(twice_per_elt * N / (ms_per_step * 1e-3) / 1e9, 1),
         "step_frac_of_peak_g_read_twice": round(twice_per_elt * N / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -204,8 +228,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if not f16 else "f32 (f16 gradients)", "data": "synthetic",
         "config": {"workload": f"configs[{a.config - 1}]: {w.name}, {N} params in {lay.n_tensors} tensors, "
-                               f"{lay.n_buckets} buckets, grads {w.grad_dtype}",
-                   "write_back": bool(a.write_back)},
+                               f"{lay.n_buckets} buckets, grads {w.grad_dtype}"},
         "roofline": roofline, "cpu_baseline": cpu, **extras,
     }
     print(json.dumps(out))
