@@ -418,3 +418,68 @@ def test_fused_step_in_a_hip_graph_replays_like_eager_calls():
     check_state("v", to_host(eager.v), ov, strict_rel=True)
     eager.close()
     graph.close()
+
+
+def random_layout(rng):
+    """Random tensors (some empty, some tiny, some spanning several chunks), cut into buckets at
+    random element positions of the reversed flat stream; a few buckets are left empty."""
+    n_t = int(rng.integers(1, 12))
+    numels = [int(rng.choice([0, 1, 3, 17, 255, 1024, 1025, 4097, 30000, 70001])) + int(rng.integers(0, 50))
+              for _ in range(n_t)]
+    total = sum(numels)
+    n_cuts = int(rng.integers(0, 8))
+    cuts = sorted(set(int(x) for x in rng.integers(0, max(total, 1) + 1, n_cuts))) if total else []
+    bounds = [0] + cuts + [total]
+    # walk the reversed stream and split at the bounds
+    stream = []                                   # (tensor, begin, len) pieces in stream order
+    for t in range(n_t - 1, -1, -1):
+        if numels[t]:
+            stream.append((t, 0, numels[t]))
+    buckets, pos, it = [], 0, 0
+    pieces = list(stream)
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        need, segs = hi - lo, []
+        while need > 0:
+            t, beg, ln = pieces[0]
+            take = min(ln, need)
+            segs.append((t, beg, take))
+            need -= take
+            if take == ln:
+                pieces.pop(0)
+            else:
+                pieces[0] = (t, beg + take, ln - take)
+        buckets.append(segs)
+        if rng.random() < 0.2:
+            buckets.append([])                    # an empty bucket
+    return W._mk_layout(numels, buckets), numels
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_layouts_all_modes(seed):
+    rng = np.random.default_rng(1000 + seed)
+    lay, numels = random_layout(rng)
+    nb = lay.n_buckets
+    f16 = bool(seed % 2)
+    offsets = [int(rng.integers(0, 4)) for _ in numels] if seed % 3 == 0 else None
+    if f16:
+        g = W.student_t_fp16_tensors(numels, seed, 1e-3, threads=1)
+    else:
+        g = W.normal_tensors(numels, seed, "g", 1e-2, threads=1)
+    p = W.normal_tensors(numels, seed, "p", 0.02, threads=1)
+    m = W.normal_tensors(numels, seed, "m", 3e-3, threads=1)
+    v = W.warm_second_moment(numels, seed, threads=1)
+    norms = oracle.bucket_norms(lay, g)
+    thr = np.asarray([max(norms[b], 1e-3) * float(rng.choice([0.05, 0.5, 0.999, 1.5, 50.0])) for b in range(nb)],
+                     np.float32)
+    hp = W.Hyper(lr=float(rng.choice([1e-3, 1e-2])), beta1=float(rng.choice([0.7, 0.9])),
+                 beta2=float(rng.choice([0.85, 0.999])), eps=float(rng.choice([1e-11, 1e-6])),
+                 weight_decay=float(rng.choice([0.0, 0.01, 0.1])))
+    step = int(rng.choice([1, 2, 77, 100000]))
+    gb = int(rng.choice([1, 5000, 1 << 40]))
+    run_fused(lay, g, p, m, v, thr, hp, step, 0, offsets=offsets, group_bytes=gb)
+    run_fused(lay, g, p, m, v, thr, hp, step, B.BCA_WRITE_BACK_GRADS, offsets=offsets, group_bytes=gb,
+              chunk_norm=int(rng.choice([1024, 4096])), chunk_apply=int(rng.choice([1024, 2048, 4096])))
+    run_fused(lay, g, p, m, v, thr, hp, step, 0, offsets=offsets, group_bytes=gb, tune_flags=B.BCA_TUNE_TICKETS)
+    run_fused(lay, g, p, m, v, thr, hp, step, B.BCA_SKIP_STEP_ON_NONFINITE, offsets=offsets, group_bytes=gb)
+    run_fused(lay, g, p, m, v, thr, hp, step, 0, offsets=offsets, group_bytes=gb, tune_flags=B.BCA_TUNE_MULTI_LAUNCH)
+    run_unfused(lay, g, p, m, v, thr, hp, step, offsets=offsets)
