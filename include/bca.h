@@ -158,6 +158,14 @@ int bucket_clip_apply(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thr
                       const float* norms /*DEVICE [B]*/, float* coefs /*DEVICE [B] or NULL*/,
                       int32_t* status /*DEVICE or NULL*/, void* stream);
 
+/* bucket_clip_norms followed by bucket_clip_apply on buckets [b0, b1) as one pipelined
+ * launch, for the paper's use of the method: a bucket is clipped as soon as backward
+ * has produced it, before its all-reduce (Sec. 4.2, Alg. 1).  Same norms, coefficients
+ * and scaled gradients, bit for bit.  norms / coefs (DEVICE [B], entries b0..b1-1
+ * written) and status (DEVICE int32, written) may each be NULL. */
+int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thresholds /*DEVICE [B]*/, float* norms,
+                float* coefs, int32_t* status, void* stream);
+
 /* theta <- ADAM(theta, eta, G) over every tensor of the plan, reading the
  * gradients as stored (Alg. 1, last line).  Adam as published by Kingma & Ba
  * with bias correction; step >= 1 counts this update:

@@ -27,7 +27,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
 
 EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_groups",
            "bca_plan_num_chunks",
-           "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "adam_step",
+           "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step",
            "bucket_clip_adam", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error", "bca_version"]
 
 
@@ -104,6 +104,7 @@ def load_library():
     L.bca_plan_bucket_chunks.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u32)]
     L.bucket_clip_norms.argtypes = [vp, u32, u32, vp, vp]
     L.bucket_clip_apply.argtypes = [vp, u32, u32, vp, vp, vp, vp, vp]
+    L.bucket_clip.argtypes = [vp, u32, u32, vp, vp, vp, vp, vp]
     L.adam_step.argtypes = [vp, C.POINTER(_Adam), u64, vp]
     L.bucket_clip_adam.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp]
     L.bca_plan_profile.argtypes = [vp, u32]
@@ -249,6 +250,10 @@ class Plan:
     def bucket_clip_apply(self, b0: int, b1: int, thresholds, norms, coefs=None, status=None, stream=None) -> None:
         _check(self._L.bucket_clip_apply(self._h, b0, b1, _ptr(thresholds), _ptr(norms), _ptr(coefs), _ptr(status),
                                          _stream(stream)))
+
+    def bucket_clip(self, b0: int, b1: int, thresholds, norms=None, coefs=None, status=None, stream=None) -> None:
+        _check(self._L.bucket_clip(self._h, b0, b1, _ptr(thresholds), _ptr(norms), _ptr(coefs), _ptr(status),
+                                   _stream(stream)))
 
     def adam_step(self, hp: AdamHyper, step: int, stream=None) -> None:
         h = hp._c()

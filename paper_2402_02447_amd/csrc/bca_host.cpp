@@ -543,6 +543,29 @@ int bucket_clip_apply(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresh
   return BCA_OK;
 }
 
+int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, float* norms, float* coefs,
+                int32_t* status, void* stream) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  if (int rc = check_range(p, b0, b1)) return rc;
+  if (!thresholds) return fail(BCA_ERR_NULL, "thresholds is NULL");
+  if (int rc = check_ready(p)) return rc;
+  if (b0 == b1) return BCA_OK;
+  DeviceGuard g(p->device);
+  StepState ss;
+  ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
+  ss.norm_bucket_off = p->norm_tab.d_bucket_off;
+  ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+  const Table& TN = p->norm_tab;
+  const Table& TA = p->apply_tab;
+  const uint32_t cn0 = TN.bucket_off[b0], nn = TN.bucket_off[b1] - cn0;
+  const uint32_t ca0 = TA.bucket_off[b0], na = TA.bucket_off[b1] - ca0;
+  hipError_t e = launch_clip(p->grad_dtype, ss, b0, b1, cn0, nn, ca0, na, thresholds, norms ? norms : p->d_norms,
+                             coefs ? coefs : p->d_coefs, status ? status : p->d_status, p->unroll_apply,
+                             (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "launching the clip kernel");
+  return BCA_OK;
+}
+
 int adam_step(bca_plan* p, const bca_adam* hp, uint64_t step, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   AdamK k;

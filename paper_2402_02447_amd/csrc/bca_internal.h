@@ -111,6 +111,11 @@ hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const u
                        const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
                        const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream);
 
+// Clipping of buckets [b0, b1) in one launch (k_prepare_range, then k_clip): cn0 / n_norm
+// and ca0 / n_apply are the range's chunks in the norm and the apply table.
+hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
+                       uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
+                       int32_t* status, uint32_t unroll, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 
 void set_error(const std::string& msg);

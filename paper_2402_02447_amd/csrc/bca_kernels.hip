@@ -328,41 +328,46 @@ __global__ __launch_bounds__(kBlock) void k_coefs(uint32_t b0, uint32_t b1, cons
 
 // ---- in-place scale -------------------------------------------------------------
 
-// G_b <- coef_b * G_b for clipped buckets (Alg. 1, the assignment under the if);
-// buckets with coef_b == 1 are not read at all.
-template <int GDT, uint32_t U, bool NT, bool STAGED>
-__global__ __launch_bounds__(kBlock) void k_scale(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
-                                                   const float* __restrict__ coefs) {
+// g <- coef * g over one chunk, in the gradient's storage type (Alg. 1, the
+// assignment under the if).
+template <int GDT, uint32_t U, bool NT>
+__device__ __forceinline__ void scale_chunk(const Entry& en, float coef) {
   typedef Grad<GDT> G;
   constexpr uint32_t gsize = sizeof(typename G::elem);
   const uint32_t tid = threadIdx.x;
-  for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t) {
-    const float coef = coefs[en.bucket];
-    if (coef == 1.f) return;
-    const uint64_t ga = en.g;
-    const uint32_t len = en.len;
-    const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, false, 0, 0, 0);
-    const uint32_t nvec = (len - head) / 4u;
-    const uint32_t tail0 = head + nvec * 4u;
-    void* gbase = reinterpret_cast<void*>(ga);
-    void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
-    for (uint32_t base = 0; base < nvec; base += kBlock * U) {
-      const uint32_t j0 = base + tid;
-      if (base + kBlock * U <= nvec) {
-        f32x4 x[U];
+  const uint64_t ga = en.g;
+  const uint32_t len = en.len;
+  const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, false, 0, 0, 0);
+  const uint32_t nvec = (len - head) / 4u;
+  const uint32_t tail0 = head + nvec * 4u;
+  void* gbase = reinterpret_cast<void*>(ga);
+  void* gv = reinterpret_cast<void*>(ga + (uint64_t)head * gsize);
+  for (uint32_t base = 0; base < nvec; base += kBlock * U) {
+    const uint32_t j0 = base + tid;
+    if (base + kBlock * U <= nvec) {
+      f32x4 x[U];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) x[u] = G::template load4<NT>(gv, j0 + u * kBlock);
+      for (uint32_t u = 0; u < U; ++u) x[u] = G::template load4<NT>(gv, j0 + u * kBlock);
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) G::template store4<NT>(gv, j0 + u * kBlock, x[u] * coef);
-      } else {
-        for (uint32_t u = 0; u < U; ++u) {
-          const uint32_t j = j0 + u * kBlock;
-          if (j < nvec) G::template store4<NT>(gv, j, G::template load4<NT>(gv, j) * coef);
-        }
+      for (uint32_t u = 0; u < U; ++u) G::template store4<NT>(gv, j0 + u * kBlock, x[u] * coef);
+    } else {
+      for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t j = j0 + u * kBlock;
+        if (j < nvec) G::template store4<NT>(gv, j, G::template load4<NT>(gv, j) * coef);
       }
     }
-    for (uint32_t i = tid; i < head; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
-    for (uint32_t i = tail0 + tid; i < len; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
+  }
+  for (uint32_t i = tid; i < head; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
+  for (uint32_t i = tail0 + tid; i < len; i += kBlock) G::store1(gbase, i, G::load1(gbase, i) * coef);
+}
+
+// Buckets with coef_b == 1 are not read at all.
+template <int GDT, uint32_t U, bool NT, bool STAGED>
+__global__ __launch_bounds__(kBlock) void k_scale(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
+                                                   const float* __restrict__ coefs) {
+  for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t) {
+    const float coef = coefs[en.bucket];
+    if (coef != 1.f) scale_chunk<GDT, U, NT>(en, coef);
   });
 }
 
@@ -521,73 +526,51 @@ __global__ __launch_bounds__(kBlock) void k_prepare(StepState st, uint32_t n_buc
   }
 }
 
-template <int GDT, bool WB, uint32_t U, bool TICKETS>
-__global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
-                                                  const float* __restrict__ thresholds, float* __restrict__ norms,
-                                                  float* __restrict__ coefs, int32_t* status, const AdamK k) {
-  __shared__ uint32_t s_item;
-  __shared__ uint32_t s_flag;
-  __shared__ float s_coef;
-  __shared__ double s_w[kWaves];
+// Shared memory of one k_step / k_clip workgroup.
+struct StepShared {
+  uint32_t item;
+  uint32_t flag;
+  float coef;
+  double w[kWaves];
+};
+
+// Waits (bounded) for bucket b's ready word of this epoch.  Returns true with the
+// bucket's coefficient in sh.coef, or false after reporting BCA_STATUS_TIMEOUT.
+__device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b, uint32_t epoch, int32_t* status,
+                                                StepShared& sh) {
+  if (threadIdx.x == 0) {
+    // ready word: (epoch << 32) | bits of the coefficient
+    unsigned long long r = 0;
+    uint32_t polls = 0;
+    for (;;) {
+      r = __hip_atomic_load(&st.ready[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((uint32_t)(r >> 32) == epoch || ++polls > kSpinLimit) break;
+      // once one wait has expired every other waiter gives up at its next look
+      if ((polls & 63u) == 0 && __hip_atomic_load(&st.ctl[kCtlAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
+        break;
+      __builtin_amdgcn_s_sleep(8);
+    }
+    const bool ok = (uint32_t)(r >> 32) == epoch;
+    sh.flag = ok ? 1u : 0u;
+    sh.coef = __uint_as_float((uint32_t)r);
+    if (!ok) {
+      __hip_atomic_store(&st.ctl[kCtlAbort], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      atomicOr(status, BCA_STATUS_TIMEOUT);
+    }
+  }
+  __syncthreads();
+  return sh.flag != 0u;
+}
+
+// A squared-norm item (kind kItemNorm, idx = chunk of the norm table) or the
+// stand-in for a bucket without elements (kItemEmpty, idx = bucket).  The last
+// workgroup of a bucket to get here adds the bucket's partials in the fixed
+// order of k_finalize, writes norm and coefficient and publishes the ready word.
+template <int GDT>
+__device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, uint32_t idx, uint32_t epoch,
+                                          const float* __restrict__ thresholds, float* __restrict__ norms,
+                                          float* __restrict__ coefs, int32_t* status, StepShared& sh) {
   const uint32_t tid = threadIdx.x;
-  uint32_t ticket;
-  if constexpr (TICKETS) {
-    // Eight ticket counters, one per XCD: item 8 t + y is the t-th item of list y.  A
-    // workgroup draws from its own XCD's list and moves on to the next list when that
-    // one is used up, so every list is started strictly in order and every item is
-    // taken by exactly one of the n_work workgroups.
-    if (tid == 0) {
-      const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;  // HW_REG_XCC_ID[3:0]
-      uint32_t it = 0xffffffffu;
-      for (uint32_t a = 0; a < 8u; ++a) {
-        const uint32_t y = (xcc + a) & 7u;
-        const uint32_t t = atomicAdd(&st.ctl[kCtlTicket + 32u * y], 1u);
-        if ((uint64_t)t * 8u + y < n_work) {
-          it = t * 8u + y;
-          break;
-        }
-      }
-      s_item = it;
-    }
-    __syncthreads();
-    ticket = s_item;
-  } else {
-    ticket = blockIdx.x;
-  }
-  if (ticket >= n_work) return;
-  const uint32_t epoch = st.ctl[kCtlEpoch];  // written by k_prepare, constant during this launch
-  const uint32_t item = work[ticket];
-  const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
-
-  if (kind == kItemAdam) {
-    const Entry en = read_entry(&st.apply_tab[idx]);
-    if (tid == 0) {
-      // wait for the bucket's ready word: (epoch << 32) | bits of the coefficient
-      unsigned long long r = 0;
-      uint32_t polls = 0;
-      for (;;) {
-        r = __hip_atomic_load(&st.ready[en.bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((uint32_t)(r >> 32) == epoch || ++polls > kSpinLimit) break;
-        // once one wait has expired every other waiter gives up at its next look
-        if ((polls & 63u) == 0 &&
-            __hip_atomic_load(&st.ctl[kCtlAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
-          break;
-        __builtin_amdgcn_s_sleep(8);
-      }
-      const bool ok = (uint32_t)(r >> 32) == epoch;
-      s_flag = ok ? 1u : 0u;
-      s_coef = __uint_as_float((uint32_t)r);
-      if (!ok) {
-        __hip_atomic_store(&st.ctl[kCtlAbort], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        atomicOr(status, BCA_STATUS_TIMEOUT);
-      }
-    }
-    __syncthreads();
-    if (s_flag) adam_chunk<GDT, true, WB, U, false>(en, s_coef, k);
-    return;
-  }
-
-  // squared-norm item, or the stand-in for a bucket without elements
   uint32_t b = idx;
   if (kind == kItemNorm) {
     const Entry en = read_entry(&st.norm_tab[idx]);
@@ -604,22 +587,20 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
     if (tid == 0) {
       const uint32_t total = st.norm_bucket_off[b + 1] - st.norm_bucket_off[b];
       const uint32_t old = atomicAdd(&st.arrived[b], 1u);
-      s_flag = (old + 1u == total) ? 1u : 0u;
+      sh.flag = (old + 1u == total) ? 1u : 0u;
     }
     __syncthreads();
-    if (!s_flag) return;  // the last to arrive goes on; its loads below are device-scope and bypass L2
+    if (!sh.flag) return;  // the last to arrive goes on; its loads below are device-scope and bypass L2
   }
-
-  // add the bucket's partials in the fixed order of k_finalize
   const uint64_t lo = (uint64_t)st.norm_bucket_off[b] * kWaves, hi = (uint64_t)st.norm_bucket_off[b + 1] * kWaves;
   double s = 0.0;
   for (uint64_t i = lo + tid; i < hi; i += kBlock)
     s += __hip_atomic_load(&st.partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   s = wave_sum(s);
-  if ((tid & 63u) == 0) s_w[tid >> 6] = s;
+  if ((tid & 63u) == 0) sh.w[tid >> 6] = s;
   __syncthreads();
   if (tid == 0) {
-    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+    const double tot = ((sh.w[0] + sh.w[1]) + sh.w[2]) + sh.w[3];
     const float norm = (float)sqrt(tot);
     int32_t bst = 0;
     const float coef = clip_coef(norm, thresholds[b], bst);
@@ -628,6 +609,96 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
     if (bst) atomicOr(status, bst);
     const unsigned long long word = ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(coef);
     __hip_atomic_store(&st.ready[b], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+template <int GDT, bool WB, uint32_t U, bool TICKETS>
+__global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
+                                                  const float* __restrict__ thresholds, float* __restrict__ norms,
+                                                  float* __restrict__ coefs, int32_t* status, const AdamK k) {
+  __shared__ StepShared sh;
+  uint32_t ticket;
+  if constexpr (TICKETS) {
+    // Eight ticket counters, one per XCD: item 8 t + y is the t-th item of list y.  A
+    // workgroup draws from its own XCD's list and moves on to the next list when that
+    // one is used up, so every list is started strictly in order and every item is
+    // taken by exactly one of the n_work workgroups.
+    if (threadIdx.x == 0) {
+      const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;  // HW_REG_XCC_ID[3:0]
+      uint32_t it = 0xffffffffu;
+      for (uint32_t a = 0; a < 8u; ++a) {
+        const uint32_t y = (xcc + a) & 7u;
+        const uint32_t t = atomicAdd(&st.ctl[kCtlTicket + 32u * y], 1u);
+        if ((uint64_t)t * 8u + y < n_work) {
+          it = t * 8u + y;
+          break;
+        }
+      }
+      sh.item = it;
+    }
+    __syncthreads();
+    ticket = sh.item;
+  } else {
+    ticket = blockIdx.x;
+  }
+  if (ticket >= n_work) return;
+  const uint32_t epoch = st.ctl[kCtlEpoch];  // written by k_prepare, constant during this launch
+  const uint32_t item = work[ticket];
+  const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
+  if (kind == kItemAdam) {
+    const Entry en = read_entry(&st.apply_tab[idx]);
+    if (wait_for_bucket(st, en.bucket, epoch, status, sh)) adam_chunk<GDT, true, WB, U, false>(en, sh.coef, k);
+  } else {
+    norm_item<GDT>(st, kind, idx, epoch, thresholds, norms, coefs, status, sh);
+  }
+}
+
+// Clipping of a bucket range in one launch (the paper's per-bucket use: a bucket
+// is clipped the moment backward has produced it).  Workgroups 0 .. n_norm-1 take
+// the range's squared-norm chunks, the following n_apply ones its scale chunks,
+// which wait for their bucket's coefficient exactly as the Adam items of k_step
+// do; buckets that are not clipped are not touched.  Norms, coefficients and
+// scaled gradients are those of k_sqnorm + k_finalize + k_coefs + k_scale bit
+// for bit.  Buckets without elements are dealt with by k_prepare_range.
+template <int GDT, uint32_t U>
+__global__ __launch_bounds__(kBlock) void k_clip(StepState st, uint32_t cn0, uint32_t n_norm, uint32_t ca0,
+                                                  uint32_t n_apply, const float* __restrict__ thresholds,
+                                                  float* __restrict__ norms, float* __restrict__ coefs,
+                                                  int32_t* status) {
+  __shared__ StepShared sh;
+  const uint32_t w = blockIdx.x;
+  const uint32_t epoch = st.ctl[kCtlEpoch];
+  if (w < n_norm) {
+    norm_item<GDT>(st, kItemNorm, cn0 + w, epoch, thresholds, norms, coefs, status, sh);
+  } else if (w - n_norm < n_apply) {
+    const Entry en = read_entry(&st.apply_tab[ca0 + (w - n_norm)]);
+    if (wait_for_bucket(st, en.bucket, epoch, status, sh) && sh.coef != 1.f) scale_chunk<GDT, U, false>(en, sh.coef);
+  }
+}
+
+// Per-call reset for k_clip: new epoch, arrival counters of the range, status
+// word; norm 0 and the coefficient of buckets that have no elements.
+__global__ __launch_bounds__(kBlock) void k_prepare_range(StepState st, uint32_t b0, uint32_t b1,
+                                                           const float* __restrict__ thresholds,
+                                                           float* __restrict__ norms, float* __restrict__ coefs,
+                                                           int32_t* status) {
+  __shared__ int32_t s_st;
+  if (threadIdx.x == 0) s_st = 0;
+  __syncthreads();
+  int32_t bst = 0;
+  for (uint32_t b = b0 + threadIdx.x; b < b1; b += kBlock) {
+    st.arrived[b] = 0u;
+    if (st.norm_bucket_off[b] == st.norm_bucket_off[b + 1]) {
+      norms[b] = 0.f;
+      coefs[b] = clip_coef(0.f, thresholds[b], bst);
+    }
+  }
+  if (bst) atomicOr(&s_st, bst);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    st.ctl[kCtlAbort] = 0u;
+    st.ctl[kCtlEpoch] = st.ctl[kCtlEpoch] + 1u;
+    *status = s_st;
   }
 }
 
@@ -685,6 +756,24 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t 
   const uint64_t want = (nbytes / 16u + kBlock - 1) / kBlock;
   const uint32_t grid = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(want, 1), 1u << 20);
   hipLaunchKernelGGL(k_copy, dim3(grid), dim3(kBlock), 0, stream, (uint8_t*)dst, (const uint8_t*)src, nbytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
+                       uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
+                       int32_t* status, uint32_t unroll, hipStream_t stream) {
+  hipLaunchKernelGGL(k_prepare_range, dim3(1), dim3(kBlock), 0, stream, st, b0, b1, thresholds, norms, coefs, status);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_norm + n_apply == 0) return e;
+  pick_unroll(unroll, [&](auto uu) {
+    constexpr uint32_t U = decltype(uu)::value;
+    if (gdt == BCA_GRAD_F32)
+      hipLaunchKernelGGL((k_clip<BCA_GRAD_F32, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm,
+                         ca0, n_apply, thresholds, norms, coefs, status);
+    else
+      hipLaunchKernelGGL((k_clip<BCA_GRAD_F16, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm,
+                         ca0, n_apply, thresholds, norms, coefs, status);
+  });
   return hipGetLastError();
 }
 

@@ -87,6 +87,19 @@ def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=Tr
     og = [x.copy() for x in g]
     oracle.bucket_scale(layout, og, ocoef)
     check_scaled_grads(to_host(dev.g), og, g)
+    # the one-launch form of the same two calls gives the same bits
+    one = Device(layout, g, p, m, v, offsets, **tuning)
+    stat1 = 0
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        one.plan.bucket_clip(a, b, dthr, one.norms, one.coefs, one.status)
+        stat1 |= int(one.status.item())
+    one.sync()
+    assert stat1 == ost
+    assert np.array_equal(one.norms.cpu().numpy(), dev.norms.cpu().numpy())
+    assert np.array_equal(one.coefs.cpu().numpy(), gcoef)
+    assert bits_equal(to_host(one.g), to_host(dev.g))
+    assert bits_equal(to_host(one.p), p)
+    one.close()
     # Adam on the stored gradients.  For fp16 storage a last-bit difference between the
     # GPU's and the oracle's coefficient can move a stored gradient by one fp16 ulp
     # (checked above); so that Adam is compared on identical inputs, the GPU's copy

@@ -19,8 +19,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     L = B.load_library()
     header = open(os.path.join(ROOT, "include", "bca.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|adam_step)\s*\(", header))
-    assert {"bucket_clip_norms", "bucket_clip_apply", "adam_step", "bucket_clip_adam"} <= declared
+    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|bucket_clip|adam_step)\s*\(", header))
+    assert {"bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam"} <= declared
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(L, name), name
@@ -181,12 +181,21 @@ def test_argument_errors_come_before_any_launch():
         with pytest.raises(B.BcaError) as e:
             p.bucket_clip_apply(b0, b1, 1234, 1234)
         assert e.value.code == -3
+        with pytest.raises(B.BcaError) as e:
+            p.bucket_clip(b0, b1, 1234)
+        assert e.value.code == -3
     with pytest.raises(B.BcaError) as e:
         p.bucket_clip_norms(0, 2, None)
     assert e.value.code == -1
     with pytest.raises(B.BcaError) as e:
         p.bucket_clip_apply(0, 2, None, 1234)
     assert e.value.code == -1
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip(0, 2, None)
+    assert e.value.code == -1
+    with pytest.raises(B.BcaError) as e:
+        p.bucket_clip(0, 2, 1234)
+    assert e.value.code == -5
 
 
 def test_a_device_plan_fails_loudly_without_a_gpu():
