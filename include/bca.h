@@ -57,6 +57,11 @@ typedef struct bca_plan bca_plan; /* opaque */
 /* flags of bucket_clip_adam */
 #define BCA_WRITE_BACK_GRADS 1u       /* also store the scaled gradient into g (what Alg. 1
                                          hands to the all-reduce)                          */
+#define BCA_CLIP_WHOLE_GRADIENT 4u    /* clip the whole gradient by its norm with ONE threshold instead
+                                         of bucket by bucket (the paper's two baselines, Sec. 3.2):
+                                         `thresholds` points to a single float c; all coefs[b] are the
+                                         same factor; norms, if given, needs n_buckets + 1 entries and
+                                         norms[n_buckets] receives the whole-gradient norm              */
 #define BCA_SKIP_STEP_ON_NONFINITE 2u /* if any bucket norm is non-finite, leave g, p, m, v
                                          untouched (status still reports it)               */
 
@@ -176,8 +181,9 @@ int adam_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, void* 
 /* The fused step: norms and clip factors of all buckets, then one sweep that
  * forms ghat = coef_b * g in registers and applies Adam to it.  g is read, not
  * written, unless BCA_WRITE_BACK_GRADS.  norms / coefs (DEVICE [B]) and status
- * (DEVICE int32) may each be NULL.  With BCA_SKIP_STEP_ON_NONFINITE all norms
- * are computed before any update (no pipelining of bucket groups). */
+ * (DEVICE int32) may each be NULL.  With BCA_SKIP_STEP_ON_NONFINITE or
+ * BCA_CLIP_WHOLE_GRADIENT all norms are computed before any update (no
+ * pipelining of bucket groups). */
 int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
                      uint64_t step, uint32_t flags, float* norms, float* coefs, int32_t* status, void* stream);
 

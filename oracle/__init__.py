@@ -60,6 +60,10 @@ def _declare(L):
                                        C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64,
                                        C.c_int, C.c_int, dp, fp]
     L.orc_bucket_clip_adam.restype = C.c_int32
+    L.orc_whole_clip_adam.argtypes = [C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, vpp, vpp, vpp, C.c_float,
+                                      C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64, C.c_int,
+                                      dp, dp, fp]
+    L.orc_whole_clip_adam.restype = C.c_int32
     L.orc_compare_f32.argtypes = [fp, dp, C.c_uint64, C.c_double, C.c_double, C.c_double, C.c_double, dp]
     L.orc_compare_f32.restype = C.c_uint64
     return L
@@ -187,6 +191,25 @@ def bucket_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: Li
                                     lr, beta1, beta2, eps, weight_decay, int(step), int(write_back),
                                     int(skip_on_nonfinite), _p(norms, C.c_double), _p(coefs, C.c_float))
     return norms[:la.nb], coefs[:la.nb], int(st)
+
+
+def whole_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: List[np.ndarray], v: List[np.ndarray],
+                    threshold: float, lr: float, beta1: float, beta2: float, eps: float, weight_decay: float,
+                    step: int, write_back: bool = False) -> Tuple[np.ndarray, float, float, int]:
+    """Whole-gradient clipping + Adam.  Returns (per-bucket norms, whole norm, coefficient, status bits)."""
+    la = _Lay(layout)
+    gdt, dt = _gdt(grads)
+    for t in range(la.nt):
+        assert grads[t].shape[0] == p[t].shape[0] == m[t].shape[0] == v[t].shape[0] == int(la.numel[t])
+    norms = np.zeros(max(1, la.nb), np.float64)
+    whole = np.zeros(1, np.float64)
+    coef = np.ones(1, np.float32)
+    st = lib().orc_whole_clip_adam(*la.args(), _ptr_array(grads, dt), gdt, _ptr_array(p, np.float64),
+                                   _ptr_array(m, np.float64), _ptr_array(v, np.float64),
+                                   C.c_float(float(np.float32(threshold))), lr, beta1, beta2, eps, weight_decay,
+                                   int(step), int(write_back), _p(norms, C.c_double), _p(whole, C.c_double),
+                                   _p(coef, C.c_float))
+    return norms[:la.nb], float(whole[0]), float(coef[0]), int(st)
 
 
 def compare_f32(got: np.ndarray, want: np.ndarray, rel_tol: float = 1e-5, abs_tol: float = 1e-7,

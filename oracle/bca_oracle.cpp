@@ -240,6 +240,48 @@ int32_t orc_bucket_clip_adam(uint32_t n_buckets, const uint64_t* bucket_seg_off,
   return status;
 }
 
+// Whole-gradient clipping, the two baselines the paper compares with (Sec. 3.2:
+// clipping after or before the all-reduce, which coincide on one GPU): the
+// clipping-by-norm rule of Sec. 2.3 applied once to the concatenation of all
+// buckets with the single threshold c, then Adam on the scaled gradient formed
+// in working precision.  norms_out (may be null) receives the per-bucket norms,
+// *whole_norm_out the norm of the whole gradient, *coef_out the one coefficient.
+int32_t orc_whole_clip_adam(uint32_t n_buckets, const uint64_t* bucket_seg_off, const uint32_t* seg_tensor,
+                            const uint64_t* seg_begin, const uint64_t* seg_len, void* const* grads, int gdt,
+                            double* const* p, double* const* m, double* const* v, float threshold, double lr,
+                            double beta1, double beta2, double eps, double wd, uint64_t step, int write_back,
+                            double* norms_out, double* whole_norm_out, float* coef_out) {
+  double total = 0.0;
+  for (uint32_t b = 0; b < n_buckets; ++b) {
+    double s = 0.0;
+    for (uint64_t k = bucket_seg_off[b]; k < bucket_seg_off[b + 1]; ++k)
+      for (uint64_t i = seg_begin[k]; i < seg_begin[k] + seg_len[k]; ++i) {
+        const double x = load_grad(grads[seg_tensor[k]], gdt, i);
+        s += x * x;
+      }
+    if (norms_out) norms_out[b] = std::sqrt(s);
+    total += s;
+  }
+  const double whole = std::sqrt(total);
+  float coef = 1.0f;
+  const int32_t status = orc_clip_coefs(1, &whole, &threshold, &coef);
+  if (whole_norm_out) *whole_norm_out = whole;
+  if (coef_out) *coef_out = coef;
+  const Adam h{lr, beta1, beta2, eps, wd};
+  const double bc1 = 1.0 - std::pow(beta1, static_cast<double>(step));
+  const double bc2 = 1.0 - std::pow(beta2, static_cast<double>(step));
+  for (uint32_t b = 0; b < n_buckets; ++b)
+    for (uint64_t k = bucket_seg_off[b]; k < bucket_seg_off[b + 1]; ++k) {
+      const uint32_t t = seg_tensor[k];
+      for (uint64_t i = seg_begin[k]; i < seg_begin[k] + seg_len[k]; ++i) {
+        const double ghat = static_cast<double>(coef) * load_grad(grads[t], gdt, i);
+        adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);
+        if (write_back && coef != 1.0f) store_scaled_grad(grads[t], gdt, i, coef);
+      }
+    }
+  return status;
+}
+
 // Element-wise comparison of a GPU fp32 array with the oracle's fp64 array
 // under the acceptance rule: relative error <= rel_tol, or absolute error <=
 // abs_tol where |oracle| < small.  Returns the number of failing elements and

@@ -17,7 +17,7 @@ import numpy as np
 
 BCA_GRAD_F32, BCA_GRAD_F16 = 0, 1
 BCA_STATUS_NONFINITE, BCA_STATUS_BAD_THRESHOLD = 1, 2
-BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE = 1, 2
+BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE, BCA_CLIP_WHOLE_GRADIENT = 1, 2, 4
 BCA_TUNE_MULTI_LAUNCH, BCA_TUNE_STAGE_TABLE_LDS, BCA_TUNE_TICKETS = 1, 2, 4
 BCA_STATUS_TIMEOUT = 4
 BCA_TABLE_NORM, BCA_TABLE_APPLY = 0, 1

@@ -177,6 +177,8 @@ void free_device(bca_plan* p) {
   p->d_work = nullptr, p->d_arrived = nullptr, p->d_ready = nullptr, p->d_ctl = nullptr;
   if (p->d_partials) (void)hipFree(p->d_partials);
   if (p->d_norms) (void)hipFree(p->d_norms);
+  if (p->d_bucket_sq) (void)hipFree(p->d_bucket_sq);
+  p->d_bucket_sq = nullptr;
   if (p->d_coefs) (void)hipFree(p->d_coefs);
   if (p->d_status) (void)hipFree(p->d_status);
   p->d_partials = nullptr, p->d_norms = nullptr, p->d_coefs = nullptr, p->d_status = nullptr;
@@ -351,7 +353,8 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
         (e = hipMalloc((void**)&p->d_ctl, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMemset(p->d_ctl, 0, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_partials, np * sizeof(double))) != hipSuccess ||
-        (e = hipMalloc((void**)&p->d_norms, nb * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_norms, (nb + 1) * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_bucket_sq, nb * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_coefs, nb * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_status, sizeof(int32_t))) != hipSuccess ||
         (e = hipMemset(p->d_status, 0, sizeof(int32_t))) != hipSuccess) {
@@ -518,7 +521,7 @@ int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void*
   hipError_t e = launch_sqnorm(p->grad_dtype, T.d_chunks, c0, n, p->d_partials, nullptr,
                                make_launch(p, p->grid_norm, n, true), s);
   if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
-  e = launch_finalize(p->d_partials, T.d_bucket_off, b0, b1, nullptr, norms, nullptr, nullptr, s);
+  e = launch_finalize(p->d_partials, T.d_bucket_off, b0, b1, nullptr, norms, nullptr, nullptr, nullptr, s);
   if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
   return BCA_OK;
 }
@@ -584,11 +587,13 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
                      float* norms, float* coefs, int32_t* status, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   if (!thresholds) return fail(BCA_ERR_NULL, "thresholds is NULL");
-  if (flags & ~(BCA_WRITE_BACK_GRADS | BCA_SKIP_STEP_ON_NONFINITE)) return fail(BCA_ERR_RANGE, "unknown flag bits");
+  if (flags & ~(BCA_WRITE_BACK_GRADS | BCA_SKIP_STEP_ON_NONFINITE | BCA_CLIP_WHOLE_GRADIENT))
+    return fail(BCA_ERR_RANGE, "unknown flag bits");
   AdamK k;
   if (int rc = make_adam_constants(hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
-  const bool skip = (flags & BCA_SKIP_STEP_ON_NONFINITE) != 0;
+  const bool whole = (flags & BCA_CLIP_WHOLE_GRADIENT) != 0;
+  const bool skip = (flags & BCA_SKIP_STEP_ON_NONFINITE) != 0 || whole;  // both need every norm before any update
   const bool multi = (p->tune_flags & BCA_TUNE_MULTI_LAUNCH) != 0;
   DeviceGuard g(p->device);
   hipStream_t s = (hipStream_t)stream;
@@ -635,10 +640,14 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
                                  make_launch(p, p->grid_norm, nn, keep), s);
     if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
     if (ev) (void)hipEventRecord(*ev++, s);
-    e = launch_finalize(p->d_partials, TN.d_bucket_off, b0, b1, thresholds, nm, cf, st, s);
+    e = launch_finalize(p->d_partials, TN.d_bucket_off, b0, b1, whole ? nullptr : thresholds, nm, cf, st,
+                        whole ? p->d_bucket_sq : nullptr, s);
+    if (e == hipSuccess && whole)
+      e = launch_whole_coef(p->d_bucket_sq, p->n_buckets, thresholds, nm + p->n_buckets, cf, st, s);
     if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
     if (ev) (void)hipEventRecord(*ev++, s);
-    e = launch_adam(p->grad_dtype, TA.d_chunks, ca0, na, cf, (flags & BCA_WRITE_BACK_GRADS) != 0, skip ? st : nullptr,
+    e = launch_adam(p->grad_dtype, TA.d_chunks, ca0, na, cf, (flags & BCA_WRITE_BACK_GRADS) != 0,
+                    (flags & BCA_SKIP_STEP_ON_NONFINITE) ? st : nullptr,
                     k, make_launch(p, p->grid_apply, na, keep), s);
     if (e != hipSuccess) return fail_hip(e, "launching the Adam kernel");
     if (ev) (void)hipEventRecord(*ev++, s);

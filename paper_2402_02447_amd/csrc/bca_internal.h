@@ -93,9 +93,13 @@ struct StepState {
 hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, double* partials, int32_t* status,
                          const Launch& L, hipStream_t stream);
 // norms/coefs/status may alias plan scratch.  thresholds == nullptr: norms only.
+// bucket_sq (may be null) receives the buckets' fp64 sums of squares.
 hipError_t launch_finalize(const double* partials, const uint32_t* bucket_chunk_off, uint32_t b0, uint32_t b1,
-                           const float* thresholds, float* norms, float* coefs, int32_t* status,
+                           const float* thresholds, float* norms, float* coefs, int32_t* status, double* bucket_sq,
                            hipStream_t stream);
+// One coefficient for all buckets from the whole-gradient norm and the single threshold *c.
+hipError_t launch_whole_coef(const double* bucket_sq, uint32_t n_buckets, const float* c, float* whole_norm,
+                             float* coefs, int32_t* status, hipStream_t stream);
 hipError_t launch_coefs(uint32_t b0, uint32_t b1, const float* thresholds, const float* norms, float* coefs,
                         int32_t* status, hipStream_t stream);
 hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, const Launch& L,
@@ -142,7 +146,8 @@ struct bca_plan {
   uint32_t* d_ctl = nullptr;
   // device memory owned by the plan
   double* d_partials = nullptr;
-  float* d_norms = nullptr;
+  float* d_norms = nullptr;        // n_buckets + 1 (the last one: whole-gradient norm)
+  double* d_bucket_sq = nullptr;   // n_buckets
   float* d_coefs = nullptr;
   int32_t* d_status = nullptr;
   // per-kernel timing of the fused call: 1 + 3 * groups events per profiled call

@@ -289,7 +289,8 @@ __device__ __forceinline__ float clip_coef(float norm, float c, int32_t& status)
 __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ partials,
                                                       const uint32_t* __restrict__ bucket_chunk_off, uint32_t b0,
                                                       const float* __restrict__ thresholds, float* __restrict__ norms,
-                                                      float* __restrict__ coefs, int32_t* status) {
+                                                      float* __restrict__ coefs, int32_t* status,
+                                                      double* __restrict__ bucket_sq) {
   __shared__ double s_w[kWaves];
   const uint32_t b = b0 + blockIdx.x;
   const uint64_t lo = (uint64_t)bucket_chunk_off[b] * kWaves, hi = (uint64_t)bucket_chunk_off[b + 1] * kWaves;
@@ -302,6 +303,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
     const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
     const float norm = (float)sqrt(tot);
     norms[b] = norm;
+    if (bucket_sq != nullptr) bucket_sq[b] = tot;
     if (thresholds != nullptr) {
       int32_t st = 0;
       const float coef = clip_coef(norm, thresholds[b], st);
@@ -309,6 +311,31 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
       if (st != 0 && status != nullptr) atomicOr(status, st);
     }
   }
+}
+
+// Whole-gradient clipping (Sec. 3.2's baselines): the buckets' sums of squares
+// are added in index order in fp64, the clipping rule of Sec. 2.3 is applied
+// once with the single threshold *c, and every bucket gets that coefficient.
+// One workgroup; ORs its status bits into *status.
+__global__ __launch_bounds__(kBlock) void k_whole_coef(const double* __restrict__ bucket_sq, uint32_t n_buckets,
+                                                        const float* __restrict__ c, float* __restrict__ whole_norm,
+                                                        float* __restrict__ coefs, int32_t* status) {
+  __shared__ double s_w[kWaves];
+  __shared__ float s_coef;
+  double s = 0.0;
+  for (uint32_t b = threadIdx.x; b < n_buckets; b += kBlock) s += bucket_sq[b];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float norm = (float)sqrt(((s_w[0] + s_w[1]) + s_w[2]) + s_w[3]);
+    int32_t st = 0;
+    s_coef = clip_coef(norm, *c, st);
+    *whole_norm = norm;
+    if (st != 0) atomicOr(status, st);
+  }
+  __syncthreads();
+  for (uint32_t b = threadIdx.x; b < n_buckets; b += kBlock) coefs[b] = s_coef;
 }
 
 // Coefficients from norms the caller supplies (unfused path).  One workgroup;
@@ -801,11 +828,18 @@ hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const u
 }
 
 hipError_t launch_finalize(const double* partials, const uint32_t* bucket_chunk_off, uint32_t b0, uint32_t b1,
-                           const float* thresholds, float* norms, float* coefs, int32_t* status,
+                           const float* thresholds, float* norms, float* coefs, int32_t* status, double* bucket_sq,
                            hipStream_t stream) {
   if (b1 <= b0) return hipSuccess;
   hipLaunchKernelGGL(k_finalize, dim3(b1 - b0), dim3(kBlock), 0, stream, partials, bucket_chunk_off, b0, thresholds,
-                     norms, coefs, status);
+                     norms, coefs, status, bucket_sq);
+  return hipGetLastError();
+}
+
+hipError_t launch_whole_coef(const double* bucket_sq, uint32_t n_buckets, const float* c, float* whole_norm,
+                             float* coefs, int32_t* status, hipStream_t stream) {
+  hipLaunchKernelGGL(k_whole_coef, dim3(1), dim3(kBlock), 0, stream, bucket_sq, n_buckets, c, whole_norm, coefs,
+                     status);
   return hipGetLastError();
 }
 

@@ -97,3 +97,28 @@ def test_bert_large_4mib_20_steps_full_size():
     assert 0.4 < frac < 0.6, frac        # about half of the buckets clip
     print("[20 steps] worst", worst, flush=True)
     dev.close()
+
+
+def test_bert_large_whole_gradient_clipping_full_size():
+    # the paper's baseline (clip the whole gradient once, Sec. 3.2) on the 50 MiB layout
+    w = W.config_bert_large()
+    lay = w.layout
+    g, p, m, v = w.grads(), w.params(), w.exp_avg(), w.exp_avg_sq()
+    dev = Device(lay, g, p, m, v)
+    import torch
+    norms = torch.zeros(lay.n_buckets + 1, dtype=torch.float32, device="cuda")
+    dc = torch.tensor([1.0], dtype=torch.float32, device="cuda")
+    dev.plan.bucket_clip_adam(dc, hyper(w.hyper), w.first_step, B.BCA_CLIP_WHOLE_GRADIENT, norms, dev.coefs, dev.status)
+    dev.sync()
+    op, om, ov = f64(p), f64(m), f64(v)
+    onorms, owhole, ocoef, ost = oracle.whole_clip_adam(lay, g, op, om, ov, 1.0, step=w.first_step, **hp_kwargs(w.hyper))
+    gn = norms.cpu().numpy()
+    check_norms(gn[:-1], onorms)
+    check_norms(gn[-1:], np.asarray([owhole]))
+    assert ocoef < 1 and int(dev.status.item()) == ost == 0
+    assert np.all(dev.coefs.cpu().numpy() == dev.coefs.cpu().numpy()[0])
+    check_state("p", to_host(dev.p), op)
+    check_state("m", to_host(dev.m), om)
+    check_state("v", to_host(dev.v), ov, strict_rel=True)
+    print(f"[whole] norm {owhole:.4f} coef {ocoef:.6f}", flush=True)
+    dev.close()

@@ -496,3 +496,59 @@ def test_random_layouts_all_modes(seed):
     run_fused(lay, g, p, m, v, thr, hp, step, B.BCA_SKIP_STEP_ON_NONFINITE, offsets=offsets, group_bytes=gb)
     run_fused(lay, g, p, m, v, thr, hp, step, 0, offsets=offsets, group_bytes=gb, tune_flags=B.BCA_TUNE_MULTI_LAUNCH)
     run_unfused(lay, g, p, m, v, thr, hp, step, offsets=offsets)
+
+
+# ------------------------------------------------------------------ whole-gradient clipping (the paper's baselines)
+
+
+def run_whole(layout, g, p, m, v, c, hp, step, flags=0, offsets=None, **tuning):
+    dev = Device(layout, g, p, m, v, offsets, **tuning)
+    nb = layout.n_buckets
+    norms = torch.full((nb + 1,), -1.0, dtype=torch.float32, device="cuda")
+    dc = torch.tensor([c], dtype=torch.float32, device="cuda")
+    dev.plan.bucket_clip_adam(dc, hyper(hp), step, flags | B.BCA_CLIP_WHOLE_GRADIENT, norms, dev.coefs, dev.status)
+    dev.sync()
+    og = [x.copy() for x in g]
+    op, om, ov = f64(p), f64(m), f64(v)
+    onorms, owhole, ocoef, ost = oracle.whole_clip_adam(layout, og, op, om, ov, c, step=step,
+                                                        write_back=bool(flags & B.BCA_WRITE_BACK_GRADS),
+                                                        **hp_kwargs(hp))
+    gn = norms.cpu().numpy()
+    check_norms(gn[:nb], onorms)
+    check_norms(gn[nb:], np.asarray([owhole]))
+    gcoef = dev.coefs.cpu().numpy()
+    assert np.all(gcoef == gcoef[0]) if nb else True
+    assert gcoef[0] == pytest.approx(ocoef, rel=2e-5)
+    assert int(dev.status.item()) == ost
+    check_state("p", to_host(dev.p), op)
+    check_state("m", to_host(dev.m), om)
+    check_state("v", to_host(dev.v), ov, strict_rel=True)
+    if flags & B.BCA_WRITE_BACK_GRADS:
+        check_scaled_grads(to_host(dev.g), og, g)
+    else:
+        assert bits_equal(to_host(dev.g), g)
+    dev.close()
+    return ocoef
+
+
+@pytest.mark.parametrize("kind", ["base", "fp16", "multistep"])
+def test_whole_gradient_clipping_vs_oracle(kind):
+    w = small_bert(kind)
+    p, m, v = state_of(w)
+    g = w.grads()
+    whole = float(np.sqrt(np.sum(oracle.bucket_norms(w.layout, g) ** 2)))
+    assert run_whole(w.layout, g, p, m, v, 0.3 * whole, w.hyper, w.first_step) < 1            # clips
+    assert run_whole(w.layout, g, p, m, v, 0.3 * whole, w.hyper, w.first_step, B.BCA_WRITE_BACK_GRADS) < 1
+    assert run_whole(w.layout, g, p, m, v, 3.0 * whole, w.hyper, w.first_step, B.BCA_WRITE_BACK_GRADS) == 1   # does not
+    assert run_whole(w.layout, g, p, m, v, 0.5 * whole, w.hyper, w.first_step, tune_flags=B.BCA_TUNE_MULTI_LAUNCH) < 1
+
+
+def test_whole_gradient_clipping_adversarial_layouts():
+    for name, (lay, offsets) in adversarial_cases().items():
+        numels = [int(n) for n in lay.tensor_numel]
+        g = W.normal_tensors(numels, 9, "g", 1e-2, threads=1)
+        p = W.normal_tensors(numels, 9, "p", 0.02, threads=1)
+        m = W.normal_tensors(numels, 9, "m", 3e-3, threads=1)
+        v = W.warm_second_moment(numels, 9, threads=1)
+        whole = float(np.sqrt(np.sum(oracle.bucket_norms(lay, g) ** 2)))
+        run_whole(lay, g, p, m, v, max(0.2 * whole, 1e-6), W.Hyper(), 5, B.BCA_WRITE_BACK_GRADS, offsets=offsets)

@@ -15,7 +15,8 @@ import pytest
 from oracle import build as obuild
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PIN_TESTS = ["tests/test_oracle_half.py", "tests/test_oracle_norm_clip.py", "tests/test_oracle_adam.py"]
+PIN_TESTS = ["tests/test_oracle_half.py", "tests/test_oracle_norm_clip.py", "tests/test_oracle_adam.py",
+             "tests/test_oracle_whole_clip.py"]
 
 MUTANTS = [
     ("norm: sum of |x| instead of squares", "s += x * x;", "s += std::fabs(x);"),
@@ -58,6 +59,11 @@ MUTANTS = [
      "adam_element(gdt == GRAD_F16 ? half_bits_to_double(float_to_half_bits((float)ghat)) : (double)(float)ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);\n          if (write_back"),
     ("fused: write-back always on", "if (write_back && coefs[b] != 1.0f)", "if (coefs[b] != 1.0f)"),
     ("fused: skip flag ignored", "if (!(skip_on_nonfinite && (status & ORC_STATUS_NONFINITE))) {", "if (true) {"),
+    ("whole: sum of squares restarts at every bucket", "total += s;", "total = s;"),
+    ("whole: square root dropped", "const double whole = std::sqrt(total);", "const double whole = total;"),
+    ("whole: Adam sees the unscaled gradient", "const double ghat = static_cast<double>(coef) * load_grad(grads[t], gdt, i);",
+     "const double ghat = load_grad(grads[t], gdt, i);"),
+    ("whole: per-bucket norms not rooted", "if (norms_out) norms_out[b] = std::sqrt(s);", "if (norms_out) norms_out[b] = s;"),
     ("fused: wrong tensor for state", "adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);", "adam_element(ghat, p[t][i], v[t][i], m[t][i], h, bc1, bc2);"),
 ]
 
