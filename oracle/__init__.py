@@ -5,7 +5,8 @@ benchmark's cpu_baseline leg.  It does not import the GPU package and the GPU
 package does not import it.
 
 All functions take plain numpy arrays.  A "tensor list" is a Python list of 1-D
-numpy arrays, one per tensor (float32 or float16 gradients; float64 state).
+numpy arrays, one per tensor (float32 or float16 gradients, or bfloat16 gradients
+wrapped in `Bf16`; float64 state).
 Layout arguments are the five arrays of a bucket layout: tensor_numel,
 bucket_seg_off, seg_tensor, seg_begin, seg_len.
 """
@@ -45,6 +46,10 @@ def _declare(L):
     L.orc_half_to_double.restype = C.c_double
     L.orc_float_to_half.argtypes = [C.c_float]
     L.orc_float_to_half.restype = C.c_uint16
+    L.orc_bf16_to_double.argtypes = [C.c_uint16]
+    L.orc_bf16_to_double.restype = C.c_double
+    L.orc_float_to_bf16.argtypes = [C.c_float]
+    L.orc_float_to_bf16.restype = C.c_uint16
     L.orc_alg1_threshold.argtypes = [C.c_double, C.c_uint64]
     L.orc_alg1_threshold.restype = C.c_double
     L.orc_bucket_norms.argtypes = [C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, dp]
@@ -53,17 +58,25 @@ def _declare(L):
     L.orc_clip_coefs.restype = C.c_int32
     L.orc_bucket_scale.argtypes = [C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, fp]
     L.orc_bucket_scale.restype = None
+    u8p = C.POINTER(C.c_uint8)
     L.orc_adam_step.argtypes = [C.c_uint32, u64p, vpp, C.c_int, vpp, vpp, vpp,
-                                C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64]
+                                C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64, u8p]
     L.orc_adam_step.restype = None
     L.orc_bucket_clip_adam.argtypes = [C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, vpp, vpp, vpp, fp,
                                        C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64,
-                                       C.c_int, C.c_int, dp, fp]
+                                       C.c_int, C.c_int, dp, fp, u8p]
     L.orc_bucket_clip_adam.restype = C.c_int32
     L.orc_whole_clip_adam.argtypes = [C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, vpp, vpp, vpp, C.c_float,
                                       C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64, C.c_int,
-                                      dp, dp, fp]
+                                      dp, dp, fp, u8p]
     L.orc_whole_clip_adam.restype = C.c_int32
+    L.orc_lamb_step.argtypes = [C.c_uint32, u64p, vpp, C.c_int, vpp, vpp, vpp,
+                                C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64, u8p, dp]
+    L.orc_lamb_step.restype = None
+    L.orc_bucket_clip_lamb.argtypes = [C.c_uint32, u64p, C.c_uint32, u64p, u32p, u64p, u64p, vpp, C.c_int, vpp, vpp, vpp,
+                                       fp, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64,
+                                       C.c_int, u8p, dp, fp, dp]
+    L.orc_bucket_clip_lamb.restype = C.c_int32
     L.orc_compare_f32.argtypes = [fp, dp, C.c_uint64, C.c_double, C.c_double, C.c_double, C.c_double, dp]
     L.orc_compare_f32.restype = C.c_uint64
     return L
@@ -85,7 +98,14 @@ def _ptr_array(tensors: Sequence[np.ndarray], dtype) -> "C.Array":
     return arr
 
 
+class Bf16(list):
+    """A tensor list of bfloat16 gradients: 1-D uint16 arrays holding the bit patterns
+    (numpy has no bfloat16 type)."""
+
+
 def _gdt(grads: Sequence[np.ndarray]) -> Tuple[int, type]:
+    if isinstance(grads, Bf16):
+        return 2, np.uint16
     if len(grads) == 0:
         return 0, np.float32
     dt = grads[0].dtype
@@ -94,6 +114,17 @@ def _gdt(grads: Sequence[np.ndarray]) -> Tuple[int, type]:
     if dt == np.float16:
         return 1, np.float16
     raise TypeError(f"gradient dtype {dt} not supported")
+
+
+def _mask(decay, n_tensors: int):
+    """Per-tensor weight-decay mask as (keep-alive array, pointer); None means decay everywhere."""
+    if decay is None:
+        return None, None
+    a = np.ascontiguousarray(decay, dtype=np.uint8)
+    assert a.shape == (n_tensors,)
+    if n_tensors == 0:
+        a = np.zeros(1, np.uint8)
+    return a, _p(a, C.c_uint8)
 
 
 class _Lay:
@@ -125,6 +156,14 @@ def half_to_double(bits: int) -> float:
 
 def float_to_half(x: float) -> int:
     return int(lib().orc_float_to_half(C.c_float(x)))
+
+
+def bf16_to_double(bits: int) -> float:
+    return float(lib().orc_bf16_to_double(int(bits)))
+
+
+def float_to_bf16(x: float) -> int:
+    return int(lib().orc_float_to_bf16(C.c_float(x)))
 
 
 def alg1_threshold(c: float, n_buckets: int) -> float:
@@ -161,22 +200,63 @@ def bucket_scale(layout, grads: List[np.ndarray], coefs: np.ndarray) -> None:
 
 def adam_step(layout_or_numel, grads: Sequence[np.ndarray], p: List[np.ndarray], m: List[np.ndarray],
               v: List[np.ndarray], lr: float, beta1: float, beta2: float, eps: float, weight_decay: float,
-              step: int) -> None:
-    """p, m, v (float64) are updated in place from the stored gradients."""
+              step: int, decay=None) -> None:
+    """p, m, v (float64) are updated in place from the stored gradients.  decay: optional
+    per-tensor mask (non-zero = weight decay applies to that tensor)."""
     numel = getattr(layout_or_numel, "tensor_numel", layout_or_numel)
     numel = np.ascontiguousarray(numel, np.uint64)
     gdt, dt = _gdt(grads)
     for t, n in enumerate(numel):
         assert grads[t].shape[0] == p[t].shape[0] == m[t].shape[0] == v[t].shape[0] == int(n)
+    keep, dm = _mask(decay, numel.shape[0])
     lib().orc_adam_step(numel.shape[0], _p(numel, C.c_uint64), _ptr_array(grads, dt), gdt,
                         _ptr_array(p, np.float64), _ptr_array(m, np.float64), _ptr_array(v, np.float64),
-                        lr, beta1, beta2, eps, weight_decay, int(step))
+                        lr, beta1, beta2, eps, weight_decay, int(step), dm)
+
+
+def lamb_step(layout_or_numel, grads: Sequence[np.ndarray], p: List[np.ndarray], m: List[np.ndarray],
+              v: List[np.ndarray], lr: float, beta1: float, beta2: float, eps: float, weight_decay: float,
+              step: int, decay=None) -> np.ndarray:
+    """LAMB on the stored gradients; p, m, v (float64) updated in place.  Returns the per-tensor trust ratios."""
+    numel = getattr(layout_or_numel, "tensor_numel", layout_or_numel)
+    numel = np.ascontiguousarray(numel, np.uint64)
+    gdt, dt = _gdt(grads)
+    for t, n in enumerate(numel):
+        assert grads[t].shape[0] == p[t].shape[0] == m[t].shape[0] == v[t].shape[0] == int(n)
+    keep, dm = _mask(decay, numel.shape[0])
+    trust = np.ones(max(1, numel.shape[0]), np.float64)
+    lib().orc_lamb_step(numel.shape[0], _p(numel, C.c_uint64), _ptr_array(grads, dt), gdt,
+                        _ptr_array(p, np.float64), _ptr_array(m, np.float64), _ptr_array(v, np.float64),
+                        lr, beta1, beta2, eps, weight_decay, int(step), dm, _p(trust, C.c_double))
+    return trust[:numel.shape[0]]
+
+
+def bucket_clip_lamb(layout, grads: List[np.ndarray], p: List[np.ndarray], m: List[np.ndarray],
+                     v: List[np.ndarray], thresholds: np.ndarray, lr: float, beta1: float, beta2: float,
+                     eps: float, weight_decay: float, step: int, write_back: bool = False, decay=None):
+    """Bucket-wise clipping, then LAMB.  Returns (norms float64, coefs float32, trust float64, status bits)."""
+    la = _Lay(layout)
+    gdt, dt = _gdt(grads)
+    thr = np.ascontiguousarray(thresholds, np.float32)
+    assert thr.shape[0] == la.nb
+    for t in range(la.nt):
+        assert grads[t].shape[0] == p[t].shape[0] == m[t].shape[0] == v[t].shape[0] == int(la.numel[t])
+    norms = np.zeros(max(1, la.nb), np.float64)
+    coefs = np.ones(max(1, la.nb), np.float32)
+    trust = np.ones(max(1, la.nt), np.float64)
+    keep, dm = _mask(decay, la.nt)
+    st = lib().orc_bucket_clip_lamb(C.c_uint32(la.nt), _p(la.numel, C.c_uint64), *la.args(), _ptr_array(grads, dt), gdt,
+                                    _ptr_array(p, np.float64), _ptr_array(m, np.float64), _ptr_array(v, np.float64),
+                                    _p(thr, C.c_float), lr, beta1, beta2, eps, weight_decay, int(step),
+                                    int(write_back), dm, _p(norms, C.c_double), _p(coefs, C.c_float),
+                                    _p(trust, C.c_double))
+    return norms[:la.nb], coefs[:la.nb], trust[:la.nt], int(st)
 
 
 def bucket_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: List[np.ndarray],
                      v: List[np.ndarray], thresholds: np.ndarray, lr: float, beta1: float, beta2: float,
                      eps: float, weight_decay: float, step: int, write_back: bool = False,
-                     skip_on_nonfinite: bool = False) -> Tuple[np.ndarray, np.ndarray, int]:
+                     skip_on_nonfinite: bool = False, decay=None) -> Tuple[np.ndarray, np.ndarray, int]:
     """Fused step.  Returns (norms float64, coefs float32, status bits)."""
     la = _Lay(layout)
     gdt, dt = _gdt(grads)
@@ -186,16 +266,17 @@ def bucket_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: Li
         assert grads[t].shape[0] == p[t].shape[0] == m[t].shape[0] == v[t].shape[0] == int(la.numel[t])
     norms = np.zeros(max(1, la.nb), np.float64)
     coefs = np.ones(max(1, la.nb), np.float32)
+    keep, dm = _mask(decay, la.nt)
     st = lib().orc_bucket_clip_adam(*la.args(), _ptr_array(grads, dt), gdt, _ptr_array(p, np.float64),
                                     _ptr_array(m, np.float64), _ptr_array(v, np.float64), _p(thr, C.c_float),
                                     lr, beta1, beta2, eps, weight_decay, int(step), int(write_back),
-                                    int(skip_on_nonfinite), _p(norms, C.c_double), _p(coefs, C.c_float))
+                                    int(skip_on_nonfinite), _p(norms, C.c_double), _p(coefs, C.c_float), dm)
     return norms[:la.nb], coefs[:la.nb], int(st)
 
 
 def whole_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: List[np.ndarray], v: List[np.ndarray],
                     threshold: float, lr: float, beta1: float, beta2: float, eps: float, weight_decay: float,
-                    step: int, write_back: bool = False) -> Tuple[np.ndarray, float, float, int]:
+                    step: int, write_back: bool = False, decay=None) -> Tuple[np.ndarray, float, float, int]:
     """Whole-gradient clipping + Adam.  Returns (per-bucket norms, whole norm, coefficient, status bits)."""
     la = _Lay(layout)
     gdt, dt = _gdt(grads)
@@ -204,11 +285,12 @@ def whole_clip_adam(layout, grads: List[np.ndarray], p: List[np.ndarray], m: Lis
     norms = np.zeros(max(1, la.nb), np.float64)
     whole = np.zeros(1, np.float64)
     coef = np.ones(1, np.float32)
+    keep, dm = _mask(decay, la.nt)
     st = lib().orc_whole_clip_adam(*la.args(), _ptr_array(grads, dt), gdt, _ptr_array(p, np.float64),
                                    _ptr_array(m, np.float64), _ptr_array(v, np.float64),
                                    C.c_float(float(np.float32(threshold))), lr, beta1, beta2, eps, weight_decay,
                                    int(step), int(write_back), _p(norms, C.c_double), _p(whole, C.c_double),
-                                   _p(coef, C.c_float))
+                                   _p(coef, C.c_float), dm)
     return norms[:la.nb], float(whole[0]), float(coef[0]), int(st)
 
 

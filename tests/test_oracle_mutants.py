@@ -16,7 +16,7 @@ from oracle import build as obuild
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PIN_TESTS = ["tests/test_oracle_half.py", "tests/test_oracle_norm_clip.py", "tests/test_oracle_adam.py",
-             "tests/test_oracle_whole_clip.py"]
+             "tests/test_oracle_whole_clip.py", "tests/test_oracle_bf16.py", "tests/test_oracle_lamb.py"]
 
 MUTANTS = [
     ("norm: sum of |x| instead of squares", "s += x * x;", "s += std::fabs(x);"),
@@ -64,6 +64,26 @@ MUTANTS = [
     ("whole: Adam sees the unscaled gradient", "const double ghat = static_cast<double>(coef) * load_grad(grads[t], gdt, i);",
      "const double ghat = load_grad(grads[t], gdt, i);"),
     ("whole: per-bucket norms not rooted", "if (norms_out) norms_out[b] = std::sqrt(s);", "if (norms_out) norms_out[b] = s;"),
+    ("bf16: subnormal exponent off by one", "std::ldexp(static_cast<double>(frac), -133)", "std::ldexp(static_cast<double>(frac), -134)"),
+    ("bf16: exponent bias of binary16", "std::ldexp(static_cast<double>(128 + frac), expo - 134)", "std::ldexp(static_cast<double>(128 + frac), expo - 22)"),
+    ("bf16: truncation instead of rounding", "const double r = std::nearbyint(std::ldexp(a, -ulp_exp));", "const double r = std::floor(std::ldexp(a, -ulp_exp));"),
+    ("bf16: ties away from zero", "const double r = std::nearbyint(std::ldexp(a, -ulp_exp));", "const double r = std::floor(std::ldexp(a, -ulp_exp) + 0.5);"),
+    ("bf16: scaled gradient stored through binary16 rounding", "g[i] = float_to_bf16_bits(prod);", "g[i] = float_to_bf16_bits((float)half_bits_to_double(float_to_half_bits(prod)));"),
+    ("mask: inverted", "if (decay != nullptr && decay[t] == 0) h.wd = 0.0;", "if (decay != nullptr && decay[t] != 0) h.wd = 0.0;"),
+    ("mask: ignored", "if (decay != nullptr && decay[t] == 0) h.wd = 0.0;", ""),
+    ("mask: indexed by the wrong tensor", "if (decay != nullptr && decay[t] == 0) h.wd = 0.0;", "if (decay != nullptr && decay[t ? t - 1 : 0] == 0) h.wd = 0.0;"),
+    ("lamb: inverted trust ratio", "? p_norm / u_norm : 1.0;", "? u_norm / p_norm : 1.0;"),
+    ("lamb: squared norms in the ratio", "const double p_norm = std::sqrt(sum_pp), u_norm = std::sqrt(sum_uu);", "const double p_norm = sum_pp, u_norm = sum_uu;"),
+    ("lamb: decay term left out of the update norm", "sum_uu += u[i] * u[i];", "sum_uu += (u[i] - h.wd * p[i]) * (u[i] - h.wd * p[i]);"),
+    ("lamb: decay term left out of the update", "u[i] = mhat / (std::sqrt(vhat) + h.eps) + h.wd * p[i];", "u[i] = mhat / (std::sqrt(vhat) + h.eps);"),
+    ("lamb: no guard for zero norms", "(p_norm > 0.0 && u_norm > 0.0) ? p_norm / u_norm : 1.0;", "p_norm / u_norm;"),
+    ("lamb: trust ratio not applied", "p[i] = p[i] - h.lr * trust * u[i];", "p[i] = p[i] - h.lr * u[i];"),
+    ("lamb: no bias correction", "    const double mhat = m[i] / bc1;", "    const double mhat = m[i];"),
+    ("lamb: eps inside the root", "u[i] = mhat / (std::sqrt(vhat) + h.eps)", "u[i] = mhat / (std::sqrt(vhat + h.eps))"),
+    ("lamb: max norm instead of Euclidean", "sum_pp += p[i] * p[i];", "sum_pp = std::fmax(sum_pp, p[i] * p[i]);"),
+    ("clip+lamb: LAMB sees the unscaled gradient", "ghat[t][i] = static_cast<double>(coefs[b]) * load_grad(grads[t], gdt, i);", "ghat[t][i] = load_grad(grads[t], gdt, i);"),
+    ("clip+lamb: one coefficient for all buckets", "ghat[t][i] = static_cast<double>(coefs[b]) * load_grad(grads[t], gdt, i);", "ghat[t][i] = static_cast<double>(coefs[0]) * load_grad(grads[t], gdt, i);"),
+    ("clip+lamb: write-back always on", "if (write_back && coefs[b] != 1.0f) store_scaled_grad(grads[t], gdt, i, coefs[b]);\n      }\n    }\n  const Adam h_all", "if (coefs[b] != 1.0f) store_scaled_grad(grads[t], gdt, i, coefs[b]);\n      }\n    }\n  const Adam h_all"),
     ("fused: wrong tensor for state", "adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);", "adam_element(ghat, p[t][i], v[t][i], m[t][i], h, bc1, bc2);"),
 ]
 

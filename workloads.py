@@ -216,6 +216,33 @@ def student_t_fp16_tensors(numels, seed: int, scale: float, threads: int = 8) ->
     return _fill(numels, one, threads)
 
 
+def float32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Input preparation only: the bfloat16 bit patterns (uint16) nearest to fp32 values,
+    ties to even; NaN stays NaN.  bfloat16 is the upper half of a binary32."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    rounded = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    nan = np.isnan(a)
+    if nan.any():
+        rounded[nan] = ((u[nan] >> 16) | 0x40).astype(np.uint16)
+    return rounded
+
+
+def bf16_bits_to_float32(bits: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def normal_bf16_tensors(numels, seed: int, sigma: float, threads: int = 8) -> List[np.ndarray]:
+    """N(0, sigma^2) rounded to bfloat16, as uint16 bit patterns."""
+    return [float32_to_bf16_bits(x) for x in normal_tensors(numels, seed, "g", sigma, threads)]
+
+
+def bert_decay_mask(vocab: int, hidden: int, n_layers: int, ffn: int, max_pos: int) -> np.ndarray:
+    """The usual BERT exemption: weight decay on weight matrices and embeddings,
+    none on biases and LayerNorm gains/offsets.  uint8 [n_tensors], 1 = decay."""
+    names = [n for n, _ in bert_tensor_list(vocab, hidden, n_layers, ffn, max_pos)]
+    return np.asarray([0 if (n.endswith(".b") or ".ln" in n) else 1 for n in names], np.uint8)
+
+
 def scale_buckets_inplace(layout: Layout, tensors: List[np.ndarray], which: Sequence[int], factor: float):
     for b in which:
         for t, beg, ln in layout.segments_of(b):
