@@ -15,7 +15,7 @@
  *     host; outputs are valid once the caller has synchronised the stream.
  *   - Return value: 0 on success, a negative BCA_ERR_* otherwise.  On error
  *     nothing has been enqueued.  bca_last_error() gives a message.
- *   - Gradients are fp32 or fp16; parameters and both moments are fp32.
+ *   - Gradients are fp32, fp16 or bf16; parameters and both moments are fp32.
  *   - The caller owns every gradient / parameter / moment / threshold / norm /
  *     coefficient / status buffer.  The library owns only the plan (chunk
  *     table, partial sums, per-bucket scratch), freed by bca_plan_destroy.
@@ -36,6 +36,7 @@ typedef struct bca_plan bca_plan; /* opaque */
 /* gradient storage type */
 #define BCA_GRAD_F32 0
 #define BCA_GRAD_F16 1
+#define BCA_GRAD_BF16 2 /* bfloat16: the upper half of a binary32 */
 
 /* error codes */
 #define BCA_OK 0
@@ -105,6 +106,7 @@ typedef struct bca_tuning {
 /* which chunk table an introspection call looks at */
 #define BCA_TABLE_NORM 0
 #define BCA_TABLE_APPLY 1
+#define BCA_TABLE_LAMB 2 /* the fine cut again, tensor by tensor (bucket-major order does not apply) */
 
 /* ---- plan -----------------------------------------------------------------
  * A plan records the bucket layout of Alg. 1's G = [G_1 ... G_B]: B buckets,
@@ -130,18 +132,27 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
 int bca_plan_bind(bca_plan* plan, void* const* grads, float* const* params, float* const* exp_avg,
                   float* const* exp_avg_sq);
 
+/* Per-tensor weight-decay mask: decay is a HOST array of n_tensors bytes, non-zero =
+ * weight decay applies to that tensor, zero = exempt (the usual treatment of biases
+ * and normalisation weights; the paper tunes one weight decay, App. A Table 4, and
+ * does not say which tensors it covers).  NULL restores the default, decay everywhere.
+ * Affects adam_step, bucket_clip_adam, lamb_step and bucket_clip_lamb.  May be called
+ * before or after bca_plan_bind; on a bound plan it is synchronous (rewrites the tables). */
+int bca_plan_set_decay_mask(bca_plan* plan, const uint8_t* decay /*HOST [n_tensors] or NULL*/);
+
 void bca_plan_destroy(bca_plan* plan);
 
-/* Introspection of the host-side plan (no GPU needed).  `table` is BCA_TABLE_NORM
- * or BCA_TABLE_APPLY: the layout is cut twice, coarsely for the squared-norm pass
- * and finely for the passes that also write. */
+/* Introspection of the host-side plan (no GPU needed).  `table` is BCA_TABLE_NORM,
+ * BCA_TABLE_APPLY or BCA_TABLE_LAMB: the layout is cut coarsely for the squared-norm
+ * pass, finely for the passes that also write, and finely again in tensor-major
+ * order for LAMB. */
 uint32_t bca_plan_num_buckets(const bca_plan* plan);
 uint32_t bca_plan_num_groups(const bca_plan* plan);
 uint32_t bca_plan_num_chunks(const bca_plan* plan, int table);
 /* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
 int bca_plan_chunk_info(const bca_plan* plan, int table, uint32_t i, uint32_t* tensor, uint64_t* begin,
                         uint32_t* len, uint32_t* bucket);
-/* Chunks of bucket b are [first, first + count). */
+/* Chunks of bucket b are [first, first + count); for BCA_TABLE_LAMB b is a tensor index. */
 int bca_plan_bucket_chunks(const bca_plan* plan, int table, uint32_t b, uint32_t* first, uint32_t* count);
 
 /* ---- compute --------------------------------------------------------------*/
@@ -186,6 +197,22 @@ int adam_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, void* 
  * pipelining of bucket groups). */
 int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
                      uint64_t step, uint32_t flags, float* norms, float* coefs, int32_t* status, void* stream);
+
+/* LAMB in place of Adam (the optimizer the paper compares Adam with, Sec. 2.2, Sec. 5,
+ * App. A; taken as published by You et al. 2020, Alg. 2, with bias correction):
+ *   m, v as in adam_step;  u = (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + wd * p
+ *   trust_t = ||p_t|| / ||u_t|| per tensor t (Euclidean, p before the update; 1 if either
+ *   norm is 0);  p <- p - lr * trust_t * u.
+ * lamb_step reads the gradients as stored.  bucket_clip_lamb first clips bucket by bucket
+ * exactly as bucket_clip_adam does (thresholds, norms, coefs, status as there) and feeds
+ * LAMB the scaled gradient formed in registers; flags: BCA_WRITE_BACK_GRADS only.
+ * trust (DEVICE [n_tensors], may be NULL) receives the ratios.  Three sweeps: squared
+ * norms (clip only), moments + per-tensor sums, parameter update. */
+int lamb_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, float* trust /*DEVICE or NULL*/,
+              void* stream);
+int bucket_clip_lamb(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
+                     uint64_t step, uint32_t flags, float* norms, float* coefs, float* trust, int32_t* status,
+                     void* stream);
 
 /* ---- per-kernel timing (for benchmarks) -----------------------------------
  * With profiling on, bucket_clip_adam records HIP events on `stream` around each

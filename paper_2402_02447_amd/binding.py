@@ -15,20 +15,21 @@ from typing import Optional, Sequence
 
 import numpy as np
 
-BCA_GRAD_F32, BCA_GRAD_F16 = 0, 1
+BCA_GRAD_F32, BCA_GRAD_F16, BCA_GRAD_BF16 = 0, 1, 2
 BCA_STATUS_NONFINITE, BCA_STATUS_BAD_THRESHOLD = 1, 2
 BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE, BCA_CLIP_WHOLE_GRADIENT = 1, 2, 4
 BCA_TUNE_MULTI_LAUNCH, BCA_TUNE_STAGE_TABLE_LDS, BCA_TUNE_TICKETS = 1, 2, 4
 BCA_STATUS_TIMEOUT = 4
-BCA_TABLE_NORM, BCA_TABLE_APPLY = 0, 1
+BCA_TABLE_NORM, BCA_TABLE_APPLY, BCA_TABLE_LAMB = 0, 1, 2
 
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN"}
 
-EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_destroy", "bca_plan_num_buckets", "bca_plan_num_groups",
-           "bca_plan_num_chunks",
-           "bca_plan_chunk_info", "bca_plan_bucket_chunks", "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step",
-           "bucket_clip_adam", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error", "bca_version"]
+EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_destroy", "bca_plan_num_buckets",
+           "bca_plan_num_groups", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
+           "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
+           "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error",
+           "bca_version"]
 
 
 class BcaError(RuntimeError):
@@ -92,6 +93,7 @@ def load_library():
     L.bca_plan_create.argtypes = [C.POINTER(vp), i32, u32, C.POINTER(u64), u32, C.POINTER(u64), C.POINTER(_Segment), i32,
                                   C.POINTER(_Tuning)]
     L.bca_plan_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+    L.bca_plan_set_decay_mask.argtypes = [vp, C.POINTER(C.c_uint8)]
     L.bca_plan_destroy.argtypes = [vp]
     L.bca_plan_destroy.restype = None
     L.bca_plan_num_buckets.argtypes = [vp]
@@ -107,6 +109,8 @@ def load_library():
     L.bucket_clip.argtypes = [vp, u32, u32, vp, vp, vp, vp, vp]
     L.adam_step.argtypes = [vp, C.POINTER(_Adam), u64, vp]
     L.bucket_clip_adam.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp]
+    L.lamb_step.argtypes = [vp, C.POINTER(_Adam), u64, vp, vp]
+    L.bucket_clip_lamb.argtypes = [vp, vp, C.POINTER(_Adam), u64, u32, vp, vp, vp, vp, vp]
     L.bca_plan_profile.argtypes = [vp, u32]
     L.bca_plan_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]
     L.bca_copy_bytes.argtypes = [vp, vp, u64, vp]
@@ -232,6 +236,17 @@ class Plan:
         _check(self._L.bca_plan_bind(self._h, arr(grads), arr(params), arr(exp_avg), arr(exp_avg_sq)))
         self._keep = (grads, params, exp_avg, exp_avg_sq)     # keep the tensors alive while bound
 
+    def set_decay_mask(self, decay) -> None:
+        """decay: one entry per tensor, non-zero = weight decay applies; None = everywhere."""
+        if decay is None:
+            _check(self._L.bca_plan_set_decay_mask(self._h, None))
+            return
+        a = np.ascontiguousarray(decay, dtype=np.uint8)
+        if a.shape != (self.n_tensors,):
+            raise ValueError(f"expected {self.n_tensors} mask entries, got {a.shape}")
+        buf = (C.c_uint8 * max(1, self.n_tensors)).from_buffer_copy(a.tobytes() or b"\0")
+        _check(self._L.bca_plan_set_decay_mask(self._h, buf))
+
     # -- per-kernel timing of the fused call
     def profile(self, max_calls: int) -> None:
         _check(self._L.bca_plan_profile(self._h, max_calls))
@@ -264,3 +279,13 @@ class Plan:
         h = hp._c()
         _check(self._L.bucket_clip_adam(self._h, _ptr(thresholds), C.byref(h), step, flags, _ptr(norms), _ptr(coefs),
                                         _ptr(status), _stream(stream)))
+
+    def lamb_step(self, hp: AdamHyper, step: int, trust=None, stream=None) -> None:
+        h = hp._c()
+        _check(self._L.lamb_step(self._h, C.byref(h), step, _ptr(trust), _stream(stream)))
+
+    def bucket_clip_lamb(self, thresholds, hp: AdamHyper, step: int, flags: int = 0, norms=None, coefs=None,
+                         trust=None, status=None, stream=None) -> None:
+        h = hp._c()
+        _check(self._L.bucket_clip_lamb(self._h, _ptr(thresholds), C.byref(h), step, flags, _ptr(norms), _ptr(coefs),
+                                        _ptr(trust), _ptr(status), _stream(stream)))

@@ -26,6 +26,8 @@ int fail_hip(hipError_t e, const char* what) {
   return fail(BCA_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+uint64_t grad_bytes(int gdt) { return gdt == BCA_GRAD_F32 ? 4 : 2; }
+
 // Makes the plan's device current for the lifetime of the object.
 struct DeviceGuard {
   int prev = -1;
@@ -109,13 +111,47 @@ void build_table(Table* t, uint32_t chunk_elems, uint32_t n_buckets, const uint6
   t->bucket_off[n_buckets] = (uint32_t)t->chunks.size();
 }
 
+// The same cut, tensor by tensor: tensor t's pieces in the order of their position in
+// the tensor, so that the chunks (and partial sums) of a tensor are contiguous.  A
+// chunk still lies in one bucket, because the clip coefficient is the bucket's.
+void build_tensor_table(Table* t, std::vector<uint32_t>* tensor_off, uint32_t chunk_elems, uint32_t n_tensors,
+                        uint32_t n_buckets, const uint64_t* seg_off, const bca_segment* segs) {
+  const uint64_t C = chunk_elems;
+  t->chunk_elems = chunk_elems;
+  t->chunks.clear();
+  t->bucket_off.clear();
+  struct Piece {
+    uint64_t begin, len;
+    uint32_t bucket;
+  };
+  std::vector<std::vector<Piece>> per_tensor(n_tensors);
+  for (uint32_t b = 0; b < n_buckets; ++b)
+    for (uint64_t s = seg_off[b]; s < seg_off[b + 1]; ++s)
+      if (segs[s].len) per_tensor[segs[s].tensor].push_back(Piece{segs[s].begin, segs[s].len, b});
+  tensor_off->assign(n_tensors + 1, 0);
+  for (uint32_t ti = 0; ti < n_tensors; ++ti) {
+    (*tensor_off)[ti] = (uint32_t)t->chunks.size();
+    auto& v = per_tensor[ti];
+    std::sort(v.begin(), v.end(), [](const Piece& a, const Piece& b) { return a.begin < b.begin; });
+    for (const Piece& pc : v) {
+      uint64_t pos = pc.begin;
+      const uint64_t end = pc.begin + pc.len;
+      while (pos < end) {
+        const uint64_t stop = std::min(end, (pos / C + 1) * C);
+        t->chunks.push_back(ChunkInfo{ti, (uint32_t)(stop - pos), pos, pc.bucket});
+        pos = stop;
+      }
+    }
+  }
+  (*tensor_off)[n_tensors] = (uint32_t)t->chunks.size();
+}
+
 // Consecutive buckets are put in one group until their gradients exceed
 // group_bytes (0: the library default).  A group has at least one bucket.
 void build_groups(bca_plan* p, uint64_t group_bytes, const uint64_t* seg_off, const bca_segment* segs) {
   p->groups.clear();
-  const uint64_t gsize0 = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
-  if (group_bytes == 0) group_bytes = kDefaultGroupElems * gsize0;
-  const uint64_t gsize = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+  const uint64_t gsize = grad_bytes(p->grad_dtype);
+  if (group_bytes == 0) group_bytes = kDefaultGroupElems * gsize;
   uint32_t first = 0;
   uint64_t acc = 0;
   for (uint32_t b = 0; b < p->n_buckets; ++b) {
@@ -165,7 +201,7 @@ void free_device(bca_plan* p) {
   if (p->device < 0) return;
   DeviceGuard g(p->device);
   free_profile(p);
-  for (Table* t : {&p->norm_tab, &p->apply_tab}) {
+  for (Table* t : {&p->norm_tab, &p->apply_tab, &p->lamb_tab}) {
     if (t->d_chunks) (void)hipFree(t->d_chunks);
     if (t->d_bucket_off) (void)hipFree(t->d_bucket_off);
     t->d_chunks = nullptr, t->d_bucket_off = nullptr;
@@ -179,6 +215,11 @@ void free_device(bca_plan* p) {
   if (p->d_norms) (void)hipFree(p->d_norms);
   if (p->d_bucket_sq) (void)hipFree(p->d_bucket_sq);
   p->d_bucket_sq = nullptr;
+  if (p->d_tensor_off) (void)hipFree(p->d_tensor_off);
+  if (p->d_lamb_sums) (void)hipFree(p->d_lamb_sums);
+  if (p->d_trust) (void)hipFree(p->d_trust);
+  if (p->d_lamb_scale) (void)hipFree(p->d_lamb_scale);
+  p->d_tensor_off = nullptr, p->d_lamb_sums = nullptr, p->d_trust = nullptr, p->d_lamb_scale = nullptr;
   if (p->d_coefs) (void)hipFree(p->d_coefs);
   if (p->d_status) (void)hipFree(p->d_status);
   p->d_partials = nullptr, p->d_norms = nullptr, p->d_coefs = nullptr, p->d_status = nullptr;
@@ -187,27 +228,39 @@ void free_device(bca_plan* p) {
 hipError_t alloc_table(Table* t, uint32_t n_buckets) {
   const size_t nc = std::max<size_t>(t->chunks.size(), 1);
   hipError_t e = hipMalloc((void**)&t->d_chunks, nc * sizeof(Chunk));
+  if (t->bucket_off.empty()) return e;  // the tensor-major table has no bucket offsets
   if (e == hipSuccess) e = hipMalloc((void**)&t->d_bucket_off, (n_buckets + 1) * sizeof(uint32_t));
   if (e == hipSuccess)
     e = hipMemcpy(t->d_bucket_off, t->bucket_off.data(), (n_buckets + 1) * sizeof(uint32_t), hipMemcpyHostToDevice);
   return e;
 }
 
-hipError_t upload_table(const bca_plan* p, Table* t, void* const* grads, float* const* params, float* const* exp_avg,
-                        float* const* exp_avg_sq) {
-  const uint64_t gsize = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+// Writes a table's device copy from the bound pointers and the decay mask.
+hipError_t upload_table(const bca_plan* p, Table* t) {
+  const uint64_t gsize = grad_bytes(p->grad_dtype);
   std::vector<Chunk> table(std::max<size_t>(t->chunks.size(), 1));
   memset(table.data(), 0, table.size() * sizeof(Chunk));
   for (size_t i = 0; i < t->chunks.size(); ++i) {
     const ChunkInfo& c = t->chunks[i];
-    table[i].g = (uint64_t)(uintptr_t)grads[c.tensor] + c.begin * gsize;
-    table[i].p = (uint64_t)(uintptr_t)params[c.tensor] + c.begin * 4;
-    table[i].m = (uint64_t)(uintptr_t)exp_avg[c.tensor] + c.begin * 4;
-    table[i].v = (uint64_t)(uintptr_t)exp_avg_sq[c.tensor] + c.begin * 4;
+    table[i].g = p->bound_g[c.tensor] + c.begin * gsize;
+    table[i].p = p->bound_p[c.tensor] + c.begin * 4;
+    table[i].m = p->bound_m[c.tensor] + c.begin * 4;
+    table[i].v = p->bound_v[c.tensor] + c.begin * 4;
     table[i].len = c.len;
     table[i].bucket = c.bucket;
+    table[i].tensor = c.tensor;
+    table[i].flags = p->decay[c.tensor] ? 0u : kChunkNoDecay;
   }
   return hipMemcpy(t->d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+}
+
+// Kernels enqueued earlier on any stream may still be reading the old tables, so
+// wait for them before the (host-synchronous) copies.
+hipError_t upload_all_tables(bca_plan* p) {
+  hipError_t e = hipDeviceSynchronize();
+  for (Table* t : {&p->norm_tab, &p->apply_tab, &p->lamb_tab})
+    if (e == hipSuccess) e = upload_table(p, t);
+  return e;
 }
 
 int check_ready(const bca_plan* p) {
@@ -243,6 +296,7 @@ int make_adam_constants(const bca_adam* hp, uint64_t step, AdamK* k) {
   k->eps = (float)hp->eps;
   k->neg_lr = (float)(-hp->lr);
   k->wd = (float)hp->weight_decay;
+  k->lr = hp->lr;
   return BCA_OK;
 }
 
@@ -276,7 +330,8 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   if (!bucket_seg_off) return fail(BCA_ERR_NULL, "bucket_seg_off is NULL");
   if (n_tensors && !tensor_numel) return fail(BCA_ERR_NULL, "tensor_numel is NULL");
   if (n_buckets == 0) return fail(BCA_ERR_LAYOUT, "a plan needs at least one bucket");
-  if (grad_dtype != BCA_GRAD_F32 && grad_dtype != BCA_GRAD_F16) return fail(BCA_ERR_DTYPE, "unknown gradient type");
+  if (grad_dtype != BCA_GRAD_F32 && grad_dtype != BCA_GRAD_F16 && grad_dtype != BCA_GRAD_BF16)
+    return fail(BCA_ERR_DTYPE, "unknown gradient type");
   if (bucket_seg_off[n_buckets] && !segments) return fail(BCA_ERR_NULL, "segments is NULL");
   if (device < -1) return fail(BCA_ERR_RANGE, "device must be >= 0, or -1 for a host-only plan");
   uint32_t chunk_norm = kDefaultChunkNorm, chunk_apply = kDefaultChunkApply, unroll = 0;
@@ -307,8 +362,10 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   p->unroll_apply = unroll ? unroll : (chunk_apply >= 4096 ? 4u : chunk_apply >= 2048 ? 2u : 1u);
   p->tune_flags = tuning ? tuning->flags : 0;
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
+  p->decay.assign(n_tensors, 1);
   build_table(&p->norm_tab, chunk_norm, n_buckets, bucket_seg_off, segments);
   build_table(&p->apply_tab, chunk_apply, n_buckets, bucket_seg_off, segments);
+  build_tensor_table(&p->lamb_tab, &p->tensor_off, chunk_apply, n_tensors, n_buckets, bucket_seg_off, segments);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
   build_work(p);
   // A launch holds at most 2^32 threads: with 256 per workgroup that is 2^24 workgroups.
@@ -341,8 +398,16 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
     }
     const size_t np = std::max<size_t>(p->norm_tab.chunks.size(), 1) * kWaves;
     const size_t nb = n_buckets;
+    const size_t nl = std::max<size_t>(p->lamb_tab.chunks.size(), 1), nt = std::max<size_t>(n_tensors, 1);
     if ((e = alloc_table(&p->norm_tab, n_buckets)) != hipSuccess ||
         (e = alloc_table(&p->apply_tab, n_buckets)) != hipSuccess ||
+        (e = alloc_table(&p->lamb_tab, n_buckets)) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_tensor_off, (n_tensors + 1) * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemcpy(p->d_tensor_off, p->tensor_off.data(), (n_tensors + 1) * sizeof(uint32_t),
+                       hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_lamb_sums, nl * 2 * sizeof(double))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_trust, nt * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_lamb_scale, nt * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_work, std::max<size_t>(p->work.size(), 1) * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMemcpy(p->d_work, p->work.data(), p->work.size() * sizeof(uint32_t), hipMemcpyHostToDevice)) !=
             hipSuccess ||
@@ -372,7 +437,7 @@ int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* 
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan (device -1) cannot be bound");
   if (p->n_tensors && (!grads || !params || !exp_avg || !exp_avg_sq)) return fail(BCA_ERR_NULL, "a pointer array is NULL");
-  const uint64_t gsize = p->grad_dtype == BCA_GRAD_F16 ? 2 : 4;
+  const uint64_t gsize = grad_bytes(p->grad_dtype);
   for (uint32_t t = 0; t < p->n_tensors; ++t) {
     if (p->tensor_numel[t] == 0) continue;
     char buf[96];
@@ -387,13 +452,29 @@ int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* 
     }
   }
   DeviceGuard g(p->device);
-  // The copies are synchronous with respect to the host; kernels enqueued earlier
-  // on any stream may still be reading the old tables, so wait for them first.
-  hipError_t e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = upload_table(p, &p->norm_tab, grads, params, exp_avg, exp_avg_sq);
-  if (e == hipSuccess) e = upload_table(p, &p->apply_tab, grads, params, exp_avg, exp_avg_sq);
+  p->bound = false;
+  p->bound_g.assign(p->n_tensors, 0), p->bound_p.assign(p->n_tensors, 0);
+  p->bound_m.assign(p->n_tensors, 0), p->bound_v.assign(p->n_tensors, 0);
+  for (uint32_t t = 0; t < p->n_tensors; ++t) {
+    p->bound_g[t] = (uint64_t)(uintptr_t)grads[t], p->bound_p[t] = (uint64_t)(uintptr_t)params[t];
+    p->bound_m[t] = (uint64_t)(uintptr_t)exp_avg[t], p->bound_v[t] = (uint64_t)(uintptr_t)exp_avg_sq[t];
+  }
+  hipError_t e = upload_all_tables(p);
   if (e != hipSuccess) return fail_hip(e, "uploading the chunk tables");
   p->bound = true;
+  return BCA_OK;
+}
+
+int bca_plan_set_decay_mask(bca_plan* p, const uint8_t* decay) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  for (uint32_t t = 0; t < p->n_tensors; ++t) p->decay[t] = decay ? (decay[t] != 0) : 1;
+  if (p->device < 0 || !p->bound) return BCA_OK;  // the next bind writes the flags
+  DeviceGuard g(p->device);
+  hipError_t e = upload_all_tables(p);
+  if (e != hipSuccess) {
+    p->bound = false;
+    return fail_hip(e, "uploading the chunk tables");
+  }
   return BCA_OK;
 }
 
@@ -414,11 +495,11 @@ static const Table* pick_table(const bca_plan* p, int which) {
     fail(BCA_ERR_NULL, "plan is NULL");
     return nullptr;
   }
-  if (which != BCA_TABLE_NORM && which != BCA_TABLE_APPLY) {
-    fail(BCA_ERR_RANGE, "table must be BCA_TABLE_NORM or BCA_TABLE_APPLY");
+  if (which != BCA_TABLE_NORM && which != BCA_TABLE_APPLY && which != BCA_TABLE_LAMB) {
+    fail(BCA_ERR_RANGE, "table must be BCA_TABLE_NORM, BCA_TABLE_APPLY or BCA_TABLE_LAMB");
     return nullptr;
   }
-  return which == BCA_TABLE_NORM ? &p->norm_tab : &p->apply_tab;
+  return which == BCA_TABLE_NORM ? &p->norm_tab : which == BCA_TABLE_APPLY ? &p->apply_tab : &p->lamb_tab;
 }
 
 uint32_t bca_plan_num_chunks(const bca_plan* p, int which) {
@@ -444,9 +525,10 @@ int bca_plan_chunk_info(const bca_plan* p, int which, uint32_t i, uint32_t* tens
 int bca_plan_bucket_chunks(const bca_plan* p, int which, uint32_t b, uint32_t* first, uint32_t* count) {
   const Table* t = pick_table(p, which);
   if (!t) return p ? BCA_ERR_RANGE : BCA_ERR_NULL;
-  if (b >= p->n_buckets) return fail(BCA_ERR_RANGE, "bucket index out of range");
-  if (first) *first = t->bucket_off[b];
-  if (count) *count = t->bucket_off[b + 1] - t->bucket_off[b];
+  const std::vector<uint32_t>& off = which == BCA_TABLE_LAMB ? p->tensor_off : t->bucket_off;
+  if ((size_t)b + 1 >= off.size()) return fail(BCA_ERR_RANGE, "bucket (or tensor) index out of range");
+  if (first) *first = off[b];
+  if (count) *count = off[b + 1] - off[b];
   return BCA_OK;
 }
 
@@ -654,6 +736,53 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     first = false;
   }
   return BCA_OK;
+}
+
+// LAMB, with (thresholds != nullptr) or without bucket-wise clipping in front.
+static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, uint64_t step, uint32_t flags,
+                     float* norms, float* coefs, float* trust, int32_t* status, hipStream_t s) {
+  AdamK k;
+  if (int rc = make_adam_constants(hp, step, &k)) return rc;
+  if (int rc = check_ready(p)) return rc;
+  DeviceGuard g(p->device);
+  const float* cf = nullptr;
+  if (thresholds) {
+    float* nm = norms ? norms : p->d_norms;
+    float* cw = coefs ? coefs : p->d_coefs;
+    int32_t* st = status ? status : p->d_status;
+    const Table& TN = p->norm_tab;
+    const uint32_t nn = (uint32_t)TN.chunks.size();
+    // the gradients are read again right away by the moments sweep: cacheable loads
+    hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, 0, nn, p->d_partials, st, make_launch(p, 0, nn, true), s);
+    if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
+    e = launch_finalize(p->d_partials, TN.d_bucket_off, 0, p->n_buckets, thresholds, nm, cw, st, nullptr, s);
+    if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
+    cf = cw;
+  }
+  const Table& TL = p->lamb_tab;
+  const uint32_t nl = (uint32_t)TL.chunks.size();
+  hipError_t e = launch_lamb_moments(p->grad_dtype, TL.d_chunks, nl, cf, (flags & BCA_WRITE_BACK_GRADS) != 0,
+                                     p->d_lamb_sums, k, s);
+  if (e != hipSuccess) return fail_hip(e, "launching the LAMB moments kernel");
+  e = launch_lamb_trust(p->d_lamb_sums, p->d_tensor_off, p->n_tensors, k.lr, trust ? trust : p->d_trust,
+                        p->d_lamb_scale, s);
+  if (e != hipSuccess) return fail_hip(e, "launching the LAMB trust-ratio kernel");
+  e = launch_lamb_update(TL.d_chunks, nl, p->d_lamb_scale, k, s);
+  if (e != hipSuccess) return fail_hip(e, "launching the LAMB update kernel");
+  return BCA_OK;
+}
+
+int lamb_step(bca_plan* p, const bca_adam* hp, uint64_t step, float* trust, void* stream) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  return lamb_impl(p, nullptr, hp, step, 0, nullptr, nullptr, trust, nullptr, (hipStream_t)stream);
+}
+
+int bucket_clip_lamb(bca_plan* p, const float* thresholds, const bca_adam* hp, uint64_t step, uint32_t flags,
+                     float* norms, float* coefs, float* trust, int32_t* status, void* stream) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  if (!thresholds) return fail(BCA_ERR_NULL, "thresholds is NULL");
+  if (flags & ~BCA_WRITE_BACK_GRADS) return fail(BCA_ERR_RANGE, "bucket_clip_lamb knows BCA_WRITE_BACK_GRADS only");
+  return lamb_impl(p, thresholds, hp, step, flags, norms, coefs, trust, status, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -22,8 +22,10 @@ struct alignas(16) Chunk {
   uint64_t g, p, m, v;  // device byte addresses of the chunk's first element
   uint32_t len;         // elements
   uint32_t bucket;
-  uint32_t pad0, pad1;
+  uint32_t tensor;
+  uint32_t flags;       // kChunk* bits
 };
+constexpr uint32_t kChunkNoDecay = 1u;  // the chunk's tensor is exempt from weight decay
 static_assert(sizeof(Chunk) == 48, "chunk table entries are 3 x 16 bytes");
 
 struct ChunkInfo {  // host-side description, independent of addresses
@@ -33,9 +35,10 @@ struct ChunkInfo {  // host-side description, independent of addresses
   uint32_t bucket;
 };
 
-// One cut of the layout into chunks.  A plan holds two: a coarse one for the
-// squared-norm pass (fewer partial sums) and a fine one for the passes that
-// read and write (scale, Adam), where short-lived workgroups stream best.
+// One cut of the layout into chunks.  A plan holds three: a coarse one for the
+// squared-norm pass (fewer partial sums), a fine one for the passes that read
+// and write (scale, Adam), where short-lived workgroups stream best, and a fine
+// one in tensor-major order for LAMB, whose trust ratio needs per-tensor sums.
 struct Table {
   uint32_t chunk_elems = 0;
   std::vector<ChunkInfo> chunks;     // bucket-major
@@ -52,6 +55,7 @@ struct AdamK {
   float eps;
   float neg_lr;  // -lr
   float wd;
+  double lr;     // LAMB: the step -lr * trust_t is formed in fp64 per tensor and rounded once
 };
 
 constexpr uint32_t kBlock = 256;          // threads per workgroup (4 wavefronts)
@@ -122,6 +126,17 @@ hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, u
                        int32_t* status, uint32_t unroll, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 
+// LAMB (tensor-major table `table` of n chunks; tensor_off[t] = first chunk of tensor t).
+// Stage 1: moments, per-chunk sums of p^2 and update^2 (2 doubles per chunk in `sums`);
+// coefs == nullptr: gradients as stored.  Trust: per tensor, ratio and step scale.
+// Stage 2: p <- p + scale_t * update, the update recomputed from the stored moments.
+hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const float* coefs, bool write_back,
+                               double* sums, const AdamK& k, hipStream_t stream);
+hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, double lr,
+                             float* trust, float* scale, hipStream_t stream);
+hipError_t launch_lamb_update(const Chunk* table, uint32_t n, const float* scale, const AdamK& k,
+                              hipStream_t stream);
+
 void set_error(const std::string& msg);
 
 }  // namespace bca
@@ -136,6 +151,16 @@ struct bca_plan {
   bool bound = false;
   std::vector<uint64_t> tensor_numel;
   bca::Table norm_tab, apply_tab;
+  // LAMB: the fine cut again, tensor by tensor (chunks of tensor t are tensor_off[t] .. tensor_off[t+1]-1)
+  bca::Table lamb_tab;
+  std::vector<uint32_t> tensor_off;
+  uint32_t* d_tensor_off = nullptr;
+  double* d_lamb_sums = nullptr;   // 2 per chunk of lamb_tab: sum p^2, sum update^2
+  float* d_trust = nullptr;        // n_tensors
+  float* d_lamb_scale = nullptr;   // n_tensors: -lr * trust
+  // what bca_plan_bind was given, kept so that the tables can be written again (decay mask)
+  std::vector<uint64_t> bound_g, bound_p, bound_m, bound_v;
+  std::vector<uint8_t> decay;      // per tensor: 1 = weight decay applies (default), 0 = exempt
   // the fused call walks the buckets in groups [first, last)
   std::vector<std::pair<uint32_t, uint32_t>> groups;
   // work list of the single-launch step: (kind << 30) | index, in pipeline order

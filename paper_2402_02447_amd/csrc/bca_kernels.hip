@@ -37,6 +37,8 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
 // ---- streaming accesses ---------------------------------------------------------
 // NT = non-temporal: data that is touched once per launch is loaded and stored
@@ -57,12 +59,13 @@ __device__ __forceinline__ void stv(T* p, T x) {
 
 struct Entry {  // one chunk, in registers (uniform across the workgroup)
   uint64_t g, p, m, v;
-  uint32_t len, bucket;
+  uint32_t len, bucket, tensor, flags;
 };
 
 __device__ __forceinline__ Entry read_entry(const Chunk* e) {
   Entry r;
   r.g = e->g, r.p = e->p, r.m = e->m, r.v = e->v, r.len = e->len, r.bucket = e->bucket;
+  r.tensor = e->tensor, r.flags = e->flags;
   return r;
 }
 
@@ -107,9 +110,16 @@ __device__ __forceinline__ void for_each_chunk(const Chunk* __restrict__ table, 
 template <int GDT>
 struct Grad;
 
+// `wide` is the 128-bit piece the squared-norm pass loads; widen() turns it into
+// its VE fp32 values (exactly).
 template <>
 struct Grad<BCA_GRAD_F32> {
   typedef float elem;
+  typedef f32x4 wide;
+  static constexpr uint32_t VE = 4;
+  static __device__ __forceinline__ void widen(const wide& x, float (&f)[VE]) {
+    f[0] = x.x, f[1] = x.y, f[2] = x.z, f[3] = x.w;
+  }
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
     return ldv<NT>(reinterpret_cast<const f32x4*>(base) + vec);
@@ -129,6 +139,12 @@ struct Grad<BCA_GRAD_F32> {
 template <>
 struct Grad<BCA_GRAD_F16> {
   typedef _Float16 elem;
+  typedef f16x8 wide;
+  static constexpr uint32_t VE = 8;
+  static __device__ __forceinline__ void widen(const wide& x, float (&f)[VE]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) f[q] = (float)x[q];
+  }
   // fp16 -> fp32 is exact (subnormals included); fp32 -> fp16 rounds to nearest even.
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
@@ -148,6 +164,47 @@ struct Grad<BCA_GRAD_F16> {
   }
   static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
     reinterpret_cast<_Float16*>(base)[i] = (_Float16)x;
+  }
+};
+
+// bfloat16 is the upper half of a binary32: widening appends 16 zero bits (exact);
+// narrowing rounds to nearest, ties to even, in integer arithmetic (the carry out of
+// the fraction moves to the exponent and ends at infinity, as it should); NaN stays
+// NaN with the quiet bit set.
+__device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ unsigned short f32_to_bf16(float x) {
+  const uint32_t u = __float_as_uint(x);
+  if (x != x) return (unsigned short)((u >> 16) | 0x40u);
+  return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+template <>
+struct Grad<BCA_GRAD_BF16> {
+  typedef unsigned short elem;
+  typedef u16x8 wide;
+  static constexpr uint32_t VE = 8;
+  static __device__ __forceinline__ void widen(const wide& x, float (&f)[VE]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) f[q] = bf16_to_f32(x[q]);
+  }
+  template <bool NT>
+  static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
+    const u16x4 h = ldv<NT>(reinterpret_cast<const u16x4*>(base) + vec);
+    f32x4 r;
+    r.x = bf16_to_f32(h.x), r.y = bf16_to_f32(h.y), r.z = bf16_to_f32(h.z), r.w = bf16_to_f32(h.w);
+    return r;
+  }
+  template <bool NT>
+  static __device__ __forceinline__ void store4(void* base, uint32_t vec, f32x4 x) {
+    u16x4 h;
+    h.x = f32_to_bf16(x.x), h.y = f32_to_bf16(x.y), h.z = f32_to_bf16(x.z), h.w = f32_to_bf16(x.w);
+    stv<NT>(reinterpret_cast<u16x4*>(base) + vec, h);
+  }
+  static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
+    return bf16_to_f32(reinterpret_cast<const unsigned short*>(base)[i]);
+  }
+  static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
+    reinterpret_cast<unsigned short*>(base)[i] = f32_to_bf16(x);
   }
 };
 
@@ -184,8 +241,8 @@ template <int GDT, bool NT>
 __device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
   typedef Grad<GDT> G;
   constexpr uint32_t gsize = sizeof(typename G::elem);
-  constexpr uint32_t VE = 16u / gsize;  // elements per 128-bit load: 4 (fp32) or 8 (fp16)
-  constexpr uint32_t U = 8;             // loads in flight per lane
+  constexpr uint32_t VE = G::VE;  // elements per 128-bit load: 4 (fp32) or 8 (fp16, bf16)
+  constexpr uint32_t U = 8;       // loads in flight per lane
   const uint32_t tid = threadIdx.x;
   const uint64_t ga = en.g;
   const uint32_t len = en.len;
@@ -196,49 +253,29 @@ __device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
   const void* gv = reinterpret_cast<const void*>(ga + (uint64_t)head * gsize);
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 
+  typedef typename G::wide wide;
+  const wide* gw = reinterpret_cast<const wide*>(gv);
+  auto add_squares = [&](const wide& x) {
+    float f[VE];
+    G::widen(x, f);
+#pragma unroll
+    for (uint32_t q = 0; q < VE; q += 4) {
+      a0 = __fmaf_rn(f[q], f[q], a0), a1 = __fmaf_rn(f[q + 1], f[q + 1], a1);
+      a2 = __fmaf_rn(f[q + 2], f[q + 2], a2), a3 = __fmaf_rn(f[q + 3], f[q + 3], a3);
+    }
+  };
   for (uint32_t base = 0; base < nvec; base += kBlock * U) {
     const uint32_t j0 = base + tid;
     if (base + kBlock * U <= nvec) {
-      if constexpr (GDT == BCA_GRAD_F32) {
-        f32x4 x[U];
+      wide x[U];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(reinterpret_cast<const f32x4*>(gv) + j0 + u * kBlock);
+      for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(gw + j0 + u * kBlock);
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-          a0 = __fmaf_rn(x[u].x, x[u].x, a0), a1 = __fmaf_rn(x[u].y, x[u].y, a1);
-          a2 = __fmaf_rn(x[u].z, x[u].z, a2), a3 = __fmaf_rn(x[u].w, x[u].w, a3);
-        }
-      } else {
-        f16x8 x[U];
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(reinterpret_cast<const f16x8*>(gv) + j0 + u * kBlock);
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-          const float f0 = (float)x[u][0], f1 = (float)x[u][1], f2 = (float)x[u][2], f3 = (float)x[u][3];
-          const float f4 = (float)x[u][4], f5 = (float)x[u][5], f6 = (float)x[u][6], f7 = (float)x[u][7];
-          a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1), a2 = __fmaf_rn(f2, f2, a2);
-          a3 = __fmaf_rn(f3, f3, a3), a0 = __fmaf_rn(f4, f4, a0), a1 = __fmaf_rn(f5, f5, a1);
-          a2 = __fmaf_rn(f6, f6, a2), a3 = __fmaf_rn(f7, f7, a3);
-        }
-      }
+      for (uint32_t u = 0; u < U; ++u) add_squares(x[u]);
     } else {
       for (uint32_t u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * kBlock;
-        if (j < nvec) {
-          if constexpr (GDT == BCA_GRAD_F32) {
-            const f32x4 x = ldv<NT>(reinterpret_cast<const f32x4*>(gv) + j);
-            a0 = __fmaf_rn(x.x, x.x, a0), a1 = __fmaf_rn(x.y, x.y, a1);
-            a2 = __fmaf_rn(x.z, x.z, a2), a3 = __fmaf_rn(x.w, x.w, a3);
-          } else {
-            const f16x8 x = ldv<NT>(reinterpret_cast<const f16x8*>(gv) + j);
-#pragma unroll
-            for (int q = 0; q < 8; q += 4) {
-              const float f0 = (float)x[q], f1 = (float)x[q + 1], f2 = (float)x[q + 2], f3 = (float)x[q + 3];
-              a0 = __fmaf_rn(f0, f0, a0), a1 = __fmaf_rn(f1, f1, a1);
-              a2 = __fmaf_rn(f2, f2, a2), a3 = __fmaf_rn(f3, f3, a3);
-            }
-          }
-        }
+        if (j < nvec) add_squares(ldv<NT>(gw + j));
       }
     }
   }
@@ -404,23 +441,36 @@ __global__ __launch_bounds__(kBlock) void k_scale(const Chunk* __restrict__ tabl
 //   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
 //   p <- p - lr * ( mhat / (sqrt(vhat) + eps) + wd p ),  mhat = m/(1-b1^t), vhat = v/(1-b2^t)
 // Division and square root are the correctly rounded ones.
-__device__ __forceinline__ void adam1(float g, float& p, float& m, float& v, const AdamK& k) {
+// wd is the weight decay that applies to the element's tensor: k.wd, or 0 for a
+// tensor the decay mask exempts.
+__device__ __forceinline__ void adam_moments(float g, float& m, float& v, const AdamK& k) {
   m = __fmaf_rn(k.b1, m, k.omb1 * g);
   v = __fmaf_rn(k.b2, v, k.omb2 * (g * g));
+}
+// mhat / (sqrt(vhat) + eps) + wd p: the bracket of Adam's parameter update, which is
+// also LAMB's update direction.
+__device__ __forceinline__ float adam_direction(float p, float m, float v, const AdamK& k, float wd) {
   const float mhat = m * k.rbc1;
   const float vhat = v * k.rbc2;
   const float denom = __fsqrt_rn(vhat) + k.eps;
-  const float upd = __fdiv_rn(mhat, denom);
-  p = __fmaf_rn(k.neg_lr, __fmaf_rn(k.wd, p, upd), p);
+  return __fmaf_rn(wd, p, __fdiv_rn(mhat, denom));
+}
+__device__ __forceinline__ void adam1(float g, float& p, float& m, float& v, const AdamK& k, float wd) {
+  adam_moments(g, m, v, k);
+  p = __fmaf_rn(k.neg_lr, adam_direction(p, m, v, k, wd), p);
 }
 
-__device__ __forceinline__ void adam4(f32x4 g, f32x4& p, f32x4& m, f32x4& v, const AdamK& k) {
+__device__ __forceinline__ void adam4(f32x4 g, f32x4& p, f32x4& m, f32x4& v, const AdamK& k, float wd) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     float pi = p[i], mi = m[i], vi = v[i];
-    adam1(g[i], pi, mi, vi, k);
+    adam1(g[i], pi, mi, vi, k, wd);
     p[i] = pi, m[i] = mi, v[i] = vi;
   }
+}
+
+__device__ __forceinline__ float chunk_wd(const Entry& en, const AdamK& k) {
+  return (en.flags & kChunkNoDecay) ? 0.f : k.wd;
 }
 
 // The read-modify-write sweep over one chunk.  coef != 1 only on the fused path:
@@ -437,6 +487,7 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
   const uint64_t ga = en.g, pa = en.p, ma = en.m, va = en.v;
   const uint32_t len = en.len;
   const bool wb = WB && coef != 1.f;
+  const float wd = chunk_wd(en, k);
   const uint32_t head = vector_head(len, ga, gsize, 4u * gsize, true, pa, ma, va);
   const uint32_t nvec = (len - head) / 4u;
   const uint32_t tail0 = head + nvec * 4u;
@@ -460,7 +511,7 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) {
         if constexpr (FUSED) g[u] = g[u] * coef;
-        adam4(g[u], p[u], m[u], v[u], k);
+        adam4(g[u], p[u], m[u], v[u], k, wd);
         const uint32_t j = j0 + u * kBlock;
         stv<NT>(pv + j, p[u]), stv<NT>(mv + j, m[u]), stv<NT>(vv + j, v[u]);
         if (wb) G::template store4<GNT>(gv, j, g[u]);
@@ -471,7 +522,7 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
         if (j < nvec) {
           f32x4 g = G::template load4<GNT>(gv, j), p = ldv<NT>(pv + j), m = ldv<NT>(mv + j), v = ldv<NT>(vv + j);
           if constexpr (FUSED) g = g * coef;
-          adam4(g, p, m, v, k);
+          adam4(g, p, m, v, k, wd);
           stv<NT>(pv + j, p), stv<NT>(mv + j, m), stv<NT>(vv + j, v);
           if (wb) G::template store4<GNT>(gv, j, g);
         }
@@ -487,7 +538,7 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
     const uint32_t i = r < head ? r : tail0 + (r - head);
     float g = G::load1(gbase, i), p = p1[i], m = m1[i], v = v1[i];
     if constexpr (FUSED) g = g * coef;
-    adam1(g, p, m, v, k);
+    adam1(g, p, m, v, k, wd);
     p1[i] = p, m1[i] = m, v1[i] = v;
     if (wb) G::store1(gbase, i, g);
   }
@@ -503,6 +554,136 @@ __global__ __launch_bounds__(kBlock) void k_adam(const Chunk* __restrict__ table
     if constexpr (FUSED) coef = coefs[en.bucket];
     adam_chunk<GDT, FUSED, WB, U, GNT>(en, coef, k);
   });
+}
+
+// ---- LAMB -------------------------------------------------------------------------
+//
+// LAMB (You et al. 2020, the optimizer the paper weighs Adam against in Sec. 2.2 and
+// Sec. 5) keeps Adam's moments and direction u = mhat / (sqrt(vhat) + eps) + wd p, and
+// scales each tensor's step by the trust ratio ||p|| / ||u||.  The ratio needs sums
+// over whole tensors, so the sweep is split in two, over a tensor-major chunk table:
+//   k_lamb_moments : g, p, m, v -> m, v; per-chunk sums of p^2 and u^2
+//   k_lamb_trust   : per tensor, the sums in chunk order (fp64) -> ratio, -lr * ratio
+//   k_lamb_update  : p, m, v -> p + (-lr ratio) u, u recomputed from the stored moments
+// (recomputing u costs the same 16 B/element as storing and re-reading it would, and
+// leaves the gradients alone).  Both stages evaluate u with the same correctly rounded
+// operations on the same fp32 inputs, so the u that is applied is the u that was measured.
+
+// Combines per-lane values of the four wavefronts in a fixed order; the result is valid in thread 0.
+__device__ __forceinline__ double block_sum(double x, double* s_w) {
+  x = wave_sum(x);
+  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+}
+
+template <int GDT, bool FUSED, bool WB>
+__global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict__ table, uint32_t n,
+                                                          const float* __restrict__ coefs,
+                                                          double* __restrict__ sums, const AdamK k) {
+  typedef Grad<GDT> G;
+  constexpr uint32_t gsize = sizeof(typename G::elem);
+  __shared__ double s_pp[kWaves], s_uu[kWaves];
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t ci = blockIdx.x; ci < n; ci += gridDim.x) {
+    const Entry en = read_entry(&table[ci]);
+    float coef = 1.f;
+    if constexpr (FUSED) coef = coefs[en.bucket];
+    const bool wb = WB && coef != 1.f;
+    const float wd = chunk_wd(en, k);
+    const uint32_t len = en.len;
+    const uint32_t head = vector_head(len, en.g, gsize, 4u * gsize, true, en.p, en.m, en.v);
+    const uint32_t nvec = (len - head) / 4u;
+    const uint32_t tail0 = head + nvec * 4u;
+    void* gv = reinterpret_cast<void*>(en.g + (uint64_t)head * gsize);
+    const f32x4* pv = reinterpret_cast<const f32x4*>(en.p + (uint64_t)head * 4u);
+    f32x4* mv = reinterpret_cast<f32x4*>(en.m + (uint64_t)head * 4u);
+    f32x4* vv = reinterpret_cast<f32x4*>(en.v + (uint64_t)head * 4u);
+    float pp = 0.f, uu = 0.f;  // a lane adds 4 * chunk_elems / 1024 squares in fp32, then everything is fp64
+    for (uint32_t j = tid; j < nvec; j += kBlock) {
+      f32x4 g = G::template load4<true>(gv, j), p = ldv<true>(pv + j), m = ldv<true>(mv + j), v = ldv<true>(vv + j);
+      if constexpr (FUSED) g = g * coef;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float mi = m[i], vi = v[i];
+        adam_moments(g[i], mi, vi, k);
+        const float u = adam_direction(p[i], mi, vi, k, wd);
+        pp = __fmaf_rn(p[i], p[i], pp), uu = __fmaf_rn(u, u, uu);
+        m[i] = mi, v[i] = vi;
+      }
+      stv<true>(mv + j, m), stv<true>(vv + j, v);
+      if (wb) G::template store4<true>(gv, j, g);
+    }
+    void* gbase = reinterpret_cast<void*>(en.g);
+    const float* p1 = reinterpret_cast<const float*>(en.p);
+    float* m1 = reinterpret_cast<float*>(en.m);
+    float* v1 = reinterpret_cast<float*>(en.v);
+    for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
+      const uint32_t i = r < head ? r : tail0 + (r - head);
+      float g = G::load1(gbase, i), m = m1[i], v = v1[i];
+      const float p = p1[i];
+      if constexpr (FUSED) g = g * coef;
+      adam_moments(g, m, v, k);
+      const float u = adam_direction(p, m, v, k, wd);
+      pp = __fmaf_rn(p, p, pp), uu = __fmaf_rn(u, u, uu);
+      m1[i] = m, v1[i] = v;
+      if (wb) G::store1(gbase, i, g);
+    }
+    const double tpp = block_sum((double)pp, s_pp), tuu = block_sum((double)uu, s_uu);
+    if (tid == 0) sums[(uint64_t)ci * 2u] = tpp, sums[(uint64_t)ci * 2u + 1u] = tuu;
+    __syncthreads();  // s_pp / s_uu are reused by the next chunk
+  }
+}
+
+// One workgroup per tensor: the chunk sums in index order (strided over the threads,
+// butterfly, four wavefronts), then trust = ||p|| / ||u||, or 1 where either norm is
+// zero and the quotient means nothing; scale = -lr * trust in fp64, rounded once.
+__global__ __launch_bounds__(kBlock) void k_lamb_trust(const double* __restrict__ sums,
+                                                        const uint32_t* __restrict__ tensor_off, double lr,
+                                                        float* __restrict__ trust, float* __restrict__ scale) {
+  __shared__ double s_pp[kWaves], s_uu[kWaves];
+  const uint32_t t = blockIdx.x;
+  double pp = 0.0, uu = 0.0;
+  for (uint32_t c = tensor_off[t] + threadIdx.x; c < tensor_off[t + 1]; c += kBlock)
+    pp += sums[(uint64_t)c * 2u], uu += sums[(uint64_t)c * 2u + 1u];
+  const double tpp = block_sum(pp, s_pp), tuu = block_sum(uu, s_uu);
+  if (threadIdx.x == 0) {
+    const double pn = sqrt(tpp), un = sqrt(tuu);
+    const double r = (pn > 0.0 && un > 0.0) ? pn / un : 1.0;
+    trust[t] = (float)r;
+    scale[t] = (float)(-lr * r);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict__ table, uint32_t n,
+                                                         const float* __restrict__ scale, const AdamK k) {
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t ci = blockIdx.x; ci < n; ci += gridDim.x) {
+    const Entry en = read_entry(&table[ci]);
+    const float sc = scale[en.tensor];
+    const float wd = chunk_wd(en, k);
+    const uint32_t len = en.len;
+    const uint32_t head = vector_head(len, en.p, 4u, 16u, true, en.p, en.m, en.v);
+    const uint32_t nvec = (len - head) / 4u;
+    const uint32_t tail0 = head + nvec * 4u;
+    f32x4* pv = reinterpret_cast<f32x4*>(en.p + (uint64_t)head * 4u);
+    const f32x4* mv = reinterpret_cast<const f32x4*>(en.m + (uint64_t)head * 4u);
+    const f32x4* vv = reinterpret_cast<const f32x4*>(en.v + (uint64_t)head * 4u);
+    for (uint32_t j = tid; j < nvec; j += kBlock) {
+      f32x4 p = ldv<true>(pv + j);
+      const f32x4 m = ldv<true>(mv + j), v = ldv<true>(vv + j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[i] = __fmaf_rn(sc, adam_direction(p[i], m[i], v[i], k, wd), p[i]);
+      stv<true>(pv + j, p);
+    }
+    float* p1 = reinterpret_cast<float*>(en.p);
+    const float* m1 = reinterpret_cast<const float*>(en.m);
+    const float* v1 = reinterpret_cast<const float*>(en.v);
+    for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
+      const uint32_t i = r < head ? r : tail0 + (r - head);
+      p1[i] = __fmaf_rn(sc, adam_direction(p1[i], m1[i], v1[i], k, wd), p1[i]);
+    }
+  }
 }
 
 // ---- the whole fused step in one launch ----------------------------------------------
@@ -753,6 +934,12 @@ void pick2(bool a, bool b, F f) {
   }
 }
 template <typename F>
+void pick_gdt(int gdt, F f) {
+  if (gdt == BCA_GRAD_F32) f(std::integral_constant<int, BCA_GRAD_F32>{});
+  else if (gdt == BCA_GRAD_F16) f(std::integral_constant<int, BCA_GRAD_F16>{});
+  else f(std::integral_constant<int, BCA_GRAD_BF16>{});
+}
+template <typename F>
 void pick_unroll(uint32_t u, F f) {
   if (u == 1) f(std::integral_constant<uint32_t, 1>{});
   else if (u == 2) f(std::integral_constant<uint32_t, 2>{});
@@ -768,12 +955,11 @@ hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, d
   if (n == 0 && status == nullptr) return hipSuccess;  // with a status word the launch still has to clear it
   pick2(!L.g_keep, L.staged, [&](auto nt, auto st) {
     constexpr bool NT = decltype(nt)::value, ST = decltype(st)::value;
-    if (gdt == BCA_GRAD_F32)
-      hipLaunchKernelGGL((k_sqnorm<BCA_GRAD_F32, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n,
-                         partials, status);
-    else
-      hipLaunchKernelGGL((k_sqnorm<BCA_GRAD_F16, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n,
-                         partials, status);
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      hipLaunchKernelGGL((k_sqnorm<GDT, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, partials,
+                         status);
+    });
   });
   return hipGetLastError();
 }
@@ -794,12 +980,11 @@ hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, u
   if (e != hipSuccess || n_norm + n_apply == 0) return e;
   pick_unroll(unroll, [&](auto uu) {
     constexpr uint32_t U = decltype(uu)::value;
-    if (gdt == BCA_GRAD_F32)
-      hipLaunchKernelGGL((k_clip<BCA_GRAD_F32, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm,
-                         ca0, n_apply, thresholds, norms, coefs, status);
-    else
-      hipLaunchKernelGGL((k_clip<BCA_GRAD_F16, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm,
-                         ca0, n_apply, thresholds, norms, coefs, status);
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      hipLaunchKernelGGL((k_clip<GDT, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm, ca0,
+                         n_apply, thresholds, norms, coefs, status);
+    });
   });
   return hipGetLastError();
 }
@@ -813,15 +998,13 @@ hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const u
   if (e != hipSuccess || n_work == 0) return e;
   pick_unroll(unroll, [&](auto uu) {
     constexpr uint32_t U = decltype(uu)::value;
-    pick2(gdt == BCA_GRAD_F32, write_back, [&](auto f32, auto wb) {
-      constexpr int GDT = decltype(f32)::value ? BCA_GRAD_F32 : BCA_GRAD_F16;
-      constexpr bool WB = decltype(wb)::value;
-      if (tickets)
-        hipLaunchKernelGGL((k_step<GDT, WB, U, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+    pick2(tickets, write_back, [&](auto tk, auto wb) {
+      constexpr bool TK = decltype(tk)::value, WB = decltype(wb)::value;
+      pick_gdt(gdt, [&](auto gd) {
+        constexpr int GDT = decltype(gd)::value;
+        hipLaunchKernelGGL((k_step<GDT, WB, U, TK>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
                            thresholds, norms, coefs, status, k);
-      else
-        hipLaunchKernelGGL((k_step<GDT, WB, U, false>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
-                           thresholds, norms, coefs, status, k);
+      });
     });
   });
   return hipGetLastError();
@@ -855,10 +1038,12 @@ hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, co
   // The scaled gradients are about to be read again (by the all-reduce or by Adam): plain stores.
   pick_unroll(L.unroll, [&](auto uu) {
     constexpr uint32_t U = decltype(uu)::value;
-    pick2(gdt == BCA_GRAD_F32, L.staged, [&](auto f32, auto st) {
-      constexpr int GDT = decltype(f32)::value ? BCA_GRAD_F32 : BCA_GRAD_F16;
-      constexpr bool ST = decltype(st)::value;
-      hipLaunchKernelGGL((k_scale<GDT, U, false, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      if (L.staged)
+        hipLaunchKernelGGL((k_scale<GDT, U, false, true>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
+      else
+        hipLaunchKernelGGL((k_scale<GDT, U, false, false>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, coefs);
     });
   });
   return hipGetLastError();
@@ -885,12 +1070,39 @@ hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, con
     constexpr uint32_t U = decltype(uu)::value;
     pick2(!L.g_keep, L.staged, [&](auto gnt, auto st) {
       constexpr bool GNT = decltype(gnt)::value, ST = decltype(st)::value;
-      if (gdt == BCA_GRAD_F32)
-        launch_adam_t<BCA_GRAD_F32, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
-      else
-        launch_adam_t<BCA_GRAD_F16, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
+      pick_gdt(gdt, [&](auto gd) {
+        launch_adam_t<decltype(gd)::value, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
+      });
     });
   });
+  return hipGetLastError();
+}
+
+hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const float* coefs, bool write_back,
+                               double* sums, const AdamK& k, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  pick_gdt(gdt, [&](auto gd) {
+    constexpr int GDT = decltype(gd)::value;
+    if (coefs == nullptr)
+      hipLaunchKernelGGL((k_lamb_moments<GDT, false, false>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+    else if (!write_back)
+      hipLaunchKernelGGL((k_lamb_moments<GDT, true, false>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+    else
+      hipLaunchKernelGGL((k_lamb_moments<GDT, true, true>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, double lr,
+                             float* trust, float* scale, hipStream_t stream) {
+  if (n_tensors == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kBlock), 0, stream, sums, tensor_off, lr, trust, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_lamb_update(const Chunk* table, uint32_t n, const float* scale, const AdamK& k, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_lamb_update, dim3(n), dim3(kBlock), 0, stream, table, n, scale, k);
   return hipGetLastError();
 }
 

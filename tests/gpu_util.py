@@ -17,6 +17,8 @@ SMALL = 1e-2
 
 
 def gdt_of(grads: Sequence[np.ndarray]) -> int:
+    if isinstance(grads, oracle.Bf16):
+        return B.BCA_GRAD_BF16
     return B.BCA_GRAD_F16 if len(grads) and grads[0].dtype == np.float16 else B.BCA_GRAD_F32
 
 
@@ -26,7 +28,7 @@ def to_dev(arrs: Sequence[np.ndarray], offsets: Optional[Sequence[int]] = None) 
     addresses that are only element-aligned."""
     out = []
     for i, a in enumerate(arrs):
-        t = torch.from_numpy(a)
+        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a)      # bf16 bit patterns travel as int16
         if offsets is None or offsets[i] == 0:
             out.append(t.cuda())
         else:
@@ -38,7 +40,7 @@ def to_dev(arrs: Sequence[np.ndarray], offsets: Optional[Sequence[int]] = None) 
 
 
 def to_host(ts: Sequence[torch.Tensor]) -> List[np.ndarray]:
-    return [t.cpu().numpy() for t in ts]
+    return [t.cpu().numpy().view(np.uint16) if t.dtype == torch.int16 else t.cpu().numpy() for t in ts]
 
 
 class Device:
@@ -56,10 +58,11 @@ class Device:
         self.norms = torch.full((nb,), -1.0, dtype=torch.float32, device="cuda")
         self.coefs = torch.full((nb,), -1.0, dtype=torch.float32, device="cuda")
         self.status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        self.trust = torch.full((max(1, layout.n_tensors),), -1.0, dtype=torch.float32, device="cuda")
 
     def set_grads(self, grads):
         for d, h in zip(self.g, grads):
-            d.copy_(torch.from_numpy(h))
+            d.copy_(torch.from_numpy(h.view(np.int16) if h.dtype == np.uint16 else h))
 
     def thresholds(self, thr: np.ndarray) -> torch.Tensor:
         return torch.from_numpy(np.ascontiguousarray(thr, np.float32)).cuda()

@@ -122,3 +122,34 @@ def test_bert_large_whole_gradient_clipping_full_size():
     check_state("v", to_host(dev.v), ov, strict_rel=True)
     print(f"[whole] norm {owhole:.4f} coef {ocoef:.6f}", flush=True)
     dev.close()
+
+
+def test_bert_large_lamb_bf16_masked_full_size():
+    # LAMB behind bucket-wise clipping on the 50 MiB layout, bf16 gradients, biases and LayerNorm exempt from decay
+    w = W.config_bert_large()
+    lay = w.layout
+    numels = [int(n) for n in lay.tensor_numel]
+    g = oracle.Bf16(W.normal_bf16_tensors(numels, 0, 1e-3))
+    p, m, v = w.params(), w.exp_avg(), w.exp_avg_sq()
+    mask = W.bert_decay_mask(30522, 1024, 24, 4096, 512)
+    dev = Device(lay, g, p, m, v)
+    dev.plan.set_decay_mask(mask)
+    dthr = dev.thresholds(w.thresholds)
+    dev.plan.bucket_clip_lamb(dthr, hyper(w.hyper), w.first_step, 0, dev.norms, dev.coefs, dev.trust, dev.status)
+    dev.sync()
+    t0 = time.time()
+    op, om, ov = f64(p), f64(m), f64(v)
+    onorm, ocoef, otrust, ost = oracle.bucket_clip_lamb(lay, g, op, om, ov, w.thresholds, step=w.first_step, decay=mask,
+                                                        **hp_kwargs(w.hyper))
+    print(f"[lamb] oracle step {time.time() - t0:.1f}s", flush=True)
+    assert int(dev.status.item()) == ost == 0 and (ocoef < 1).all()
+    rel = check_norms(dev.norms.cpu().numpy(), onorm)
+    tr = dev.trust.cpu().numpy().astype(np.float64)
+    trel = np.abs(tr - otrust) / otrust
+    assert trel.max() <= 1e-5, trel.max()
+    rp = check_state("p", to_host(dev.p), op)
+    rm = check_state("m", to_host(dev.m), om)
+    rv = check_state("v", to_host(dev.v), ov, strict_rel=True)
+    print(f"[lamb] norm rel {rel:.2e}; trust rel {trel.max():.2e}; p {rp}; m {rm}; v {rv}", flush=True)
+    assert bits_equal(to_host(dev.g), g)
+    dev.close()

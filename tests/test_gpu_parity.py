@@ -17,18 +17,20 @@ pytestmark = pytest.mark.gpu
 # ------------------------------------------------------------------ generic runners
 
 
-def run_fused(layout, g, p, m, v, thr, hp, step, flags=0, offsets=None, **tuning):
+def run_fused(layout, g, p, m, v, thr, hp, step, flags=0, offsets=None, decay=None, **tuning):
     """bucket_clip_adam vs oracle.bucket_clip_adam.  Returns a dict of error figures."""
     dev = Device(layout, g, p, m, v, offsets, **tuning)
+    if decay is not None:
+        dev.plan.set_decay_mask(decay)
     dthr = dev.thresholds(thr)
     dev.plan.bucket_clip_adam(dthr, hyper(hp), step, flags, dev.norms, dev.coefs, dev.status)
     dev.sync()
-    og = [x.copy() for x in g]
+    og = type(g)(x.copy() for x in g)
     op, om, ov = f64(p), f64(m), f64(v)
     onorm, ocoef, ost = oracle.bucket_clip_adam(layout, og, op, om, ov, thr, step=step,
                                                 write_back=bool(flags & B.BCA_WRITE_BACK_GRADS),
                                                 skip_on_nonfinite=bool(flags & B.BCA_SKIP_STEP_ON_NONFINITE),
-                                                **hp_kwargs(hp))
+                                                decay=decay, **hp_kwargs(hp))
     out = {"norm_rel": check_norms(dev.norms.cpu().numpy(), onorm)}
     gcoef = dev.coefs.cpu().numpy()
     assert np.all(gcoef > 0) and np.all(gcoef <= 1)
@@ -55,18 +57,21 @@ def check_scaled_grads(got, want, original):
         if a.dtype == np.float32:
             assert np.allclose(a, b, rtol=5e-7, atol=1e-45), f"scaled gradient of tensor {t}"
         else:
+            # fp16 and bf16 are sign-magnitude codes: neighbouring values of one sign differ by 1 in the code
             ai, bi = a.view(np.int16).astype(np.int32), b.view(np.int16).astype(np.int32)
             d = np.abs(ai - bi)
-            assert d.max(initial=0) <= 1, f"tensor {t}: stored fp16 gradient off by more than one ulp"
+            assert d.max(initial=0) <= 1, f"tensor {t}: stored 16-bit gradient off by more than one ulp"
             assert np.mean(d != 0) <= 0.02 if a.size >= 1000 else True
         unchanged = np.array_equal(b.view(np.uint8), o.view(np.uint8))
         if unchanged:
             assert np.array_equal(a.view(np.uint8), o.view(np.uint8)), f"tensor {t} was not clipped but changed"
 
 
-def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=True, **tuning):
+def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=True, decay=None, **tuning):
     """bucket_clip_norms -> bucket_clip_apply -> adam_step vs the oracle's chain."""
     dev = Device(layout, g, p, m, v, offsets, **tuning)
+    if decay is not None:
+        dev.plan.set_decay_mask(decay)
     dthr = dev.thresholds(thr)
     nb = layout.n_buckets
     cuts = sorted({0, nb // 3, (2 * nb) // 3, nb}) if split_ranges else [0, nb]
@@ -84,7 +89,7 @@ def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=Tr
     assert stat == ost
     gcoef = dev.coefs.cpu().numpy()
     assert np.allclose(gcoef, ocoef, rtol=2e-5, atol=0)
-    og = [x.copy() for x in g]
+    og = type(g)(x.copy() for x in g)
     oracle.bucket_scale(layout, og, ocoef)
     check_scaled_grads(to_host(dev.g), og, g)
     # the one-launch form of the same two calls gives the same bits
@@ -104,12 +109,12 @@ def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=Tr
     # GPU's and the oracle's coefficient can move a stored gradient by one fp16 ulp
     # (checked above); so that Adam is compared on identical inputs, the GPU's copy
     # is replaced by the oracle's scaled gradients first.
-    if g[0].dtype == np.float16:
+    if g[0].dtype != np.float32:
         dev.set_grads(og)
     dev.plan.adam_step(hyper(hp), step)
     dev.sync()
     op, om, ov = f64(p), f64(m), f64(v)
-    oracle.adam_step(layout, og, op, om, ov, step=step, **hp_kwargs(hp))
+    oracle.adam_step(layout, og, op, om, ov, step=step, decay=decay, **hp_kwargs(hp))
     out = {"p": check_state("p", to_host(dev.p), op), "m": check_state("m", to_host(dev.m), om),
            "v": check_state("v", to_host(dev.v), ov, strict_rel=(g[0].dtype == np.float32))}
     dev.close()
@@ -508,7 +513,7 @@ def run_whole(layout, g, p, m, v, c, hp, step, flags=0, offsets=None, **tuning):
     dc = torch.tensor([c], dtype=torch.float32, device="cuda")
     dev.plan.bucket_clip_adam(dc, hyper(hp), step, flags | B.BCA_CLIP_WHOLE_GRADIENT, norms, dev.coefs, dev.status)
     dev.sync()
-    og = [x.copy() for x in g]
+    og = type(g)(x.copy() for x in g)
     op, om, ov = f64(p), f64(m), f64(v)
     onorms, owhole, ocoef, ost = oracle.whole_clip_adam(layout, og, op, om, ov, c, step=step,
                                                         write_back=bool(flags & B.BCA_WRITE_BACK_GRADS),

@@ -19,8 +19,9 @@ def test_library_loads_and_exports_every_declared_symbol():
     L = B.load_library()
     header = open(os.path.join(ROOT, "include", "bca.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|bucket_clip|adam_step)\s*\(", header))
-    assert {"bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam"} <= declared
+    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|bucket_clip|adam_step|lamb_step)\s*\(", header))
+    assert {"bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
+            "bucket_clip_lamb", "bca_plan_set_decay_mask"} <= declared
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(L, name), name
@@ -210,3 +211,49 @@ def test_a_device_plan_fails_loudly_without_a_gpu():
 def test_alg1_threshold_helper():
     thr = B.alg1_thresholds(1.0, 16)
     assert thr.dtype == np.float32 and thr.shape == (16,) and np.all(thr == np.float32(0.25))
+
+
+@pytest.mark.parametrize("chunk", [1024, 4096])
+def test_tensor_major_table_partitions_every_tensor_in_order_and_keeps_chunks_inside_buckets(chunk):
+    numels = W.scaled_bert_numels(64, 2, 256, vocab=1000, max_pos=32) + [0, 7, 1]
+    lay = W.layout_flat_split(numels, 50_000)
+    assert lay.tensors_split() > 0
+    p = host_plan(lay, chunk_apply=chunk)
+    T = B.BCA_TABLE_LAMB
+    owner = [np.full(n, -1, np.int64) for n in numels]          # bucket of every element per the layout
+    for b in range(lay.n_buckets):
+        for t, beg, ln in lay.segments_of(b):
+            owner[t][beg:beg + ln] = b
+    total = 0
+    for t, n in enumerate(numels):
+        f, cnt = p.bucket_chunks(t, T)
+        assert f == total
+        pos = 0
+        for i in range(f, f + cnt):
+            tt, beg, ln, b = p.chunk_info(i, T)
+            assert tt == t and beg == pos and 0 < ln <= chunk     # contiguous, in order of position
+            assert beg // chunk == (beg + ln - 1) // chunk
+            assert (owner[t][beg:beg + ln] == b).all()            # one bucket per chunk: one clip coefficient
+            pos += ln
+        assert pos == n
+        total += cnt
+    assert total == p.n_chunks(T) == p.n_chunks(B.BCA_TABLE_APPLY)
+    with pytest.raises(B.BcaError):
+        p.bucket_chunks(len(numels), T)
+
+
+def test_decay_mask_is_accepted_on_a_host_plan_and_checked_for_length():
+    lay = W.layout_one_tensor_per_bucket([5, 6, 7])
+    p = host_plan(lay)
+    p.set_decay_mask([1, 0, 1])
+    p.set_decay_mask(None)
+    with pytest.raises(ValueError):
+        p.set_decay_mask([1, 0])
+
+
+def test_bf16_plans_are_accepted_and_unknown_types_are_not():
+    lay = W.layout_one_tensor_per_bucket([5, 6, 7])
+    host_plan(lay, B.BCA_GRAD_BF16)
+    with pytest.raises(B.BcaError) as e:
+        host_plan(lay, 3)
+    assert e.value.code == -7
