@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # Bytes crossing the L2 <-> fabric boundary in one launch of the dominant kernel, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for libbca's plain copy kernel
-# (profiles/k_step_bert_large_fp32_50MiB_hbm_counters.txt).  Key: (config, single_launch).
-MEASURED_TRAFFIC_BYTES = {(3, True): 10835977229}
+# (profiles/k_step_bert_large_fp32_50MiB_hbm_counters.txt).  Key: (config, gradient type, single_launch).
+MEASURED_TRAFFIC_BYTES = {(3, "f32", True): 10835977229}
 
 
 def parse():
@@ -35,6 +35,12 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="benchmark configuration: 2 BERT-Base 25 MiB, 3 BERT-Large 50 MiB, 4 fp16 1 MiB, 5 4 MiB")
+    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms"],
+                    help="what one step is: the fused bucket_clip_adam (headline, default), adam_step alone, "
+                         "bucket_clip_lamb, lamb_step, or bucket_clip_norms alone")
+    ap.add_argument("--grad-dtype", default="", choices=["", "f32", "f16", "bf16"],
+                    help="override the configuration's gradient storage type")
+    ap.add_argument("--decay-mask", action="store_true", help="exempt biases and LayerNorm tensors from weight decay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-norm", type=int, default=0)
     ap.add_argument("--chunk-apply", type=int, default=0)
@@ -47,6 +53,70 @@ def parse():
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many 1 GiB plain copies (k_copy) so that counter runs have a known reference")
     return ap.parse_args()
+
+
+def other_ops(a, w, plan, g, p, m, v, dev):
+    """Steps other than the headline one: timed the same way (K steps between two synchronisations, then each
+    step between two events on the launch stream), priced on their own algorithmic bytes.  One JSON line."""
+    import torch
+
+    import paper_2402_02447_amd as B
+    lay = w.layout
+    N = lay.n_elements
+    gb = g[0].element_size()
+    hp = B.AdamHyper(w.hyper.lr, w.hyper.beta1, w.hyper.beta2, w.hyper.eps, w.hyper.weight_decay)
+    thr = torch.from_numpy(w.thresholds).to(dev)
+    norms = torch.zeros(lay.n_buckets, dtype=torch.float32, device=dev)
+    coefs = torch.zeros_like(norms)
+    trust = torch.zeros(max(1, lay.n_tensors), dtype=torch.float32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    step = [w.first_step]
+    # algorithmic bytes per element: every sweep's reads and writes, nothing assumed cached
+    ops = {
+        "adam": (lambda: plan.adam_step(hp, step[0], stream), 24 + gb,
+                 "adam_step: k_adam, g p m v read, p m v written"),
+        "norms": (lambda: plan.bucket_clip_norms(0, lay.n_buckets, norms, stream), gb,
+                  "bucket_clip_norms: k_sqnorm + k_finalize, g read"),
+        "lamb": (lambda: plan.lamb_step(hp, step[0], trust, stream), (gb + 12 + 8) + (12 + 4),
+                 "lamb_step: k_lamb_moments (g p m v read, m v written), k_lamb_trust, k_lamb_update (p m v read, p written)"),
+        "clip_lamb": (lambda: plan.bucket_clip_lamb(thr, hp, step[0], 0, norms, coefs, trust, status, stream),
+                      gb + (gb + 12 + 8) + (12 + 4), "bucket_clip_lamb: k_sqnorm + k_finalize, then the three LAMB kernels"),
+    }
+    fn, per_elt, what = ops[a.op]
+
+    def one():
+        fn()
+        step[0] += 1
+    for _ in range(a.warmup):
+        one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        one()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for e0, e1 in evs:
+        e0.record(stream)
+        one()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    per = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    med = per[len(per) // 2]
+    gbps = per_elt * N / (med * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": f"{a.op} step time (ms/step)", "value": round(ms, 4), "unit": "ms/step", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if gb == 4 else f"f32 ({a.grad_dtype or w.grad_dtype} gradients)",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{a.config - 1}]: {w.name}, {N} params, {lay.n_buckets} buckets, op {a.op}"},
+        "roofline": {"bound": "hbm", "kernel": what, "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_elt": per_elt,
+                     "ms_per_launch": round(med, 4)},
+        "cpu_baseline": None, "ms_per_step_median": round(med, 4), "ms_per_step_min": round(per[0], 4),
+        "status": int(status.item()),
+    }))
 
 
 def main():
@@ -69,7 +139,9 @@ def main():
     lay = w.layout
     numels = [int(n) for n in lay.tensor_numel]
     N = lay.n_elements
-    f16 = w.grad_dtype == "f16"
+    gdt_name = a.grad_dtype or w.grad_dtype
+    f16 = gdt_name == "f16"
+    bf16 = gdt_name == "bf16"
 
     # ---- synthetic inputs, generated on the device (seeded), one allocation per tensor
     gen = torch.Generator(device=dev)
@@ -93,13 +165,23 @@ def main():
         for b in w.hot_buckets:
             for t, beg, ln in lay.segments_of(b):
                 g[t][beg:beg + ln] *= 100.0
+        if bf16:
+            g = [x.to(torch.bfloat16) for x in g]
     thr = torch.from_numpy(w.thresholds).to(dev)
     hp = B.AdamHyper(w.hyper.lr, w.hyper.beta1, w.hyper.beta2, w.hyper.eps, w.hyper.weight_decay)
 
-    plan = B.Plan.from_layout(lay, B.BCA_GRAD_F16 if f16 else B.BCA_GRAD_F32, device=0, chunk_norm=a.chunk_norm,
+    gdt = B.BCA_GRAD_F16 if f16 else B.BCA_GRAD_BF16 if bf16 else B.BCA_GRAD_F32
+    plan = B.Plan.from_layout(lay, gdt, device=0, chunk_norm=a.chunk_norm,
                               chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
                               unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20)
     plan.bind(g, p, m, v)
+    if a.decay_mask:
+        H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)
+        plan.set_decay_mask(W.bert_decay_mask(30522, H, L, F, 512))
+    if a.op != "clip_adam":
+        other_ops(a, w, plan, g, p, m, v, dev)
+        plan.close()
+        return
     norms = torch.zeros(lay.n_buckets, dtype=torch.float32, device=dev)
     coefs = torch.zeros_like(norms)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -173,7 +255,7 @@ def main():
     copy_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
 
-    gbytes = 2 if f16 else 4
+    gbytes = 2 if (f16 or bf16) else 4
     single = not (a.tune_flags & B.BCA_TUNE_MULTI_LAUNCH)
     pmv_bytes = 24                                         # p, m, v read and written
     once_per_elt = pmv_bytes + gbytes                      # gradients counted once (second read served by cache)
@@ -186,7 +268,7 @@ def main():
         kname = "k_adam (clip-fused Adam sweep, summed over bucket groups)"
         per_elt, ms_kernel = once_per_elt, ms_adam
     achieved = per_elt * N / (ms_kernel * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((a.config, single))
+    traffic = MEASURED_TRAFFIC_BYTES.get((a.config, gdt_name, single))
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "bytes_per_elt": per_elt,
                 "ms_per_launch": round(ms_kernel, 4),
@@ -226,9 +308,9 @@ def main():
         "metric": "fused bucket_clip_adam step time, BERT-Large fp32 (ms/step; HBM fraction in roofline)",
         "value": round(ms_per_step, 4), "unit": "ms/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if not f16 else "f32 (f16 gradients)", "data": "synthetic",
+        "dtype": "f32" if gdt_name == "f32" else f"f32 ({gdt_name} gradients)", "data": "synthetic",
         "config": {"workload": f"configs[{a.config - 1}]: {w.name}, {N} params in {lay.n_tensors} tensors, "
-                               f"{lay.n_buckets} buckets, grads {w.grad_dtype}"},
+                               f"{lay.n_buckets} buckets, grads {gdt_name}"},
         "roofline": roofline, "cpu_baseline": cpu, **extras,
     }
     print(json.dumps(out))
