@@ -88,9 +88,40 @@ MUTANTS = [
 ]
 
 
-def _run_mutant(args):
+LBS_PIN_TESTS = ["tests/test_oracle_lbs.py"]
+
+LBS_MUTANTS = [
+    ("rng: increment not multiplied by the draw number", "seed + (k + 1) * 0x9E3779B97F4A7C15ull", "seed + (k + 1) + 0x9E3779B97F4A7C15ull"),
+    ("rng: draw numbers start at 0 instead of 1", "seed + (k + 1) * 0x9E3779B97F4A7C15ull", "seed + k * 0x9E3779B97F4A7C15ull"),
+    ("rng: wrong shift in the first mixing step", "(z ^ (z >> 30))", "(z ^ (z >> 31))"),
+    ("sampling: lower half of the draw used", "const uint64_t u = orc_lbs_splitmix64(seed, k0 + j) >> 32;\n      out[j] = orc_lbs_length_of(cum, max_len, static_cast<uint32_t>((u * total) >> 32));",
+     "const uint64_t u = orc_lbs_splitmix64(seed, k0 + j) & 0xffffffffull;\n      out[j] = orc_lbs_length_of(cum, max_len, static_cast<uint32_t>((u * total) >> 32));"),
+    ("sampling: inverse histogram off by one", "if (cum[l] > index) return l;", "if (cum[l] >= index) return l;"),
+    ("sampling: GPUs of a trial share their draws", "const uint64_t k0 = (trial * n_gpus + gpu) * static_cast<uint64_t>(local_batch);",
+     "const uint64_t k0 = (trial * n_gpus + gpu);"),
+    ("sampling: trials share their draws", "const uint64_t k0 = (trial * n_gpus + gpu) * static_cast<uint64_t>(local_batch);",
+     "const uint64_t k0 = (gpu) * static_cast<uint64_t>(local_batch);"),
+    ("strata: lower bound of the previous stratum's start", "const uint32_t lo = cum[s == 0 ? 0 : stratum_end[s - 1]];   // entries before", "const uint32_t lo = cum[s <= 1 ? 0 : stratum_end[s - 2]];   // entries before"),
+    ("strata: offset inside the stratum dropped", "lo + static_cast<uint32_t>((u * size) >> 32)", "static_cast<uint32_t>((u * size) >> 32)"),
+    ("strata: quota ignored", "for (uint32_t q = 0; q < quota[s]; ++q, ++j) {", "for (uint32_t q = 0; q < local_batch / n_strata; ++q, ++j) {"),
+    ("scatter: no sort", "std::sort(lengths, lengths + static_cast<size_t>(n_group) * local_batch);", ""),
+    ("scatter: snake reverses the even rows", "(snake && (r % 2 == 1))", "(snake && (r % 2 == 0))"),
+    ("scatter: snake never reverses", "(snake && (r % 2 == 1))", "(false)"),
+    ("scatter: contiguous blocks instead of rows", "tokens[g] += lengths[static_cast<size_t>(r) * n_group + c];", "tokens[g] += lengths[static_cast<size_t>(c) * local_batch + r];"),
+    ("local: raster and snake swapped", "method == LBS_LOCAL_SNAKE,\n", "method == LBS_LOCAL_RASTER,\n"),
+    ("local: every node reads the first node's sequences", "const size_t first = static_cast<size_t>(node) * gpus_per_node * local_batch;", "const size_t first = 0;"),
+    ("global: drawn from the stratified dataset", "const bool stratified = method == LBS_STRATIFIED || method == LBS_LOCAL_RASTER || method == LBS_LOCAL_SNAKE;",
+     "const bool stratified = method != LBS_NONE;"),
+    ("global: snake order", "orc_lbs_presort_scatter(gathered.data(), n_gpus, local_batch, 0, tokens.data());", "orc_lbs_presort_scatter(gathered.data(), n_gpus, local_batch, 1, tokens.data());"),
+    ("result: last GPU left out of min/max", "for (uint32_t g = 1; g < n_gpus; ++g) lo =", "for (uint32_t g = 1; g + 1 < n_gpus; ++g) lo ="),
+    ("result: sums not accumulated", "sums[0] += lo;", "sums[0] = lo;"),
+]
+
+
+def _run_mutant(args, src_path=None, env_name="BCA_ORACLE_LIB", pin_tests=None):
     idx, (name, old, new) = args
-    src = open(obuild.SRC).read()
+    pin_tests = pin_tests or PIN_TESTS
+    src = open(src_path or obuild.SRC).read()
     if src.count(old) < 1:
         return name, "pattern not found in oracle source"
     with tempfile.TemporaryDirectory() as td:
@@ -101,8 +132,8 @@ def _run_mutant(args):
                            check=True, capture_output=True)
         except subprocess.CalledProcessError as e:
             return name, "mutant does not compile: " + e.stderr.decode()[-300:]
-        env = dict(os.environ, BCA_ORACLE_LIB=mlib)
-        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_TESTS],
+        env = dict(os.environ, **{env_name: mlib})
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *pin_tests],
                            cwd=ROOT, env=env, capture_output=True)
         if r.returncode == 0:
             return name, "SURVIVED: no pin test failed"
@@ -114,5 +145,13 @@ def _run_mutant(args):
 def test_every_planted_mistake_is_caught_by_a_pin():
     with ThreadPoolExecutor(max_workers=6) as ex:
         results = list(ex.map(_run_mutant, enumerate(MUTANTS)))
+    problems = [f"{n}: {why}" for n, why in results if why]
+    assert not problems, "\n".join(problems)
+
+
+def test_every_planted_mistake_in_the_load_balancing_oracle_is_caught_by_a_pin():
+    run = lambda a: _run_mutant(a, obuild.LBS_SRC, "LBS_ORACLE_LIB", LBS_PIN_TESTS)
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        results = list(ex.map(run, enumerate(LBS_MUTANTS)))
     problems = [f"{n}: {why}" for n, why in results if why]
     assert not problems, "\n".join(problems)

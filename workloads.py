@@ -345,6 +345,47 @@ def scaled_bert_numels(hidden: int, n_layers: int, ffn: int, vocab: int = 3052, 
     return [n for _, n in bert_tensor_list(vocab, hidden, n_layers, ffn, max_pos)]
 
 
+# ----------------------------------------------------------------------------
+# sequence-length histograms for the load-balancing simulation
+# ----------------------------------------------------------------------------
+
+# Sec. 4.1: four strata by length; Sec. 3.1: share of the Wikipedia samples in each.
+LENGTH_STRATUM_END = (128, 256, 384, 512)
+LENGTH_STRATUM_SHARE = (0.373, 0.197, 0.117, 0.314)
+
+
+def length_histogram_piecewise_uniform(n_samples: int = 10_000_000, stratum_end: Sequence[int] = LENGTH_STRATUM_END,
+                                       share: Sequence[float] = LENGTH_STRATUM_SHARE) -> np.ndarray:
+    """Cumulative length histogram cum[0..L] (uint32, cum[l] = number of samples of length <= l)
+    of a synthetic dataset that has the printed share of samples in every stratum and, inside a
+    stratum, equally many samples of every length.  Stands in for the Wikipedia histogram, which
+    the paper does not print."""
+    L = int(stratum_end[-1])
+    hist = np.zeros(L + 1, np.int64)
+    lo = 0
+    for end, sh in zip(stratum_end, share):
+        n = int(round(sh / sum(share) * n_samples))
+        width = end - lo
+        hist[lo + 1:end + 1] = n // width
+        hist[lo + 1:lo + 1 + n % width] += 1
+        lo = end
+    cum = np.cumsum(hist)
+    assert cum[-1] < 2 ** 32
+    return cum.astype(np.uint32)
+
+
+def stratum_quota(cum: np.ndarray, stratum_end: Sequence[int], local_batch: int) -> np.ndarray:
+    """Samples per stratum in a local batch, in proportion to the strata's sizes
+    (largest-remainder rounding so that they add up to local_batch)."""
+    ends = [0] + [int(e) for e in stratum_end]
+    sizes = np.asarray([int(cum[b]) - int(cum[a]) for a, b in zip(ends[:-1], ends[1:])], np.float64)
+    ideal = sizes / sizes.sum() * local_batch
+    q = np.floor(ideal).astype(np.int64)
+    for i in np.argsort(-(ideal - q), kind="stable")[:local_batch - int(q.sum())]:
+        q[i] += 1
+    return q.astype(np.uint32)
+
+
 CONFIGS = {
     1: config_tiny,
     2: config_bert_base,
