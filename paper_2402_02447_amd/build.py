@@ -1,4 +1,5 @@
-"""Compile libbca.so (host side + HIP kernels) for gfx950, in-tree."""
+"""Compile libbca.so (host side + HIP kernels of the clip + optimizer path, and the load-balancing
+simulation) for gfx950, in-tree."""
 from __future__ import annotations
 
 import os
@@ -8,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbca.so")
-SOURCES = [os.path.join(CSRC, "bca_host.cpp"), os.path.join(CSRC, "bca_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "bca_host.cpp"), os.path.join(CSRC, "bca_kernels.hip"), os.path.join(CSRC, "lbs.hip")]
 
 # Packed fp32 instructions are switched off for all device code.
 HIPCC_FLAGS = [

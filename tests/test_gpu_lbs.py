@@ -1,0 +1,87 @@
+"""GPU parity of the load-balancing simulation: every trial's minimum and maximum
+per-GPU token count and the two sums must equal the oracle's, bit for bit (all
+integer work, same counter-based draws on both sides)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import lbs as O
+from paper_2402_02447_amd import lbs
+
+pytestmark = pytest.mark.gpu
+
+CUM = W.length_histogram_piecewise_uniform()
+ENDS = W.LENGTH_STRATUM_END
+
+
+def run_gpu(ds, method, b, P, G, quota, seed, n, first=0, with_trials=True, stream=None):
+    sums = torch.full((2,), 77, dtype=torch.int64, device="cuda")           # stale contents must be overwritten
+    tmin = torch.full((max(n, 1),), 0xABCD, dtype=torch.int32, device="cuda") if with_trials else None
+    tmax = torch.full((max(n, 1),), 0xABCD, dtype=torch.int32, device="cuda") if with_trials else None
+    ds.lbs_simulate(method, b, P, G, quota, seed, n, sums, tmin, tmax, first_trial=first, stream=stream)
+    torch.cuda.synchronize()
+    s = sums.cpu().numpy()
+    if not with_trials:
+        return None, None, int(s[0]), int(s[1])
+    return tmin.cpu().numpy().view(np.uint32)[:n], tmax.cpu().numpy().view(np.uint32)[:n], int(s[0]), int(s[1])
+
+
+def check(cum, ends, method, b, P, G, quota, seed, n, first=0):
+    with lbs.Dataset(cum, ends, device=torch.cuda.current_device()) as ds:
+        gmin, gmax, g0, g1 = run_gpu(ds, method, b, P, G, quota, seed, n, first)
+        _, _, h0, h1 = run_gpu(ds, method, b, P, G, quota, seed, n, first, with_trials=False)
+    omin, omax, o0, o1 = O.simulate(cum, ends, quota if quota is not None else [b] + [0] * (len(ends) - 1), b, P, G,
+                                    method, seed, n, first_trial=first)
+    assert np.array_equal(gmin, omin), (method, np.flatnonzero(gmin != omin)[:5])
+    assert np.array_equal(gmax, omax), (method, np.flatnonzero(gmax != omax)[:5])
+    assert (g0, g1) == (o0, o1) == (h0, h1)
+    return g0 / max(n, 1), g1 / max(n, 1)
+
+
+@pytest.mark.parametrize("method", [lbs.LBS_NONE, lbs.LBS_STRATIFIED, lbs.LBS_LOCAL_RASTER, lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL])
+def test_paper_setting_1024_gpus_batch_16_nodes_of_8(method):
+    quota = [int(q) for q in W.stratum_quota(CUM, ENDS, 16)]
+    lo, hi = check(CUM, ENDS, method, 16, 8, 1024, quota, seed=11, n=200)
+    assert 1000 < lo <= hi < 8192
+
+
+@pytest.mark.parametrize("method", [lbs.LBS_NONE, lbs.LBS_STRATIFIED, lbs.LBS_LOCAL_RASTER, lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL])
+def test_ragged_sizes_and_other_strata(method):
+    # sizes that are no multiples of the wavefront or the workgroup, 3 strata, odd batch, first_trial > 0
+    cum = W.length_histogram_piecewise_uniform(70_001, (50, 201, 333), (0.2, 0.5, 0.3))
+    check(cum, (50, 201, 333), method, 7, 3, 3 * 67, [2, 4, 1], seed=5, n=37, first=1_000_003)
+    # one GPU per node, one node spanning everything, a node pool at the limit of 1024
+    check(cum, (50, 201, 333), method, 7, 1, 9, [2, 4, 1], seed=6, n=5)
+    check(cum, (50, 201, 333), method, 7, 9, 9, [0, 7, 0], seed=7, n=5)
+    check(CUM, ENDS, method, 64, 16, 32, [1, 1, 1, 61], seed=8, n=3)
+
+
+def test_degenerate_dataset_single_gpu_zero_trials_and_fig3_quota():
+    cum = np.zeros(513, np.uint32)
+    cum[100:] = 1000                                        # every sequence has length 100
+    for method in range(5):
+        lo, hi = check(cum, (512,), method, 16, 8, 64, [16], seed=1, n=4)
+        assert lo == hi == 1600
+        check(CUM, ENDS, method, 16, 1, 1, [5, 2, 3, 6], seed=2, n=6)          # a single GPU: min = max
+        check(CUM, ENDS, method, 16, 8, 64, [5, 2, 3, 6], seed=3, n=0)          # no trials: sums are cleared
+    # the paper's example quota (Fig. 3) on 64 GPUs
+    check(CUM, ENDS, lbs.LBS_LOCAL_SNAKE, 16, 8, 64, [5, 2, 3, 6], seed=4, n=100)
+
+
+def test_max_len_1024_and_many_gpus():
+    cum = W.length_histogram_piecewise_uniform(3_000_000, (256, 512, 768, 1024), (0.1, 0.2, 0.3, 0.4))
+    for method in (lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL):
+        check(cum, (256, 512, 768, 1024), method, 16, 8, 4096, [2, 3, 5, 6], seed=9, n=6)
+
+
+def test_runs_on_a_side_stream_and_trials_split_across_calls():
+    quota = [6, 3, 2, 5]
+    with lbs.Dataset(CUM, ENDS, device=0) as ds:
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        a = run_gpu(ds, lbs.LBS_LOCAL_SNAKE, 16, 8, 256, quota, 21, 60, stream=s)
+        b1 = run_gpu(ds, lbs.LBS_LOCAL_SNAKE, 16, 8, 256, quota, 21, 25)
+        b2 = run_gpu(ds, lbs.LBS_LOCAL_SNAKE, 16, 8, 256, quota, 21, 35, first=25)
+    assert np.array_equal(a[0], np.concatenate([b1[0], b2[0]])) and np.array_equal(a[1], np.concatenate([b1[1], b2[1]]))
+    assert a[2] == b1[2] + b2[2] and a[3] == b1[3] + b2[3]
