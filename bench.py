@@ -35,9 +35,12 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="benchmark configuration: 2 BERT-Base 25 MiB, 3 BERT-Large 50 MiB, 4 fp16 1 MiB, 5 4 MiB")
-    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms"],
+    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms", "lbs"],
                     help="what one step is: the fused bucket_clip_adam (headline, default), adam_step alone, "
-                         "bucket_clip_lamb, lamb_step, or bucket_clip_norms alone")
+                         "bucket_clip_lamb, lamb_step, bucket_clip_norms alone, or (lbs) the load-balancing "
+                         "simulation: one step = --lbs-trials trials of each of the five methods")
+    ap.add_argument("--lbs-trials", type=int, default=100000)
+    ap.add_argument("--lbs-gpus", type=int, default=1024)
     ap.add_argument("--grad-dtype", default="", choices=["", "f32", "f16", "bf16"],
                     help="override the configuration's gradient storage type")
     ap.add_argument("--decay-mask", action="store_true", help="exempt biases and LayerNorm tensors from weight decay")
@@ -119,6 +122,82 @@ def other_ops(a, w, plan, g, p, m, v, dev):
     }))
 
 
+def lbs_bench(a, dev):
+    """Load-balancing simulation (Sec. 5.2, Table 5) at the paper's setting: local batch 16, nodes of 8 GPUs,
+    --lbs-gpus GPUs, --lbs-trials trials per method.  One JSON line: simulated sequence draws per second over
+    the five methods, the table of average minimum / maximum token counts, and the oracle timed on a sample."""
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2402_02447_amd import lbs
+    cum = W.length_histogram_piecewise_uniform()
+    ends = W.LENGTH_STRATUM_END
+    quota = [int(q) for q in W.stratum_quota(cum, ends, 16)]
+    G, b, P, n = a.lbs_gpus, 16, 8, a.lbs_trials
+    names = {lbs.LBS_NONE: "no balancing", lbs.LBS_STRATIFIED: "+ stratification", lbs.LBS_LOCAL_RASTER: "+ local presorting",
+             lbs.LBS_LOCAL_SNAKE: "+ snake scanning", lbs.LBS_GLOBAL: "global presorting"}
+    ds = lbs.Dataset(cum, ends, device=0)
+    stream = torch.cuda.current_stream()
+    sums = {m: torch.zeros(2, dtype=torch.int64, device=dev) for m in names}
+
+    def one_step():
+        for m in names:
+            ds.lbs_simulate(m, b, P, G, quota, 2024, n, sums[m], stream=stream)
+    for _ in range(a.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    per_method = {}
+    for m in names:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        ds.lbs_simulate(m, b, P, G, quota, 2024, n, sums[m], stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        per_method[m] = e0.elapsed_time(e1)
+    table = {names[m]: {"avg_min": round(int(sums[m][0]) / n, 1), "avg_max": round(int(sums[m][1]) / n, 1),
+                        "ms": round(per_method[m], 3)} for m in names}
+    draws = 5 * n * G * b
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import lbs as O
+        n_cpu = max(1, min(n, 2000 * 1024 // G))
+        t1 = time.perf_counter()
+        for m in names:
+            _, _, s0, s1 = O.simulate(cum, ends, quota, b, P, G, m, 2024, n_cpu)
+        dt = time.perf_counter() - t1
+        cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
+    # dominant kernel: k_lbs_local (two of the five methods).  Integer lane operations per draw, counted from the
+    # source: SplitMix64 ~40 (four 64-bit multiplies of ~6 32-bit operations, three 64-bit shift-xor pairs), index
+    # scaling 2, ten binary-search steps of ~5, so ~100 for the draw; the bitonic network on a pool of 128 has 28
+    # stages of 64 compare-exchanges = 14 per draw at ~12 operations (index arithmetic, two LDS reads, compare, two
+    # LDS writes); the deal adds ~4.  About 280 per draw: an estimate, good to perhaps 20 %.
+    ops_per_draw = 280
+    t_local = (per_method[lbs.LBS_LOCAL_RASTER] + per_method[lbs.LBS_LOCAL_SNAKE]) / 2 * 1e-3
+    achieved = ops_per_draw * n * G * b / t_local / 1e12
+    peak = 256 * 4 * 16 * 2.4e9 / 1e12          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s
+    print(json.dumps({
+        "metric": "load-balancing simulation throughput (sequence draws simulated per second, five methods)",
+        "value": round(draws / (ms * 1e-3) / 1e9, 3), "unit": "G draws/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32/u64",
+        "data": "synthetic",
+        "config": {"workload": f"Table 5 setting: {G} simulated GPUs, local batch {b}, nodes of {P}, {n} trials per method, "
+                               f"piecewise-uniform length histogram with the printed stratum shares, quota {quota}"},
+        "roofline": {"bound": "alu", "kernel": "k_lbs_local (draws, bitonic sort per node in LDS, raster / snake deal)",
+                     "achieved": round(achieved, 2), "peak": round(peak, 1), "unit": "T lane-ops/s",
+                     "frac": round(achieved / peak, 3), "traffic": None, "ops_per_draw": ops_per_draw,
+                     "ms_per_launch": round(t_local * 1e3, 3)},
+        "cpu_baseline": cpu, "table": table,
+    }))
+    ds.close()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -134,6 +213,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if a.op == "lbs":
+        lbs_bench(a, dev)
+        return
 
     w = W.CONFIGS[a.config]()
     lay = w.layout

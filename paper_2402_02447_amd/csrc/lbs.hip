@@ -8,10 +8,10 @@
 // the outputs are two words per trial.
 //   NONE / STRATIFIED : a thread owns whole GPUs; 16 draws, one sum each.
 //   LOCAL_*           : a wavefront owns a node: its lanes draw the node's pool into
-//                       LDS, rank every entry against the pool (the rank is the
-//                       entry's place in the sorted order; equal lengths are ordered
-//                       by position so that ranks are distinct), write the sorted
-//                       pool, and add up each GPU's column in raster or snake order.
+//                       LDS (padded to a power of two with a sentinel above every
+//                       length), sort it there with a bitonic network (log^2 stages
+//                       of independent compare-exchanges, one pair per lane), and add
+//                       up each GPU's column in raster or snake order.
 //   GLOBAL            : lengths are small integers, so the trial's pool of
 //                       n_gpus * local_batch draws is sorted by counting: an LDS
 //                       histogram, a block-wide prefix sum, and the entry at sorted
@@ -134,41 +134,45 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
                                                        uint32_t* trial_min, uint32_t* trial_max,
                                                        unsigned long long* sums) {
   __shared__ uint32_t s_cum[LBS_MAX_LEN + 1];
-  __shared__ uint32_t s_pool[kWaves][LBS_MAX_NODE_POOL], s_sorted[kWaves][LBS_MAX_NODE_POOL];
+  __shared__ uint32_t s_pool[kWaves][LBS_MAX_NODE_POOL];
   __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
   load_histogram(s_cum, cum, P.max_len);
   const uint64_t trial = P.first_trial + blockIdx.x;
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   const uint32_t n_nodes = P.n_gpus / P.gpus_per_node;
   const uint32_t pool = P.gpus_per_node * P.local_batch;
+  uint32_t padded = 2;  // the network sorts a power of two
+  while (padded < pool) padded <<= 1;
   uint32_t* mine = s_pool[wave];
-  uint32_t* sorted = s_sorted[wave];
   uint32_t lo = 0xffffffffu, hi = 0u;
-  // every wavefront makes the same number of rounds, so the barriers below are met by all
+  // Every wavefront makes the same number of rounds and stages, so the barriers below are
+  // met by all; a wavefront without a node in the last round only keeps them company.
   for (uint32_t base = 0; base < n_nodes; base += kWaves) {
     const uint32_t node = base + wave;
     const bool active = node < n_nodes;
     if (active)
-      for (uint32_t i = lane; i < pool; i += 64u)
-        mine[i] = draw(P, s_cum, trial, node * P.gpus_per_node + i / P.local_batch, i % P.local_batch);
+      for (uint32_t i = lane; i < padded; i += 64u)
+        mine[i] = i < pool ? draw(P, s_cum, trial, node * P.gpus_per_node + i / P.local_batch, i % P.local_batch)
+                           : 0xffffffffu;
     __syncthreads();
-    if (active)
-      for (uint32_t i = lane; i < pool; i += 64u) {
-        const uint32_t x = mine[i];
-        uint32_t rank = 0;
-        for (uint32_t q = 0; q < pool; ++q) {
-          const uint32_t y = mine[q];  // same address in all lanes: an LDS broadcast
-          rank += (y < x || (y == x && q < i)) ? 1u : 0u;
-        }
-        sorted[rank] = x;
+    for (uint32_t k = 2; k <= padded; k <<= 1)
+      for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+        if (active)
+          for (uint32_t t = lane; t < (padded >> 1); t += 64u) {
+            const uint32_t a = ((t & ~(j - 1u)) << 1) | (t & (j - 1u));  // t with a 0 inserted at j's bit
+            const uint32_t b = a | j;
+            const uint32_t x = mine[a], y = mine[b];
+            const bool ascending = (a & k) == 0u;
+            if ((x > y) == ascending) mine[a] = y, mine[b] = x;
+          }
+        __syncthreads();
       }
-    __syncthreads();
     if (active)
       for (uint32_t c = lane; c < P.gpus_per_node; c += 64u) {
         uint32_t tokens = 0;
         for (uint32_t r = 0; r < P.local_batch; ++r) {
           const uint32_t col = (P.snake && (r & 1u)) ? P.gpus_per_node - 1u - c : c;  // position in the row dealt to GPU c
-          tokens += sorted[r * P.gpus_per_node + col];
+          tokens += mine[r * P.gpus_per_node + col];
         }
         lo = min(lo, tokens), hi = max(hi, tokens);
       }
