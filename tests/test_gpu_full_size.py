@@ -153,3 +153,14 @@ def test_bert_large_lamb_bf16_masked_full_size():
     print(f"[lamb] norm rel {rel:.2e}; trust rel {trel.max():.2e}; p {rp}; m {rm}; v {rv}", flush=True)
     assert bits_equal(to_host(dev.g), g)
     dev.close()
+
+
+def test_bert_large_whole_tensor_buckets_full_size():
+    # DDP-style packing: whole tensors per bucket (the 31 M-element word embedding is one bucket of its own)
+    lay = W.layout_whole_tensors(W.bert_large_numels(), 50 * W.MIB // 4)
+    assert lay.tensors_split() == 0 and lay.n_buckets < 26
+    w = W.config_bert_large()
+    w = W.Workload("bert_large_whole_tensor_buckets", lay, "f32", np.full(lay.n_buckets, 1.0, np.float32), w.hyper,
+                   first_step=1000, seed=0, warm=True)
+    coefs = full_fused(w, B.BCA_WRITE_BACK_GRADS)
+    assert (coefs < 1).all()
