@@ -26,7 +26,9 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # Bytes crossing the L2 <-> fabric boundary in one launch of the dominant kernel, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for libbca's plain copy kernel
 # (profiles/k_step_bert_large_fp32_50MiB_hbm_counters.txt).  Key: (config, gradient type, single_launch).
-MEASURED_TRAFFIC_BYTES = {(3, "f32", True): 10835977229}
+MEASURED_TRAFFIC_BYTES = {(3, "f32", True): 10800186368}
+# The same for the other entry points (all kernels of one call summed), config 3, fp32 gradients.
+MEASURED_TRAFFIC_OTHER_OPS = {"adam": 9446928384, "norms": 1341876224, "lamb": 13542207488, "clip_lamb": 14889451520}
 
 
 def parse():
@@ -115,7 +117,9 @@ def other_ops(a, w, plan, g, p, m, v, dev):
         "data": "synthetic",
         "config": {"workload": f"configs[{a.config - 1}]: {w.name}, {N} params, {lay.n_buckets} buckets, op {a.op}"},
         "roofline": {"bound": "hbm", "kernel": what, "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_elt": per_elt,
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_OTHER_OPS.get(a.op) if (a.config == 3 and gb == 4) else None,
+                     "bytes_per_elt": per_elt,
                      "ms_per_launch": round(med, 4)},
         "cpu_baseline": None, "ms_per_step_median": round(med, 4), "ms_per_step_min": round(per[0], 4),
         "status": int(status.item()),
@@ -260,6 +264,15 @@ def main():
     if a.decay_mask:
         H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)
         plan.set_decay_mask(W.bert_decay_mask(30522, H, L, F, 512))
+    if a.calibrate_copy:     # a kernel with exactly known traffic, for counter runs
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(a.calibrate_copy):
+            B.copy_bytes(dst, src, 1 << 30, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert bool((dst[:: 1 << 20] == 7).all())
+        del src, dst
     if a.op != "clip_adam":
         other_ops(a, w, plan, g, p, m, v, dev)
         plan.close()
@@ -274,16 +287,6 @@ def main():
     host = None
     if not a.no_cpu_baseline:
         host = [[t.cpu().numpy() for t in xs] for xs in (g, p, m, v)]
-
-    if a.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(a.calibrate_copy):
-            B.copy_bytes(dst, src, 1 << 30, stream)
-        torch.cuda.synchronize()
-        assert bool((dst[:: 1 << 20] == 7).all())
-        del src, dst
 
     step = w.first_step
     def one_step():
