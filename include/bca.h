@@ -92,7 +92,8 @@ typedef struct bca_adam {
 #define BCA_TUNE_STAGE_TABLE_LDS 2u /* multi-launch kernels: persistent workgroups stage chunk-table
                                        slices in LDS                                                 */
 typedef struct bca_tuning {
-  uint32_t chunk_norm;   /* largest chunk of the squared-norm pass, elements, multiple of 1024  */
+  uint32_t chunk_norm;   /* largest chunk of the squared-norm pass, elements, multiple of 1024;
+                            0: chosen from the bucket sizes (16 Ki .. 64 Ki)                     */
   uint32_t chunk_apply;  /* largest chunk of the scale / Adam passes, elements, multiple of 1024 */
   uint32_t grid_norm;    /* workgroups of the squared-norm kernel (0: one per chunk)            */
   uint32_t grid_apply;   /* workgroups of the scale / Adam kernels (0: one per chunk)           */

@@ -167,6 +167,20 @@ void build_groups(bca_plan* p, uint64_t group_bytes, const uint64_t* seg_off, co
   p->groups.emplace_back(first, p->n_buckets);
 }
 
+// Squared-norm chunk size when the caller names none: the largest power of two in
+// [16 Ki, 64 Ki] that still gives an average bucket group 160 chunks or more.  Fewer, larger
+// chunks mean fewer partial sums and arrivals; but a group's squared-norm items are all
+// that keeps its Adam items from waiting, and below ~200 of them (256 CUs) they finish
+// late (measured: 64 Ki best for 50 MiB buckets, 32 Ki for 25 MiB and 4 MiB ones).
+uint32_t default_chunk_norm(const bca_plan* p, const uint64_t* seg_off, const bca_segment* segs) {
+  uint64_t total = 0;
+  for (uint64_t s = 0; s < seg_off[p->n_buckets]; ++s) total += segs[s].len;
+  const uint64_t per_group = total / std::max<size_t>(p->groups.size(), 1);
+  uint32_t c = kDefaultChunkNorm;
+  while (c > kMinAutoChunkNorm && per_group / c < 160) c >>= 1;
+  return c;
+}
+
 // Work items of the single-launch step in pipeline order: the squared-norm
 // chunks of group i+1 come before the Adam chunks of group i, so that by the
 // time a bucket's Adam items start, its norm has long been finished, and its
@@ -334,7 +348,7 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
     return fail(BCA_ERR_DTYPE, "unknown gradient type");
   if (bucket_seg_off[n_buckets] && !segments) return fail(BCA_ERR_NULL, "segments is NULL");
   if (device < -1) return fail(BCA_ERR_RANGE, "device must be >= 0, or -1 for a host-only plan");
-  uint32_t chunk_norm = kDefaultChunkNorm, chunk_apply = kDefaultChunkApply, unroll = 0;
+  uint32_t chunk_norm = 0, chunk_apply = kDefaultChunkApply, unroll = 0;
   if (tuning) {
     for (uint32_t c : {tuning->chunk_norm, tuning->chunk_apply})
       if (c % 1024u || c > (1u << 24)) return fail(BCA_ERR_RANGE, "chunk sizes must be multiples of 1024, at most 2^24");
@@ -363,10 +377,11 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   p->tune_flags = tuning ? tuning->flags : 0;
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
   p->decay.assign(n_tensors, 1);
+  build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
+  if (chunk_norm == 0) chunk_norm = default_chunk_norm(p, bucket_seg_off, segments);
   build_table(&p->norm_tab, chunk_norm, n_buckets, bucket_seg_off, segments);
   build_table(&p->apply_tab, chunk_apply, n_buckets, bucket_seg_off, segments);
   build_tensor_table(&p->lamb_tab, &p->tensor_off, chunk_apply, n_tensors, n_buckets, bucket_seg_off, segments);
-  build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
   build_work(p);
   // A launch holds at most 2^32 threads: with 256 per workgroup that is 2^24 workgroups.
   if (p->work.size() >= (1ull << 24)) {

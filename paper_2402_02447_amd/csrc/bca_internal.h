@@ -61,7 +61,8 @@ struct AdamK {
 constexpr uint32_t kBlock = 256;          // threads per workgroup (4 wavefronts)
 constexpr uint32_t kWaves = kBlock / 64;  // wavefronts per workgroup
 constexpr uint32_t kSlice = 64;           // chunk-table entries staged in LDS at a time
-constexpr uint32_t kDefaultChunkNorm = 65536;
+constexpr uint32_t kDefaultChunkNorm = 65536;  // upper end of the automatic choice
+constexpr uint32_t kMinAutoChunkNorm = 16384;  // lower end
 constexpr uint32_t kDefaultChunkApply = 1024;
 // Buckets are pipelined in groups of about this many elements (at least one bucket):
 // large enough that a group's norms are done before its Adam items start, small enough

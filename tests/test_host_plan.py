@@ -74,12 +74,18 @@ def test_chunk_table_partitions_the_layout(chunk, table):
 
 def test_chunk_counts_and_groups_of_the_bert_large_configs():
     N = 335_141_888
-    for make in (W.config_bert_large, W.config_bert_large_fp16):
+    # default cuts: 1 024 elements for the read-write passes; for the norm pass the largest power of two in
+    # [16 Ki, 64 Ki] that leaves an average bucket group at least 160 chunks: 64 Ki for 50 MiB buckets (one per
+    # group), 32 Ki for 1 MiB buckets (32 per group of 8 Mi elements)
+    for make, cn in ((W.config_bert_large, 65536), (W.config_bert_large_fp16, 32768)):
         w = make()
         p = host_plan(w.layout)
-        # default cuts: 65 536 elements for the norm pass, 1 024 for the read-write passes
-        assert -(-N // 65536) <= p.n_chunks(B.BCA_TABLE_NORM) <= -(-N // 65536) + 2 * w.layout.n_segments
+        assert -(-N // cn) <= p.n_chunks(B.BCA_TABLE_NORM) <= -(-N // cn) + 2 * w.layout.n_segments
+        assert max(p.chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(0, p.n_chunks(B.BCA_TABLE_NORM), 7)) == cn
         assert -(-N // 1024) <= p.n_chunks(B.BCA_TABLE_APPLY) <= -(-N // 1024) + 2 * w.layout.n_segments
+    assert max(host_plan(W.config_bert_base().layout).chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(100)) == 32768
+    assert max(host_plan(W.config_tiny().layout).chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(3)) == 12345
+    assert host_plan(W.config_bert_base().layout, chunk_norm=4096).n_chunks(B.BCA_TABLE_NORM) > 109_482_240 // 4096
     w = W.config_bert_large()
     assert host_plan(w.layout).n_groups == 26                          # default 8 Mi elements: one 50 MiB bucket per group
     assert host_plan(w.layout, group_bytes=110 << 20).n_groups == 13   # two per group
