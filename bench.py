@@ -177,12 +177,10 @@ def lbs_bench(a, dev):
         dt = time.perf_counter() - t1
         cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
-    # dominant kernel: k_lbs_local (two of the five methods).  Integer lane operations per draw, counted from the
-    # source: SplitMix64 ~40 (four 64-bit multiplies of ~6 32-bit operations, three 64-bit shift-xor pairs), index
-    # scaling 2, ten binary-search steps of ~5, so ~100 for the draw; the bitonic network on a pool of 128 has 28
-    # stages of 64 compare-exchanges = 14 per draw at ~12 operations (index arithmetic, two LDS reads, compare, two
-    # LDS writes); the deal adds ~4.  About 280 per draw: an estimate, good to perhaps 20 %.
-    ops_per_draw = 280
+    # dominant kernel: k_lbs_local (two of the five methods).  Vector instructions it executes, from a rocprofv3
+    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 8.843e9 wavefront
+    # instructions per 100 000 trials at 1 024 GPUs = 345 lane-operation slots per draw (64 lanes per instruction).
+    ops_per_draw = 345
     t_local = (per_method[lbs.LBS_LOCAL_RASTER] + per_method[lbs.LBS_LOCAL_SNAKE]) / 2 * 1e-3
     achieved = ops_per_draw * n * G * b / t_local / 1e12
     peak = 256 * 4 * 16 * 2.4e9 / 1e12          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s

@@ -635,19 +635,30 @@ __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict
   }
 }
 
-// One workgroup per tensor: the chunk sums in index order (strided over the threads,
-// butterfly, four wavefronts), then trust = ||p|| / ||u||, or 1 where either norm is
-// zero and the quotient means nothing; scale = -lr * trust in fp64, rounded once.
-__global__ __launch_bounds__(kBlock) void k_lamb_trust(const double* __restrict__ sums,
-                                                        const uint32_t* __restrict__ tensor_off, double lr,
-                                                        float* __restrict__ trust, float* __restrict__ scale) {
-  __shared__ double s_pp[kWaves], s_uu[kWaves];
-  const uint32_t t = blockIdx.x;
-  double pp = 0.0, uu = 0.0;
-  for (uint32_t c = tensor_off[t] + threadIdx.x; c < tensor_off[t + 1]; c += kBlock)
-    pp += sums[(uint64_t)c * 2u], uu += sums[(uint64_t)c * 2u + 1u];
-  const double tpp = block_sum(pp, s_pp), tuu = block_sum(uu, s_uu);
+// One workgroup of 1024 threads per tensor: the chunk sums strided over the threads (two
+// independent accumulators each, the word embedding alone has 30 K chunks), butterfly per
+// wavefront, the sixteen wavefronts in index order; then trust = ||p|| / ||u||, or 1
+// where either norm is zero and the quotient means nothing; scale = -lr * trust in fp64,
+// rounded once.  The order is fixed, so the ratios are reproducible.
+constexpr uint32_t kTrustBlock = 1024;
+__global__ __launch_bounds__(kTrustBlock) void k_lamb_trust(const double* __restrict__ sums,
+                                                             const uint32_t* __restrict__ tensor_off, double lr,
+                                                             float* __restrict__ trust, float* __restrict__ scale) {
+  __shared__ double s_pp[kTrustBlock / 64], s_uu[kTrustBlock / 64];
+  const uint32_t t = blockIdx.x, lo = tensor_off[t], hi = tensor_off[t + 1];
+  double pp0 = 0.0, uu0 = 0.0, pp1 = 0.0, uu1 = 0.0;
+  uint32_t c = lo + threadIdx.x;
+  for (; c + kTrustBlock < hi; c += 2u * kTrustBlock) {
+    pp0 += sums[(uint64_t)c * 2u], uu0 += sums[(uint64_t)c * 2u + 1u];
+    pp1 += sums[(uint64_t)(c + kTrustBlock) * 2u], uu1 += sums[(uint64_t)(c + kTrustBlock) * 2u + 1u];
+  }
+  if (c < hi) pp0 += sums[(uint64_t)c * 2u], uu0 += sums[(uint64_t)c * 2u + 1u];
+  const double pp = wave_sum(pp0 + pp1), uu = wave_sum(uu0 + uu1);
+  if ((threadIdx.x & 63u) == 0) s_pp[threadIdx.x >> 6] = pp, s_uu[threadIdx.x >> 6] = uu;
+  __syncthreads();
   if (threadIdx.x == 0) {
+    double tpp = 0.0, tuu = 0.0;
+    for (uint32_t w = 0; w < kTrustBlock / 64; ++w) tpp += s_pp[w], tuu += s_uu[w];
     const double pn = sqrt(tpp), un = sqrt(tuu);
     const double r = (pn > 0.0 && un > 0.0) ? pn / un : 1.0;
     trust[t] = (float)r;
@@ -1096,7 +1107,7 @@ hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const fl
 hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, double lr,
                              float* trust, float* scale, hipStream_t stream) {
   if (n_tensors == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kBlock), 0, stream, sums, tensor_off, lr, trust, scale);
+  hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kTrustBlock), 0, stream, sums, tensor_off, lr, trust, scale);
   return hipGetLastError();
 }
 
