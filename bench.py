@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--grid-norm", type=int, default=0)
     ap.add_argument("--grid-apply", type=int, default=0)
     ap.add_argument("--tune-flags", type=int, default=0)
-    ap.add_argument("--oracle-steps", type=int, default=3)
+    ap.add_argument("--oracle-steps", type=int, default=8)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many 1 GiB plain copies (k_copy) so that counter runs have a known reference")
     return ap.parse_args()
