@@ -1,0 +1,78 @@
+/* Plain C (C99) user of the two C ABIs, host-only: proves that the headers are C, that the
+ * library can be driven without Python or torch, and that argument checks work before any
+ * GPU is touched.  Built and run by tests/test_c_abi.py. */
+#include <stdio.h>
+#include <string.h>
+
+#include "bca.h"
+#include "lbs.h"
+
+#define CHECK(cond)                                                        \
+  do {                                                                     \
+    if (!(cond)) {                                                         \
+      printf("FAILED line %d: %s (bca: %s; lbs: %s)\n", __LINE__, #cond, bca_last_error(), lbs_last_error()); \
+      return 1;                                                            \
+    }                                                                      \
+  } while (0)
+
+int main(void) {
+  /* two tensors of 3000 and 500 elements in two buckets; tensor 0 is split between them */
+  const uint64_t numel[2] = {3000, 500};
+  const uint64_t seg_off[3] = {0, 2, 3};
+  bca_segment segs[3];
+  bca_plan* plan = NULL;
+  bca_tuning tune;
+  uint32_t tensor = 0, len = 0, bucket = 0, first = 0, count = 0;
+  uint64_t begin = 0;
+  const uint8_t mask[2] = {1, 0};
+  bca_adam hp = {1e-3, 0.9, 0.999, 1e-6, 0.01};
+  float dummy = 0.f;
+
+  memset(segs, 0, sizeof segs);
+  segs[0].tensor = 1, segs[0].begin = 0, segs[0].len = 500;
+  segs[1].tensor = 0, segs[1].begin = 2000, segs[1].len = 1000;
+  segs[2].tensor = 0, segs[2].begin = 0, segs[2].len = 2000;
+  memset(&tune, 0, sizeof tune);
+  tune.chunk_norm = 1024, tune.chunk_apply = 1024;
+
+  CHECK(bca_version() >= 1);
+  CHECK(bca_plan_create(&plan, -1, 2, numel, 2, seg_off, segs, BCA_GRAD_BF16, &tune) == BCA_OK);
+  CHECK(bca_plan_num_buckets(plan) == 2);
+  /* tensor 0: [0,1024) [1024,2000) in bucket 1, [2000,2048) [2048,3000) in bucket 0; tensor 1: one chunk */
+  CHECK(bca_plan_num_chunks(plan, BCA_TABLE_APPLY) == 5);
+  CHECK(bca_plan_num_chunks(plan, BCA_TABLE_LAMB) == 5);
+  CHECK(bca_plan_chunk_info(plan, BCA_TABLE_APPLY, 0, &tensor, &begin, &len, &bucket) == BCA_OK);
+  CHECK(tensor == 1 && begin == 0 && len == 500 && bucket == 0);
+  CHECK(bca_plan_chunk_info(plan, BCA_TABLE_LAMB, 0, &tensor, &begin, &len, &bucket) == BCA_OK);
+  CHECK(tensor == 0 && begin == 0 && len == 1024 && bucket == 1);
+  CHECK(bca_plan_bucket_chunks(plan, BCA_TABLE_LAMB, 1, &first, &count) == BCA_OK && first == 4 && count == 1);
+  CHECK(bca_plan_chunk_info(plan, BCA_TABLE_APPLY, 5, NULL, NULL, NULL, NULL) == BCA_ERR_RANGE);
+  CHECK(bca_plan_set_decay_mask(plan, mask) == BCA_OK);
+  CHECK(adam_step(plan, &hp, 1, NULL) == BCA_ERR_UNBOUND);       /* host-only plan: no kernels */
+  CHECK(lamb_step(plan, &hp, 0, NULL, NULL) == BCA_ERR_HPARAM);  /* step counts from 1 */
+  CHECK(bucket_clip_adam(plan, &dummy, &hp, 1, 64u, NULL, NULL, NULL, NULL) == BCA_ERR_RANGE);
+  bca_plan_destroy(plan);
+  segs[2].len = 1999; /* one element of tensor 0 not covered */
+  CHECK(bca_plan_create(&plan, -1, 2, numel, 2, seg_off, segs, BCA_GRAD_F32, NULL) == BCA_ERR_LAYOUT && plan == NULL);
+  CHECK(strstr(bca_last_error(), "tensor 0") != NULL);
+
+  {
+    /* lengths 1..4 with 10, 0, 5, 5 samples; two strata */
+    const uint32_t cum[5] = {0, 10, 10, 15, 20};
+    const uint32_t ends[2] = {2, 4};
+    lbs_dataset* ds = NULL;
+    lbs_run run;
+    uint64_t sums[2];
+    memset(&run, 0, sizeof run);
+    CHECK(lbs_dataset_create(&ds, -1, 4, cum, 2, ends) == 0);
+    run.method = LBS_LOCAL_SNAKE, run.local_batch = 4, run.gpus_per_node = 2, run.n_gpus = 8;
+    run.quota[0] = 2, run.quota[1] = 2, run.seed = 1, run.n_trials = 3;
+    CHECK(lbs_simulate(ds, &run, NULL, NULL, sums, NULL) == LBS_ERR_HOST);   /* valid, but no device */
+    run.quota[1] = 1;
+    CHECK(lbs_simulate(ds, &run, NULL, NULL, sums, NULL) == LBS_ERR_ARG);
+    lbs_dataset_destroy(ds);
+    CHECK(lbs_dataset_create(&ds, -1, 4, cum, 2, cum) == LBS_ERR_ARG);
+  }
+  printf("c abi ok\n");
+  return 0;
+}
