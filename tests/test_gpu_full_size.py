@@ -164,3 +164,85 @@ def test_bert_large_whole_tensor_buckets_full_size():
                    first_step=1000, seed=0, warm=True)
     coefs = full_fused(w, B.BCA_WRITE_BACK_GRADS)
     assert (coefs < 1).all()
+
+
+def test_one_tensor_of_more_than_2_pow_32_elements():
+    # Maximum sizes: element offsets beyond 32 bits, byte offsets beyond 2^34, 4.2 M work items.  The oracle cannot hold
+    # 4.3 G elements in fp64, so the norms are checked against their closed form (the gradient repeats a 4 099-value
+    # pattern, so a bucket's sum of squares is counts x squares, exact in fp64) and p, m, v on sampled elements, which the
+    # oracle updates one by one given the bucket's coefficient.
+    import torch
+    N = (1 << 32) + (1 << 20) + 7
+    cap = 1 << 30
+    period = 4099
+    lay = W.layout_flat_split([N], cap)
+    nb = lay.n_buckets
+    assert nb == 5 and int(lay.bucket_numel()[-1]) == (1 << 20) + 7
+    dev = torch.device("cuda")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    vals = (torch.randn(period, generator=gen, device=dev) * 1e-2).to(torch.float16)
+    g = torch.empty(N, dtype=torch.float16, device=dev)
+    step_fill = 1 << 28
+    for a in range(0, N, step_fill):
+        b = min(N, a + step_fill)
+        g[a:b] = vals[torch.arange(a, b, device=dev) % period]
+    p = torch.randn(N, generator=gen, device=dev) * 0.02
+    m = torch.randn(N, generator=gen, device=dev) * 3e-4
+    v = (torch.rand(N, generator=gen, device=dev) + 0.5) * 1e-6
+    # sampled elements: both ends, both sides of every bucket boundary and of the 2^32 mark
+    marks = [0, N] + [cap * k for k in range(1, 5)] + [1 << 32, (1 << 32) + 4096]
+    idx = np.unique(np.concatenate([np.arange(max(0, x - 1500), min(N, x + 1500)) for x in marks]))
+    didx = torch.from_numpy(idx).to(dev)
+    before = [x[didx].cpu().numpy() for x in (p, m, v)]
+    gs = g[didx].cpu().numpy()
+
+    # closed-form norms
+    sq = vals.cpu().numpy().astype(np.float64) ** 2
+    want_norm = np.zeros(nb)
+    for bkt in range(nb):
+        a, b = bkt * cap, min(N, (bkt + 1) * cap)
+        r = np.arange(period)
+        counts = (b - r + period - 1) // period - (a - r + period - 1) // period        # indices i in [a, b) with i % period == r
+        assert counts.sum() == b - a
+        want_norm[bkt] = np.sqrt(np.sum(counts * sq))
+    thr = (want_norm * np.asarray([0.5, 2.0, 0.25, 0.9, 0.1])).astype(np.float32)       # bucket 1 is not clipped
+
+    plan = B.Plan.from_layout(lay, B.BCA_GRAD_F16, device=torch.cuda.current_device())
+    plan.bind([g], [p], [m], [v])
+    norms = torch.zeros(nb, device=dev)
+    coefs = torch.zeros(nb, device=dev)
+    status = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    hp = W.Hyper()
+    plan.bucket_clip_adam(torch.from_numpy(thr).to(dev), hyper(hp), 77, 0, norms, coefs, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    check_norms(norms.cpu().numpy(), want_norm)
+    gcoef = coefs.cpu().numpy()
+    want_coef = np.where(want_norm >= thr, thr / want_norm, 1.0)
+    assert np.allclose(gcoef, want_coef, rtol=2e-5) and gcoef[1] == 1.0
+    after = [x[didx].cpu().numpy() for x in (p, m, v)]
+    assert np.array_equal(g[didx].cpu().numpy().view(np.uint16), gs.view(np.uint16))
+
+    # the oracle on the samples: one small bucket per original bucket, its threshold set so that it clips by the same factor
+    which = np.minimum(idx // cap, nb - 1)
+    numels = [int(np.sum(which == bkt)) for bkt in range(nb)]
+    small = W.layout_one_tensor_per_bucket(numels)
+    sg = [gs[which == bkt] for bkt in range(nb)]
+    small_norm = oracle.bucket_norms(small, sg)
+    small_thr = np.where(gcoef < 1, gcoef.astype(np.float64) * small_norm, np.inf).astype(np.float32)
+    op, om, ov = ([x[which == bkt].astype(np.float64) for bkt in range(nb)] for x in before)
+    _, ocoef, _ = oracle.bucket_clip_adam(small, sg, op, om, ov, small_thr, step=77, **hp_kwargs(hp))
+    assert np.allclose(ocoef, gcoef, rtol=3e-7)
+    check_state("p", [after[0][which == bkt] for bkt in range(nb)], op)
+    check_state("m", [after[1][which == bkt] for bkt in range(nb)], om)
+    check_state("v", [after[2][which == bkt] for bkt in range(nb)], ov, strict_rel=True)
+    # and nothing between the samples was left out: every element of m moved (a skipped chunk would keep its old bits)
+    gen2 = torch.Generator(device=dev)
+    gen2.manual_seed(5)
+    torch.randn(period, generator=gen2, device=dev)
+    torch.randn(N, generator=gen2, device=dev)                                           # replays p's draw
+    m_old = torch.randn(N, generator=gen2, device=dev) * 3e-4
+    unchanged = int((m == m_old).sum().item())
+    assert unchanged < N // 1000, unchanged
+    plan.close()
