@@ -85,3 +85,32 @@ def test_runs_on_a_side_stream_and_trials_split_across_calls():
         b2 = run_gpu(ds, lbs.LBS_LOCAL_SNAKE, 16, 8, 256, quota, 21, 35, first=25)
     assert np.array_equal(a[0], np.concatenate([b1[0], b2[0]])) and np.array_equal(a[1], np.concatenate([b1[1], b2[1]]))
     assert a[2] == b1[2] + b2[2] and a[3] == b1[3] + b2[3]
+
+
+def test_simulation_in_a_hip_graph_replays_with_the_same_result():
+    # lbs_simulate clears its sums with a small kernel (no memset node) and keeps no host-side state
+    quota = [6, 3, 2, 5]
+    with lbs.Dataset(CUM, ENDS, device=0) as ds:
+        sums = torch.zeros(2, dtype=torch.int64, device="cuda")
+        tmin = torch.zeros(50, dtype=torch.int32, device="cuda")
+        tmax = torch.zeros(50, dtype=torch.int32, device="cuda")
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            ds.lbs_simulate(lbs.LBS_LOCAL_SNAKE, 16, 8, 128, quota, 3, 50, sums, tmin, tmax, stream=s)
+            s.synchronize()
+            cg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cg, stream=s):
+                ds.lbs_simulate(lbs.LBS_LOCAL_SNAKE, 16, 8, 128, quota, 3, 50, sums, tmin, tmax,
+                                stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        omin, omax, o0, o1 = O.simulate(CUM, ENDS, quota, 16, 8, 128, O.LOCAL_SNAKE, 3, 50)
+        for _ in range(3):
+            sums.fill_(123)
+            tmin.zero_()
+            torch.cuda.synchronize()
+            cg.replay()
+            torch.cuda.synchronize()
+            assert (int(sums[0]), int(sums[1])) == (o0, o1)
+            assert np.array_equal(tmin.cpu().numpy().view(np.uint32), omin)
+            assert np.array_equal(tmax.cpu().numpy().view(np.uint32), omax)

@@ -286,3 +286,49 @@ def test_lamb_random_layouts(seed):
     run_fused(lay, g, p, m, v, thr, hp, step, B.BCA_WRITE_BACK_GRADS, offsets=offsets, decay=mask,
               tune_flags=B.BCA_TUNE_MULTI_LAUNCH, group_bytes=5000)
     run_unfused(lay, g, p, m, v, thr, hp, step, offsets=offsets, decay=mask)
+
+
+def test_clip_lamb_in_a_hip_graph_replays_like_eager_calls():
+    # bucket_clip_lamb is five kernel launches with no host-side state that a capture would freeze and no memset
+    # nodes.  Replays are interleaved with eager work and synchronisations; each is compared with an eager twin.
+    w = small_bert("multistep")
+    lay = w.layout
+    p, m, v = state_of(w)
+    norms0 = oracle.bucket_norms(lay, w.grads(0))
+    thr = (norms0 * (w.thresholds / 1.024)).astype(np.float32)
+    eager = Device(lay, w.grads(0), p, m, v)
+    graph = Device(lay, w.grads(0), p, m, v)
+    ethr, gthr = eager.thresholds(thr), graph.thresholds(thr)
+    hp = hyper(w.hyper)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        graph.plan.bucket_clip_lamb(gthr, hp, 7, 0, graph.norms, graph.coefs, graph.trust, graph.status, stream=s)   # warm-up
+        eager.plan.bucket_clip_lamb(ethr, hp, 7, 0, eager.norms, eager.coefs, eager.trust, eager.status, stream=s)
+        s.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cg, stream=s):
+            graph.plan.bucket_clip_lamb(gthr, hp, 7, 0, graph.norms, graph.coefs, graph.trust, graph.status,
+                                        stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for k in range(1, 5):
+        gk = w.grads(k)
+        eager.set_grads(gk)
+        graph.set_grads(gk)
+        torch.cuda.synchronize()
+        cg.replay()
+        eager.plan.bucket_clip_lamb(ethr, hp, 7, 0, eager.norms, eager.coefs, eager.trust, eager.status)
+        torch.cuda.synchronize()
+        assert int(graph.status.item()) == 0 == int(eager.status.item())
+        assert np.array_equal(graph.trust.cpu().numpy(), eager.trust.cpu().numpy())
+        assert np.array_equal(graph.coefs.cpu().numpy(), eager.coefs.cpu().numpy())
+        assert bits_equal(to_host(graph.p), to_host(eager.p))
+        assert bits_equal(to_host(graph.m), to_host(eager.m))
+        assert bits_equal(to_host(graph.v), to_host(eager.v))
+    op, om, ov = f64(p), f64(m), f64(v)
+    for k in [0, 1, 2, 3, 4]:
+        oracle.bucket_clip_lamb(lay, w.grads(k), op, om, ov, thr, step=7, **hp_kwargs(w.hyper))
+    check_state("p", to_host(eager.p), op)
+    check_state("v", to_host(eager.v), ov, strict_rel=True)
+    eager.close()
+    graph.close()
