@@ -557,3 +557,37 @@ def test_whole_gradient_clipping_adversarial_layouts():
         v = W.warm_second_moment(numels, 9, threads=1)
         whole = float(np.sqrt(np.sum(oracle.bucket_norms(lay, g) ** 2)))
         run_whole(lay, g, p, m, v, max(0.2 * whole, 1e-6), W.Hyper(), 5, B.BCA_WRITE_BACK_GRADS, offsets=offsets)
+
+
+def test_two_plans_run_concurrently_on_two_streams():
+    # Different plans share nothing; their fused steps may overlap on the GPU.  Sizes are large enough (4 M elements
+    # each, ~4 000 work items) for the two single-launch kernels to be resident together.
+    numels = [1 << 20, 3000, 1 << 21, 777, 1 << 20]
+    lay = W.layout_flat_split(numels, 600_000)
+    hp = W.Hyper()
+    devs, want = [], []
+    for seed in (21, 22):
+        g = W.normal_tensors(numels, seed, "g", 1e-2)
+        p = W.normal_tensors(numels, seed, "p", 0.02)
+        m = W.normal_tensors(numels, seed, "m", 3e-3)
+        v = W.warm_second_moment(numels, seed)
+        norms = oracle.bucket_norms(lay, g)
+        thr = (norms * np.where(np.arange(lay.n_buckets) % 2 == 0, 0.5, 2.0)).astype(np.float32)
+        dev = Device(lay, g, p, m, v, group_bytes=4 << 20)
+        devs.append((dev, dev.thresholds(thr)))
+        op, om, ov = f64(p), f64(m), f64(v)
+        for step in (1, 2, 3):
+            oracle.bucket_clip_adam(lay, g, op, om, ov, thr, step=step, **hp_kwargs(hp))
+        want.append((op, om, ov))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for step in (1, 2, 3):
+        for (dev, dthr), s in zip(devs, streams):
+            dev.plan.bucket_clip_adam(dthr, hyper(hp), step, 0, dev.norms, dev.coefs, dev.status, stream=s)
+    torch.cuda.synchronize()
+    for (dev, _), (op, om, ov) in zip(devs, want):
+        assert int(dev.status.item()) == 0
+        check_state("p", to_host(dev.p), op)
+        check_state("m", to_host(dev.m), om)
+        check_state("v", to_host(dev.v), ov, strict_rel=True)
+        dev.close()
