@@ -591,3 +591,21 @@ def test_two_plans_run_concurrently_on_two_streams():
         check_state("m", to_host(dev.m), om)
         check_state("v", to_host(dev.v), ov, strict_rel=True)
         dev.close()
+
+
+def test_fifty_thousand_tiny_buckets():
+    # one 300-element tensor per bucket: every squared-norm item is also its bucket's last arrival, and the work
+    # list alternates between kinds all the way
+    nb = 50_000
+    numels = [300] * nb
+    lay = W.layout_one_tensor_per_bucket(numels)
+    rng = np.random.default_rng(3)
+    flat = lambda sigma: (rng.standard_normal(300 * nb) * sigma).astype(np.float32)
+    split = lambda a: [a[i * 300:(i + 1) * 300] for i in range(nb)]
+    g, p, m = split(flat(1e-2)), split(flat(0.02)), split(flat(3e-3))
+    v = split((1e-6 * (0.5 + rng.random(300 * nb))).astype(np.float32))
+    thr = np.where(np.arange(nb) % 2 == 0, 0.1, 10.0).astype(np.float32)       # norms ~0.17: every other bucket clips
+    hp = W.Hyper()
+    r = run_fused(lay, g, p, m, v, thr, hp, 4)
+    assert r["norm_rel"] < 1e-6
+    run_fused(lay, g, p, m, v, thr, hp, 4, B.BCA_WRITE_BACK_GRADS, tune_flags=B.BCA_TUNE_TICKETS)
