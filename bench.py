@@ -388,7 +388,9 @@ def main():
                          f"host has {os.cpu_count()} logical cpus"}
 
     out = {
-        "metric": "fused bucket_clip_adam step time, BERT-Large fp32 (ms/step; HBM fraction in roofline)",
+        "metric": ("fused bucket_clip_adam step time, BERT-Large fp32 (ms/step; HBM fraction in roofline)"
+                   if (a.config == 3 and gdt_name == "f32") else
+                   f"fused bucket_clip_adam step time, {w.name}, {gdt_name} gradients (ms/step; HBM fraction in roofline)"),
         "value": round(ms_per_step, 4), "unit": "ms/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if gdt_name == "f32" else f"f32 ({gdt_name} gradients)", "data": "synthetic",

@@ -1,5 +1,6 @@
 // HIP kernels for gfx950 (MI355X): squared-norm partials, per-bucket finalize,
-// in-place scale, and the (optionally clip-fused) Adam sweep.
+// in-place scale, the (optionally clip-fused) Adam sweep, the whole fused step as
+// one pipelined launch, and LAMB's two sweeps.  Gradients are fp32, fp16 or bf16.
 //
 // All streaming kernels are table driven: the host cuts the bucket layout into
 // chunks (<= chunk_elems consecutive elements of one tensor in one bucket,
