@@ -230,6 +230,8 @@ void free_device(bca_plan* p) {
   if (p->d_bucket_sq) (void)hipFree(p->d_bucket_sq);
   p->d_bucket_sq = nullptr;
   if (p->d_tensor_off) (void)hipFree(p->d_tensor_off);
+  if (p->d_apply_to_lamb) (void)hipFree(p->d_apply_to_lamb);
+  p->d_apply_to_lamb = nullptr;
   if (p->d_lamb_sums) (void)hipFree(p->d_lamb_sums);
   if (p->d_trust) (void)hipFree(p->d_trust);
   if (p->d_lamb_scale) (void)hipFree(p->d_lamb_scale);
@@ -275,6 +277,33 @@ hipError_t upload_all_tables(bca_plan* p) {
   for (Table* t : {&p->norm_tab, &p->apply_tab, &p->lamb_tab})
     if (e == hipSuccess) e = upload_table(p, t);
   return e;
+}
+
+StepState step_state(const bca_plan* p) {
+  StepState ss;
+  ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
+  ss.norm_bucket_off = p->norm_tab.d_bucket_off;
+  ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+  ss.apply_to_lamb = p->d_apply_to_lamb, ss.lamb_sums = p->d_lamb_sums;
+  return ss;
+}
+
+// For every chunk of the apply table, the index of the same chunk (same tensor, same first
+// element: both tables cut at the same places) in the tensor-major table.
+std::vector<uint32_t> apply_to_lamb_map(const bca_plan* p) {
+  const auto& A = p->apply_tab.chunks;
+  const auto& L = p->lamb_tab.chunks;
+  std::vector<uint32_t> map(A.size());
+  for (size_t i = 0; i < A.size(); ++i) {
+    uint32_t lo = p->tensor_off[A[i].tensor], hi = p->tensor_off[A[i].tensor + 1];
+    while (lo + 1 < hi) {  // chunks of a tensor are sorted by their first element
+      const uint32_t mid = lo + (hi - lo) / 2;
+      if (L[mid].begin <= A[i].begin) lo = mid;
+      else hi = mid;
+    }
+    map[i] = lo;
+  }
+  return map;
 }
 
 int check_ready(const bca_plan* p) {
@@ -414,12 +443,16 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
     const size_t np = std::max<size_t>(p->norm_tab.chunks.size(), 1) * kWaves;
     const size_t nb = n_buckets;
     const size_t nl = std::max<size_t>(p->lamb_tab.chunks.size(), 1), nt = std::max<size_t>(n_tensors, 1);
+    const std::vector<uint32_t> a2l = apply_to_lamb_map(p);
     if ((e = alloc_table(&p->norm_tab, n_buckets)) != hipSuccess ||
         (e = alloc_table(&p->apply_tab, n_buckets)) != hipSuccess ||
         (e = alloc_table(&p->lamb_tab, n_buckets)) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_tensor_off, (n_tensors + 1) * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMemcpy(p->d_tensor_off, p->tensor_off.data(), (n_tensors + 1) * sizeof(uint32_t),
                        hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_apply_to_lamb, nl * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemcpy(p->d_apply_to_lamb, a2l.data(), a2l.size() * sizeof(uint32_t), hipMemcpyHostToDevice)) !=
+            hipSuccess ||
         (e = hipMalloc((void**)&p->d_lamb_sums, nl * 2 * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_trust, nt * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_lamb_scale, nt * sizeof(float))) != hipSuccess ||
@@ -651,10 +684,7 @@ int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, 
   if (int rc = check_ready(p)) return rc;
   if (b0 == b1) return BCA_OK;
   DeviceGuard g(p->device);
-  StepState ss;
-  ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
-  ss.norm_bucket_off = p->norm_tab.d_bucket_off;
-  ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+  const StepState ss = step_state(p);
   const Table& TN = p->norm_tab;
   const Table& TA = p->apply_tab;
   const uint32_t cn0 = TN.bucket_off[b0], nn = TN.bucket_off[b1] - cn0;
@@ -704,14 +734,11 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
 
   if (!multi && !skip) {
     // One launch for the whole step (plus the tiny reset kernel).
-    StepState ss;
-    ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
-    ss.norm_bucket_off = p->norm_tab.d_bucket_off;
-    ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+    const StepState ss = step_state(p);
     if (ev) (void)hipEventRecord(ev[0], s);
     hipError_t e = launch_step(p->grad_dtype, ss, p->n_buckets, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cf,
                                st, (flags & BCA_WRITE_BACK_GRADS) != 0, k, p->unroll_apply,
-                               (p->tune_flags & BCA_TUNE_TICKETS) != 0, ev ? ev[1] : nullptr, s);
+                               (p->tune_flags & BCA_TUNE_TICKETS) != 0, false, ev ? ev[1] : nullptr, s);
     if (e != hipSuccess) return fail_hip(e, "launching the fused step kernel");
     if (ev) (void)hipEventRecord(ev[2], s);
     return BCA_OK;
@@ -760,25 +787,33 @@ static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, u
   if (int rc = make_adam_constants(hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
   DeviceGuard g(p->device);
-  const float* cf = nullptr;
+  const Table& TL = p->lamb_tab;
+  const uint32_t nl = (uint32_t)TL.chunks.size();
+  hipError_t e = hipSuccess;
   if (thresholds) {
     float* nm = norms ? norms : p->d_norms;
     float* cw = coefs ? coefs : p->d_coefs;
     int32_t* st = status ? status : p->d_status;
-    const Table& TN = p->norm_tab;
-    const uint32_t nn = (uint32_t)TN.chunks.size();
-    // the gradients are read again right away by the moments sweep: cacheable loads
-    hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, 0, nn, p->d_partials, st, make_launch(p, 0, nn, true), s);
-    if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
-    e = launch_finalize(p->d_partials, TN.d_bucket_off, 0, p->n_buckets, thresholds, nm, cw, st, nullptr, s);
-    if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
-    cf = cw;
+    if (!(p->tune_flags & BCA_TUNE_MULTI_LAUNCH)) {
+      // squared norms, coefficients and LAMB's first sweep as one pipelined launch (the fused Adam step's
+      // work list and waiting scheme; the first sweep's second read of the gradients is served from cache)
+      e = launch_step(p->grad_dtype, step_state(p), p->n_buckets, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cw,
+                      st, (flags & BCA_WRITE_BACK_GRADS) != 0, k, 1, false, true, nullptr, s);
+      if (e != hipSuccess) return fail_hip(e, "launching the fused clip + LAMB moments kernel");
+    } else {
+      const Table& TN = p->norm_tab;
+      const uint32_t nn = (uint32_t)TN.chunks.size();
+      e = launch_sqnorm(p->grad_dtype, TN.d_chunks, 0, nn, p->d_partials, st, make_launch(p, 0, nn, false), s);
+      if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
+      e = launch_finalize(p->d_partials, TN.d_bucket_off, 0, p->n_buckets, thresholds, nm, cw, st, nullptr, s);
+      if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
+      e = launch_lamb_moments(p->grad_dtype, TL.d_chunks, nl, cw, (flags & BCA_WRITE_BACK_GRADS) != 0, p->d_lamb_sums, k, s);
+      if (e != hipSuccess) return fail_hip(e, "launching the LAMB moments kernel");
+    }
+  } else {
+    e = launch_lamb_moments(p->grad_dtype, TL.d_chunks, nl, nullptr, false, p->d_lamb_sums, k, s);
+    if (e != hipSuccess) return fail_hip(e, "launching the LAMB moments kernel");
   }
-  const Table& TL = p->lamb_tab;
-  const uint32_t nl = (uint32_t)TL.chunks.size();
-  hipError_t e = launch_lamb_moments(p->grad_dtype, TL.d_chunks, nl, cf, (flags & BCA_WRITE_BACK_GRADS) != 0,
-                                     p->d_lamb_sums, k, s);
-  if (e != hipSuccess) return fail_hip(e, "launching the LAMB moments kernel");
   e = launch_lamb_trust(p->d_lamb_sums, p->d_tensor_off, p->n_tensors, k.lr, trust ? trust : p->d_trust,
                         p->d_lamb_scale, s);
   if (e != hipSuccess) return fail_hip(e, "launching the LAMB trust-ratio kernel");

@@ -90,6 +90,8 @@ struct StepState {
   uint32_t* arrived;                // [B] squared-norm workgroups done per bucket
   unsigned long long* ready;        // [B] (epoch << 32) | bits of the bucket's coefficient
   uint32_t* ctl;                    // [kCtlWords] ticket counter, epoch
+  const uint32_t* apply_to_lamb;    // LAMB: place of every apply-table chunk in the tensor-major table
+  double* lamb_sums;                // LAMB: two sums per chunk, in tensor-major order
 };
 
 // Kernel launchers (bca_kernels.hip).  All enqueue on `stream` and return the
@@ -118,7 +120,8 @@ hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, con
 // (may be null) is recorded between the two kernels.
 hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
                        const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
-                       const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream);
+                       const AdamK& k, uint32_t unroll, bool tickets, bool lamb, hipEvent_t between,
+                       hipStream_t stream);
 
 // Clipping of buckets [b0, b1) in one launch (k_prepare_range, then k_clip): cn0 / n_norm
 // and ca0 / n_apply are the range's chunks in the norm and the apply table.
@@ -156,6 +159,7 @@ struct bca_plan {
   bca::Table lamb_tab;
   std::vector<uint32_t> tensor_off;
   uint32_t* d_tensor_off = nullptr;
+  uint32_t* d_apply_to_lamb = nullptr;  // for every chunk of apply_tab, its index in lamb_tab
   double* d_lamb_sums = nullptr;   // 2 per chunk of lamb_tab: sum p^2, sum update^2
   float* d_trust = nullptr;        // n_tensors
   float* d_lamb_scale = nullptr;   // n_tensors: -lr * trust

@@ -578,60 +578,71 @@ __device__ __forceinline__ double block_sum(double x, double* s_w) {
   return ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
 }
 
+// LAMB's first sweep over one chunk: moments updated and stored, the chunk's sums of
+// p^2 and u^2 written to out[0], out[1] (fp64; per lane 4 * chunk_elems / 1024 squares
+// are added in fp32 first).  coef != 1 only behind clipping; WB: the scaled gradient,
+// rounded to its storage type, also replaces g.  GNT: whether g streams (it does not
+// when the squared-norm pass has just read it and it is still cached).
+template <int GDT, bool FUSED, bool WB, bool GNT>
+__device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, const AdamK& k, double* s_pp,
+                                                   double* s_uu, double* __restrict__ out) {
+  typedef Grad<GDT> G;
+  constexpr uint32_t gsize = sizeof(typename G::elem);
+  const uint32_t tid = threadIdx.x;
+  const bool wb = WB && coef != 1.f;
+  const float wd = chunk_wd(en, k);
+  const uint32_t len = en.len;
+  const uint32_t head = vector_head(len, en.g, gsize, 4u * gsize, true, en.p, en.m, en.v);
+  const uint32_t nvec = (len - head) / 4u;
+  const uint32_t tail0 = head + nvec * 4u;
+  void* gv = reinterpret_cast<void*>(en.g + (uint64_t)head * gsize);
+  const f32x4* pv = reinterpret_cast<const f32x4*>(en.p + (uint64_t)head * 4u);
+  f32x4* mv = reinterpret_cast<f32x4*>(en.m + (uint64_t)head * 4u);
+  f32x4* vv = reinterpret_cast<f32x4*>(en.v + (uint64_t)head * 4u);
+  float pp = 0.f, uu = 0.f;
+  for (uint32_t j = tid; j < nvec; j += kBlock) {
+    f32x4 g = G::template load4<GNT>(gv, j), p = ldv<true>(pv + j), m = ldv<true>(mv + j), v = ldv<true>(vv + j);
+    if constexpr (FUSED) g = g * coef;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float mi = m[i], vi = v[i];
+      adam_moments(g[i], mi, vi, k);
+      const float u = adam_direction(p[i], mi, vi, k, wd);
+      pp = __fmaf_rn(p[i], p[i], pp), uu = __fmaf_rn(u, u, uu);
+      m[i] = mi, v[i] = vi;
+    }
+    stv<true>(mv + j, m), stv<true>(vv + j, v);
+    if (wb) G::template store4<GNT>(gv, j, g);
+  }
+  void* gbase = reinterpret_cast<void*>(en.g);
+  const float* p1 = reinterpret_cast<const float*>(en.p);
+  float* m1 = reinterpret_cast<float*>(en.m);
+  float* v1 = reinterpret_cast<float*>(en.v);
+  for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
+    const uint32_t i = r < head ? r : tail0 + (r - head);
+    float g = G::load1(gbase, i), m = m1[i], v = v1[i];
+    const float p = p1[i];
+    if constexpr (FUSED) g = g * coef;
+    adam_moments(g, m, v, k);
+    const float u = adam_direction(p, m, v, k, wd);
+    pp = __fmaf_rn(p, p, pp), uu = __fmaf_rn(u, u, uu);
+    m1[i] = m, v1[i] = v;
+    if (wb) G::store1(gbase, i, g);
+  }
+  const double tpp = block_sum((double)pp, s_pp), tuu = block_sum((double)uu, s_uu);
+  if (tid == 0) out[0] = tpp, out[1] = tuu;
+}
+
 template <int GDT, bool FUSED, bool WB>
 __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict__ table, uint32_t n,
                                                           const float* __restrict__ coefs,
                                                           double* __restrict__ sums, const AdamK k) {
-  typedef Grad<GDT> G;
-  constexpr uint32_t gsize = sizeof(typename G::elem);
   __shared__ double s_pp[kWaves], s_uu[kWaves];
-  const uint32_t tid = threadIdx.x;
   for (uint32_t ci = blockIdx.x; ci < n; ci += gridDim.x) {
     const Entry en = read_entry(&table[ci]);
     float coef = 1.f;
     if constexpr (FUSED) coef = coefs[en.bucket];
-    const bool wb = WB && coef != 1.f;
-    const float wd = chunk_wd(en, k);
-    const uint32_t len = en.len;
-    const uint32_t head = vector_head(len, en.g, gsize, 4u * gsize, true, en.p, en.m, en.v);
-    const uint32_t nvec = (len - head) / 4u;
-    const uint32_t tail0 = head + nvec * 4u;
-    void* gv = reinterpret_cast<void*>(en.g + (uint64_t)head * gsize);
-    const f32x4* pv = reinterpret_cast<const f32x4*>(en.p + (uint64_t)head * 4u);
-    f32x4* mv = reinterpret_cast<f32x4*>(en.m + (uint64_t)head * 4u);
-    f32x4* vv = reinterpret_cast<f32x4*>(en.v + (uint64_t)head * 4u);
-    float pp = 0.f, uu = 0.f;  // a lane adds 4 * chunk_elems / 1024 squares in fp32, then everything is fp64
-    for (uint32_t j = tid; j < nvec; j += kBlock) {
-      f32x4 g = G::template load4<true>(gv, j), p = ldv<true>(pv + j), m = ldv<true>(mv + j), v = ldv<true>(vv + j);
-      if constexpr (FUSED) g = g * coef;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float mi = m[i], vi = v[i];
-        adam_moments(g[i], mi, vi, k);
-        const float u = adam_direction(p[i], mi, vi, k, wd);
-        pp = __fmaf_rn(p[i], p[i], pp), uu = __fmaf_rn(u, u, uu);
-        m[i] = mi, v[i] = vi;
-      }
-      stv<true>(mv + j, m), stv<true>(vv + j, v);
-      if (wb) G::template store4<true>(gv, j, g);
-    }
-    void* gbase = reinterpret_cast<void*>(en.g);
-    const float* p1 = reinterpret_cast<const float*>(en.p);
-    float* m1 = reinterpret_cast<float*>(en.m);
-    float* v1 = reinterpret_cast<float*>(en.v);
-    for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
-      const uint32_t i = r < head ? r : tail0 + (r - head);
-      float g = G::load1(gbase, i), m = m1[i], v = v1[i];
-      const float p = p1[i];
-      if constexpr (FUSED) g = g * coef;
-      adam_moments(g, m, v, k);
-      const float u = adam_direction(p, m, v, k, wd);
-      pp = __fmaf_rn(p, p, pp), uu = __fmaf_rn(u, u, uu);
-      m1[i] = m, v1[i] = v;
-      if (wb) G::store1(gbase, i, g);
-    }
-    const double tpp = block_sum((double)pp, s_pp), tuu = block_sum((double)uu, s_uu);
-    if (tid == 0) sums[(uint64_t)ci * 2u] = tpp, sums[(uint64_t)ci * 2u + 1u] = tuu;
+    lamb_moments_chunk<GDT, FUSED, WB, true>(en, coef, k, s_pp, s_uu, sums + (uint64_t)ci * 2u);
     __syncthreads();  // s_pp / s_uu are reused by the next chunk
   }
 }
@@ -752,6 +763,7 @@ struct StepShared {
   uint32_t flag;
   float coef;
   double w[kWaves];
+  double pp[kWaves], uu[kWaves];  // LAMB: block sums of p^2 and u^2
 };
 
 // Waits (bounded) for bucket b's ready word of this epoch.  Returns true with the
@@ -832,7 +844,10 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
   }
 }
 
-template <int GDT, bool WB, uint32_t U, bool TICKETS>
+// LAMB: the items that would apply Adam run LAMB's first sweep instead (moments and the
+// chunk's two sums, filed under the chunk's place in the tensor-major order); the trust
+// ratio and the parameter update follow as launches of their own.
+template <int GDT, bool WB, uint32_t U, bool TICKETS, bool LAMB>
 __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
                                                   const float* __restrict__ thresholds, float* __restrict__ norms,
                                                   float* __restrict__ coefs, int32_t* status, const AdamK k) {
@@ -867,7 +882,13 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
   const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
   if (kind == kItemAdam) {
     const Entry en = read_entry(&st.apply_tab[idx]);
-    if (wait_for_bucket(st, en.bucket, epoch, status, sh)) adam_chunk<GDT, true, WB, U, false>(en, sh.coef, k);
+    if (wait_for_bucket(st, en.bucket, epoch, status, sh)) {
+      if constexpr (LAMB)
+        lamb_moments_chunk<GDT, true, WB, false>(en, sh.coef, k, sh.pp, sh.uu,
+                                                 st.lamb_sums + (uint64_t)st.apply_to_lamb[idx] * 2u);
+      else
+        adam_chunk<GDT, true, WB, U, false>(en, sh.coef, k);
+    }
   } else {
     norm_item<GDT>(st, kind, idx, epoch, thresholds, norms, coefs, status, sh);
   }
@@ -1003,18 +1024,31 @@ hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, u
 
 hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
                        const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
-                       const AdamK& k, uint32_t unroll, bool tickets, hipEvent_t between, hipStream_t stream) {
+                       const AdamK& k, uint32_t unroll, bool tickets, bool lamb, hipEvent_t between,
+                       hipStream_t stream) {
   hipLaunchKernelGGL(k_prepare, dim3(1), dim3(kBlock), 0, stream, st, n_buckets, status);
   hipError_t e = hipGetLastError();
   if (between != nullptr) (void)hipEventRecord(between, stream);
   if (e != hipSuccess || n_work == 0) return e;
+  if (lamb) {  // one variant per gradient type and write-back setting: items by workgroup index, no unrolling
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      if (write_back)
+        hipLaunchKernelGGL((k_step<GDT, true, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                           thresholds, norms, coefs, status, k);
+      else
+        hipLaunchKernelGGL((k_step<GDT, false, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                           thresholds, norms, coefs, status, k);
+    });
+    return hipGetLastError();
+  }
   pick_unroll(unroll, [&](auto uu) {
     constexpr uint32_t U = decltype(uu)::value;
     pick2(tickets, write_back, [&](auto tk, auto wb) {
       constexpr bool TK = decltype(tk)::value, WB = decltype(wb)::value;
       pick_gdt(gdt, [&](auto gd) {
         constexpr int GDT = decltype(gd)::value;
-        hipLaunchKernelGGL((k_step<GDT, WB, U, TK>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+        hipLaunchKernelGGL((k_step<GDT, WB, U, TK, false>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
                            thresholds, norms, coefs, status, k);
       });
     });

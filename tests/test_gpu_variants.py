@@ -332,3 +332,29 @@ def test_clip_lamb_in_a_hip_graph_replays_like_eager_calls():
     check_state("v", to_host(eager.v), ov, strict_rel=True)
     eager.close()
     graph.close()
+
+
+def test_clip_lamb_single_launch_equals_the_separate_launches_bit_for_bit():
+    for kind in ("large", "fp16"):
+        w = small_bert(kind)
+        g = w.grads()
+        p, m, v = state_of(w)
+        norms = oracle.bucket_norms(w.layout, g)
+        thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
+        outs = []
+        for tuning in (dict(), dict(tune_flags=B.BCA_TUNE_MULTI_LAUNCH), dict(group_bytes=300_000), dict(chunk_apply=2048)):
+            dev = Device(w.layout, g, p, m, v, **tuning)
+            dev.plan.bucket_clip_lamb(dev.thresholds(thr), hyper(w.hyper), 5, B.BCA_WRITE_BACK_GRADS, dev.norms, dev.coefs,
+                                      dev.trust, dev.status)
+            dev.sync()
+            assert int(dev.status.item()) == 0
+            outs.append((dev.norms.cpu().numpy(), dev.coefs.cpu().numpy(), dev.trust.cpu().numpy(), to_host(dev.p),
+                         to_host(dev.m), to_host(dev.v), to_host(dev.g)))
+            dev.close()
+        ref = outs[0]
+        assert (ref[1] < 1).any()
+        for other in outs[1:3]:            # same chunk cuts: everything identical
+            assert all(np.array_equal(ref[i], other[i]) for i in (0, 1, 2))
+            assert all(bits_equal(ref[i], other[i]) for i in (3, 4, 5, 6))
+        # other chunk cuts: other partial sums, so trust ratios may differ in the last bits; moments and gradients do not
+        assert np.array_equal(ref[1], outs[3][1]) and bits_equal(ref[4], outs[3][4]) and bits_equal(ref[6], outs[3][6])
