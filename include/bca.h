@@ -1,4 +1,4 @@
-/* bca.h -- bucket-wise gradient clipping + Adam on one MI355X (gfx950).
+/* bca.h -- bucket-wise gradient clipping + Adam (or LAMB) on one MI355X (gfx950).
  *
  * C ABI of libbca.so.  Plain pointers and sizes only; every pointer is marked
  * HOST or DEVICE.  The library implements, as hand-written HIP kernels, the
@@ -6,8 +6,8 @@
  * for every gradient bucket G_b, clip it by its own L2 norm against the
  * bucket's threshold (Sec. 2.3 defines clipping-by-norm; Sec. 4.2 applies it
  * bucket by bucket, before the all-reduce), then update the parameters with
- * Adam (Alg. 1, last line).  The all-reduce between the two is not part of
- * this library.
+ * Adam (Alg. 1, last line) or with LAMB, the optimizer the paper compares Adam
+ * with (Sec. 2.2).  The all-reduce between the two is not part of this library.
  *
  * Conventions
  *   - All compute calls only enqueue kernels on `stream` (a hipStream_t passed
@@ -86,7 +86,8 @@ typedef struct bca_adam {
 
 /* Launch tuning; zero in any field means "library default". */
 #define BCA_TUNE_MULTI_LAUNCH 1u    /* bucket_clip_adam as separate norm / finalize / Adam launches per
-                                       bucket group instead of the single pipelined launch            */
+                                       bucket group instead of the single pipelined launch; likewise
+                                       bucket_clip_lamb's norms and first sweep (one group)           */
 #define BCA_TUNE_TICKETS 4u          /* single launch: work items are handed out through an atomic
                                        ticket instead of by workgroup index                          */
 #define BCA_TUNE_STAGE_TABLE_LDS 2u /* multi-launch kernels: persistent workgroups stage chunk-table
