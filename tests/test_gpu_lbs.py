@@ -114,3 +114,22 @@ def test_simulation_in_a_hip_graph_replays_with_the_same_result():
             assert (int(sums[0]), int(sums[1])) == (o0, o1)
             assert np.array_equal(tmin.cpu().numpy().view(np.uint32), omin)
             assert np.array_equal(tmax.cpu().numpy().view(np.uint32), omax)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_settings_all_methods(seed):
+    rng = np.random.default_rng(500 + seed)
+    n_strata = int(rng.integers(1, 6))
+    max_len = int(rng.choice([17, 64, 200, 512, 1000]))
+    ends = sorted(set(int(x) for x in rng.integers(1, max_len, n_strata - 1))) + [max_len] if n_strata > 1 else [max_len]
+    share = rng.random(len(ends)) + 0.05
+    cum = W.length_histogram_piecewise_uniform(int(rng.integers(1000, 200_000)), ends, share)
+    b = int(rng.integers(1, 33))
+    quota = [int(q) for q in W.stratum_quota(cum, ends, b)]
+    P = int(rng.choice([1, 2, 3, 8, 16]))
+    if P * b > 1024:
+        P = 1
+    G = P * int(rng.integers(1, 40))
+    for method in range(5):
+        check(cum, ends, method, b, P, G, quota, seed=int(rng.integers(0, 2 ** 62)), n=int(rng.integers(1, 12)),
+              first=int(rng.integers(0, 2 ** 40)))
