@@ -15,7 +15,7 @@ SOURCES = [os.path.join(CSRC, "bca_host.cpp"), os.path.join(CSRC, "bca_kernels.h
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-command-line-argument", "-x", "hip",
+    "-Wall", "-Wextra", "-Wno-unused-command-line-argument", "-x", "hip",
 ]
 
 

@@ -2,10 +2,8 @@
 still matches what the oracle computes, and has the properties the definitions fix."""
 import importlib.util
 import json
-import math
 import os
 
-import numpy as np
 import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))

@@ -8,7 +8,6 @@ decimal), closed forms at step 1, the invariant ||delta p|| = lr ||p|| that hold
 for every tensor and step, the reduction to Adam when the ratio is 1, and the
 definition written out with numpy for the clip + LAMB composition.  The decay mask
 is pinned against torch.optim.AdamW with two parameter groups."""
-import math
 from decimal import Decimal, getcontext
 from fractions import Fraction
 

@@ -10,7 +10,6 @@ import sys
 import tempfile
 from concurrent.futures import ThreadPoolExecutor
 
-import pytest
 
 from oracle import build as obuild
 
