@@ -609,3 +609,26 @@ def test_fifty_thousand_tiny_buckets():
     r = run_fused(lay, g, p, m, v, thr, hp, 4)
     assert r["norm_rel"] < 1e-6
     run_fused(lay, g, p, m, v, thr, hp, 4, B.BCA_WRITE_BACK_GRADS, tune_flags=B.BCA_TUNE_TICKETS)
+
+
+@pytest.mark.parametrize("hp,step", [
+    (W.Hyper(lr=1e-3, beta1=0.0, beta2=0.0, eps=1e-8, weight_decay=0.0), 1),          # no averaging at all: sign-like update
+    (W.Hyper(lr=0.0, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.1), 5),          # lr 0: p must keep its bits
+    (W.Hyper(lr=1e-2, beta1=0.999, beta2=0.85, eps=0.0, weight_decay=0.0), 2),         # eps 0 (v > 0 everywhere)
+    (W.Hyper(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.01), 10 ** 9),  # bias corrections are 1
+    (W.Hyper(lr=-1e-3, beta1=0.7, beta2=0.999, eps=1e-11, weight_decay=1.0), 3),       # negative lr is finite, hence allowed
+])
+def test_hyper_parameter_extremes(hp, step):
+    w = small_bert("large")
+    g = w.grads()
+    p, m, v = state_of(w)
+    norms = oracle.bucket_norms(w.layout, g)
+    thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
+    run_fused(w.layout, g, p, m, v, thr, hp, step)
+    run_unfused(w.layout, g, p, m, v, thr, hp, step)
+    if hp.lr == 0.0:
+        dev = Device(w.layout, g, p, m, v)
+        dev.plan.bucket_clip_adam(dev.thresholds(thr), hyper(hp), step, 0, dev.norms, dev.coefs, dev.status)
+        dev.sync()
+        assert bits_equal(to_host(dev.p), p) and not bits_equal(to_host(dev.m), m)
+        dev.close()

@@ -319,3 +319,41 @@ def test_nonfinite_gradient_sets_flag_and_skip_mode_is_a_bit_exact_noop():
     _, _, st = oracle.bucket_clip_adam(lay, g, p, m, v, w.thresholds, step=10, **HP)
     assert st & oracle.STATUS_NONFINITE
     assert any(not np.array_equal(a, b) for a, b in zip(p, ref[:len(p)]))
+
+
+def test_adam_and_lamb_steps_do_not_depend_on_the_gradient_scale_when_eps_is_zero():
+    # Adam's direction mhat / sqrt(vhat) is homogeneous of degree 0 in the gradient history; scaling every
+    # gradient by a power of two scales m by it and v by its square exactly, so p must come out bit-identical.
+    numels = [257, 64]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=0.0, weight_decay=0.01)
+    outs = {}
+    for scale in (1.0, 2.0 ** 7, 2.0 ** -9):
+        for name, fn in (("adam", oracle.adam_step), ("lamb", oracle.lamb_step)):
+            p = [x.astype(np.float64) for x in W.normal_tensors(numels, 1, "p", 0.02)]
+            m = [np.zeros(n) for n in numels]
+            v = [np.zeros(n) for n in numels]
+            for step in (1, 2, 3):
+                g = [x * np.float32(scale) for x in W.normal_tensors(numels, 30 + step, "g", 1e-2)]
+                fn(np.asarray(numels, np.uint64), g, p, m, v, step=step, **hp)
+            outs[(name, scale)] = (p, m, v)
+    for name in ("adam", "lamb"):
+        ref = outs[(name, 1.0)]
+        for scale in (2.0 ** 7, 2.0 ** -9):
+            got = outs[(name, scale)]
+            assert all(np.array_equal(a, b) for a, b in zip(ref[0], got[0])), (name, scale)
+            assert all(np.array_equal(a * scale, b) for a, b in zip(ref[1], got[1]))
+            assert all(np.array_equal(a * scale * scale, b) for a, b in zip(ref[2], got[2]))
+
+
+def test_clipping_twice_with_the_same_threshold_changes_nothing_more():
+    numels = [3000, 500]
+    lay = W.layout_flat_split(numels, 1200)
+    g = [x.astype(np.float32) for x in W.normal_tensors(numels, 5, "g", 1e-2)]
+    thr = np.full(lay.n_buckets, 0.05, np.float32)
+    coefs1, _ = oracle.clip_coefs(oracle.bucket_norms(lay, g), thr)
+    assert (coefs1 < 1).all()
+    oracle.bucket_scale(lay, g, coefs1)
+    n2 = oracle.bucket_norms(lay, g)
+    assert np.allclose(n2, 0.05, rtol=1e-6)
+    coefs2, _ = oracle.clip_coefs(n2, thr)
+    assert np.all(coefs2 > 1 - 1e-6) and np.all(coefs2 <= 1)
