@@ -246,3 +246,35 @@ def test_one_tensor_of_more_than_2_pow_32_elements():
     unchanged = int((m == m_old).sum().item())
     assert unchanged < N // 1000, unchanged
     plan.close()
+
+
+def test_bert_large_per_bucket_clip_then_adam_full_size():
+    # the paper's own order of work: every bucket clipped on its own as it becomes ready (one launch per bucket),
+    # then Adam on the stored, scaled gradients
+    w = W.config_bert_large()
+    lay = w.layout
+    g, p, m, v = w.grads(), w.params(), w.exp_avg(), w.exp_avg_sq()
+    dev = Device(lay, g, p, m, v)
+    dthr = dev.thresholds(w.thresholds)
+    status = 0
+    for b in range(lay.n_buckets):
+        dev.plan.bucket_clip(b, b + 1, dthr, dev.norms, dev.coefs, dev.status)
+        status |= int(dev.status.item())
+    dev.plan.adam_step(hyper(w.hyper), w.first_step)
+    dev.sync()
+    onorm = oracle.bucket_norms(lay, g)
+    ocoef, ost = oracle.clip_coefs(onorm, w.thresholds)
+    og = [x.copy() for x in g]
+    oracle.bucket_scale(lay, og, ocoef)
+    op, om, ov = f64(p), f64(m), f64(v)
+    oracle.adam_step(lay, og, op, om, ov, step=w.first_step, **hp_kwargs(w.hyper))
+    assert status == ost == 0
+    check_norms(dev.norms.cpu().numpy(), onorm)
+    assert np.allclose(dev.coefs.cpu().numpy(), ocoef, rtol=2e-5, atol=0)
+    for a, b in zip(to_host(dev.g), og):
+        assert np.allclose(a, b, rtol=5e-7, atol=1e-45)
+    rp = check_state("p", to_host(dev.p), op)
+    check_state("m", to_host(dev.m), om)
+    rv = check_state("v", to_host(dev.v), ov, strict_rel=True)
+    print(f"[per-bucket] p {rp}; v {rv}", flush=True)
+    dev.close()
