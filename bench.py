@@ -51,6 +51,7 @@ def parse():
     ap.add_argument("--chunk-apply", type=int, default=0)
     ap.add_argument("--unroll-apply", type=int, default=0)
     ap.add_argument("--group-mib", type=int, default=0)
+    ap.add_argument("--adam-lds-kib", type=int, default=0, help="adam_step: LDS reserved per workgroup, KiB (0: default, -1: none)")
     ap.add_argument("--grid-norm", type=int, default=0)
     ap.add_argument("--grid-apply", type=int, default=0)
     ap.add_argument("--tune-flags", type=int, default=0)
@@ -257,7 +258,8 @@ def main():
     gdt = B.BCA_GRAD_F16 if f16 else B.BCA_GRAD_BF16 if bf16 else B.BCA_GRAD_F32
     plan = B.Plan.from_layout(lay, gdt, device=0, chunk_norm=a.chunk_norm,
                               chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
-                              unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20)
+                              unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20,
+                              adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10)
     plan.bind(g, p, m, v)
     if a.decay_mask:
         H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)

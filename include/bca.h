@@ -103,6 +103,11 @@ typedef struct bca_tuning {
   uint64_t group_bytes;  /* bucket_clip_adam walks the buckets in groups of at most this many
                             gradient bytes (norms, then Adam, group by group) so that a group's
                             gradients are still in cache when Adam reads them; 0: default      */
+  uint32_t adam_lds_reserve; /* adam_step (and any other Adam sweep that streams the gradients): bytes of LDS
+                            each workgroup reserves without using them, which caps the workgroups resident
+                            per compute unit (160 KiB each) -- the sweep streams fastest with few
+                            wavefronts in flight.  0: default (48 KiB); 1: none; at most 65536       */
+  uint32_t reserved;     /* must be 0 */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */

@@ -351,6 +351,7 @@ Launch make_launch(const bca_plan* p, uint32_t requested, uint32_t n_chunks, boo
   L.unroll = p->unroll_apply;
   L.staged = (p->tune_flags & BCA_TUNE_STAGE_TABLE_LDS) != 0;
   L.g_keep = g_keep;
+  L.lds = g_keep ? 0 : p->adam_lds_reserve;  // grouped sweeps read g from cache and are fastest at full occupancy
   return L;
 }
 
@@ -390,6 +391,8 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
     }
     if (tuning->flags & ~(BCA_TUNE_MULTI_LAUNCH | BCA_TUNE_STAGE_TABLE_LDS | BCA_TUNE_TICKETS))
       return fail(BCA_ERR_RANGE, "unknown tuning flag bits");
+    if (tuning->adam_lds_reserve > 65536 || tuning->reserved != 0)
+      return fail(BCA_ERR_RANGE, "adam_lds_reserve must be at most 65536 and reserved 0");
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
@@ -404,6 +407,8 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   // default: as many 128-bit accesses in flight as one pass over a full chunk needs, at most 4
   p->unroll_apply = unroll ? unroll : (chunk_apply >= 4096 ? 4u : chunk_apply >= 2048 ? 2u : 1u);
   p->tune_flags = tuning ? tuning->flags : 0;
+  p->adam_lds_reserve = (tuning && tuning->adam_lds_reserve) ? (tuning->adam_lds_reserve == 1 ? 0 : tuning->adam_lds_reserve)
+                                                              : kDefaultAdamLdsReserve;
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
   p->decay.assign(n_tensors, 1);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);

@@ -68,6 +68,11 @@ constexpr uint32_t kDefaultChunkApply = 1024;
 // large enough that a group's norms are done before its Adam items start, small enough
 // that two groups' gradients stay in the Infinity Cache (measured optimum on MI355X).
 constexpr uint64_t kDefaultGroupElems = 8ull << 20;
+// The stand-alone Adam sweep streams 3-5 % faster with three workgroups (twelve wavefronts) per compute unit
+// than with all eight: fewer requests in flight suit the four-read / three-write mix (measured on MI355X:
+// BERT-Large 1.614 -> 1.537 ms, BERT-Base 0.529 -> 0.511 ms).  48 KiB of the 160 KiB LDS per workgroup give that.
+// The fused single-launch step does not gain from it (its items wait on each other) and does not use it.
+constexpr uint32_t kDefaultAdamLdsReserve = 48u << 10;
 
 // How a streaming kernel is launched.
 struct Launch {
@@ -75,6 +80,8 @@ struct Launch {
   uint32_t unroll;  // 128-bit accesses in flight per lane and array in the scale / Adam sweeps: 1, 2 or 4
   bool staged;      // persistent grid staging its table entries in LDS (else one uniform entry load per chunk)
   bool g_keep;      // gradients are loaded with the normal (cacheable) policy because they are read again soon
+  uint32_t lds;     // Adam sweep (k_adam) only: bytes of LDS a workgroup reserves without using them, which caps
+                    // how many workgroups a compute unit holds at once
 };
 
 // Device-side state of the single-launch fused step (k_prepare / k_step).
@@ -151,6 +158,7 @@ struct bca_plan {
   uint32_t n_tensors = 0, n_buckets = 0;
   uint32_t grid_norm = 0, grid_apply = 0;  // 0: one workgroup per chunk
   uint32_t unroll_apply = 1;
+  uint32_t adam_lds_reserve = 0;  // bytes; see bca_tuning::adam_lds_reserve
   uint32_t tune_flags = 0;
   bool bound = false;
   std::vector<uint64_t> tensor_numel;

@@ -1097,15 +1097,15 @@ hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, co
 
 template <int GDT, uint32_t U, bool GNT, bool ST>
 static void launch_adam_t(const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
-                          const int32_t* skip_status, const AdamK& k, uint32_t grid, hipStream_t stream) {
+                          const int32_t* skip_status, const AdamK& k, uint32_t grid, uint32_t lds, hipStream_t stream) {
   if (coefs == nullptr)
-    hipLaunchKernelGGL((k_adam<GDT, false, false, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+    hipLaunchKernelGGL((k_adam<GDT, false, false, U, GNT, ST>), dim3(grid), dim3(kBlock), lds, stream, table, c0, n,
                        coefs, skip_status, k);
   else if (!write_back)
-    hipLaunchKernelGGL((k_adam<GDT, true, false, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+    hipLaunchKernelGGL((k_adam<GDT, true, false, U, GNT, ST>), dim3(grid), dim3(kBlock), lds, stream, table, c0, n,
                        coefs, skip_status, k);
   else
-    hipLaunchKernelGGL((k_adam<GDT, true, true, U, GNT, ST>), dim3(grid), dim3(kBlock), 0, stream, table, c0, n,
+    hipLaunchKernelGGL((k_adam<GDT, true, true, U, GNT, ST>), dim3(grid), dim3(kBlock), lds, stream, table, c0, n,
                        coefs, skip_status, k);
 }
 
@@ -1117,7 +1117,8 @@ hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, con
     pick2(!L.g_keep, L.staged, [&](auto gnt, auto st) {
       constexpr bool GNT = decltype(gnt)::value, ST = decltype(st)::value;
       pick_gdt(gdt, [&](auto gd) {
-        launch_adam_t<decltype(gd)::value, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, stream);
+        launch_adam_t<decltype(gd)::value, U, GNT, ST>(table, c0, n, coefs, write_back, skip_status, k, L.grid, L.lds,
+                                                       stream);
       });
     });
   });
