@@ -48,6 +48,7 @@ typedef struct bca_plan bca_plan; /* opaque */
 #define BCA_ERR_HIP (-6)     /* a HIP runtime call failed (message has its string)  */
 #define BCA_ERR_DTYPE (-7)   /* unknown gradient type                               */
 #define BCA_ERR_ALIGN (-8)   /* a tensor pointer is not aligned to its element size */
+#define BCA_ERR_NOMEM (-9)   /* out of host memory (bca_last_error() may be empty)   */
 
 /* bits of the device status word written by the clip calls */
 #define BCA_STATUS_NONFINITE 1     /* some bucket's sum of squares is Inf or NaN          */
@@ -227,7 +228,8 @@ int bucket_clip_lamb(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, con
  * With profiling on, bucket_clip_adam records HIP events on `stream` around each
  * of its kernels (squared norm, finalize, Adam sweep; once per bucket group), for at most
  * `max_calls` calls after it was switched on (max_calls = 0 switches it off and
- * frees the events).  bca_plan_profile_read waits for the recorded events and
+ * frees the events).  Calls with BCA_SKIP_STEP_ON_NONFINITE or BCA_CLIP_WHOLE_GRADIENT
+ * are not recorded.  bca_plan_profile_read waits for the recorded events and
  * returns the summed duration of each kernel in milliseconds in ms[0..2] and the
  * number of calls summed in *n_calls, then starts a new series. */
 int bca_plan_profile(bca_plan* plan, uint32_t max_calls);

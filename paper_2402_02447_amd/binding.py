@@ -23,7 +23,7 @@ BCA_STATUS_TIMEOUT = 4
 BCA_TABLE_NORM, BCA_TABLE_APPLY, BCA_TABLE_LAMB = 0, 1, 2
 
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
-              -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN"}
+              -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
 EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_destroy", "bca_plan_num_buckets",
            "bca_plan_num_groups", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "bca_internal.h"
@@ -24,6 +25,19 @@ int fail(int code, const std::string& msg) {
 
 int fail_hip(hipError_t e, const char* what) {
   return fail(BCA_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// No C++ exception may cross the C boundary: the calls that grow host containers run through this.
+template <class F>
+int no_throw(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    g_last_error.clear();  // no allocation while reporting the lack of memory
+    return BCA_ERR_NOMEM;
+  } catch (...) {
+    return BCA_ERR_NOMEM;
+  }
 }
 
 uint64_t grad_bytes(int gdt) { return gdt == BCA_GRAD_F32 ? 4 : 2; }
@@ -366,9 +380,9 @@ int bca_version(void) { return 1; }
 
 const char* bca_last_error(void) { return g_last_error.c_str(); }
 
-int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64_t* tensor_numel, uint32_t n_buckets,
-                    const uint64_t* bucket_seg_off, const bca_segment* segments, int grad_dtype,
-                    const bca_tuning* tuning) {
+static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64_t* tensor_numel, uint32_t n_buckets,
+                       const uint64_t* bucket_seg_off, const bca_segment* segments, int grad_dtype,
+                       const bca_tuning* tuning) {
   if (!out) return fail(BCA_ERR_NULL, "out is NULL");
   *out = nullptr;
   if (!bucket_seg_off) return fail(BCA_ERR_NULL, "bucket_seg_off is NULL");
@@ -396,9 +410,15 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
-  bca_plan* p = new (std::nothrow) bca_plan;
-  if (!p) return fail(BCA_ERR_HIP, "out of host memory");
-  p->device = device;
+  struct Release {  // a plan that is not handed out is freed, device memory included
+    void operator()(bca_plan* q) const {
+      free_device(q);
+      delete q;
+    }
+  };
+  std::unique_ptr<bca_plan, Release> owner(new bca_plan);
+  bca_plan* p = owner.get();
+  p->device = -1;  // becomes `device` once that device is known to exist: until then there is nothing to free on it
   p->grad_dtype = grad_dtype;
   p->n_tensors = n_tensors;
   p->n_buckets = n_buckets;
@@ -418,33 +438,21 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
   build_tensor_table(&p->lamb_tab, &p->tensor_off, chunk_apply, n_tensors, n_buckets, bucket_seg_off, segments);
   build_work(p);
   // A launch holds at most 2^32 threads: with 256 per workgroup that is 2^24 workgroups.
-  if (p->work.size() >= (1ull << 24)) {
-    delete p;
+  if (p->work.size() >= (1ull << 24))
     return fail(BCA_ERR_RANGE, "too many chunks for one launch; raise chunk_norm / chunk_apply");
-  }
 
   if (device >= 0) {
     int n_dev = 0;
     hipError_t e = hipGetDeviceCount(&n_dev);
-    if (e != hipSuccess || device >= n_dev) {
-      delete p;
-      return e != hipSuccess ? fail_hip(e, "hipGetDeviceCount") : fail(BCA_ERR_RANGE, "no such device");
-    }
+    if (e != hipSuccess) return fail_hip(e, "hipGetDeviceCount");
+    if (device >= n_dev) return fail(BCA_ERR_RANGE, "no such device");
     DeviceGuard g(device);
-    if (!g.ok) {
-      delete p;
-      return fail(BCA_ERR_HIP, "hipSetDevice failed");
-    }
+    if (!g.ok) return fail(BCA_ERR_HIP, "hipSetDevice failed");
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);
-    if (e != hipSuccess) {
-      delete p;
-      return fail_hip(e, "hipGetDeviceProperties");
-    }
-    if (prop.warpSize != 64) {
-      delete p;
-      return fail(BCA_ERR_HIP, "the kernels need 64-wide wavefronts (gfx950)");
-    }
+    if (e != hipSuccess) return fail_hip(e, "hipGetDeviceProperties");
+    if (prop.warpSize != 64) return fail(BCA_ERR_HIP, "the kernels need 64-wide wavefronts (gfx950)");
+    p->device = device;
     const size_t np = std::max<size_t>(p->norm_tab.chunks.size(), 1) * kWaves;
     const size_t nb = n_buckets;
     const size_t nl = std::max<size_t>(p->lamb_tab.chunks.size(), 1), nt = std::max<size_t>(n_tensors, 1);
@@ -475,18 +483,23 @@ int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64
         (e = hipMalloc((void**)&p->d_bucket_sq, nb * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_coefs, nb * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_status, sizeof(int32_t))) != hipSuccess ||
-        (e = hipMemset(p->d_status, 0, sizeof(int32_t))) != hipSuccess) {
-      free_device(p);
-      delete p;
+        (e = hipMemset(p->d_status, 0, sizeof(int32_t))) != hipSuccess)
       return fail_hip(e, "allocating plan memory");
-    }
   }
-  *out = p;
+  *out = owner.release();
   return BCA_OK;
 }
 
-int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* const* exp_avg,
-                  float* const* exp_avg_sq) {
+int bca_plan_create(bca_plan** out, int device, uint32_t n_tensors, const uint64_t* tensor_numel, uint32_t n_buckets,
+                    const uint64_t* bucket_seg_off, const bca_segment* segments, int grad_dtype,
+                    const bca_tuning* tuning) {
+  return no_throw([&] {
+    return plan_create(out, device, n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments, grad_dtype, tuning);
+  });
+}
+
+static int plan_bind(bca_plan* p, void* const* grads, float* const* params, float* const* exp_avg,
+                     float* const* exp_avg_sq) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan (device -1) cannot be bound");
   if (p->n_tensors && (!grads || !params || !exp_avg || !exp_avg_sq)) return fail(BCA_ERR_NULL, "a pointer array is NULL");
@@ -518,17 +531,24 @@ int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* 
   return BCA_OK;
 }
 
+int bca_plan_bind(bca_plan* p, void* const* grads, float* const* params, float* const* exp_avg,
+                  float* const* exp_avg_sq) {
+  return no_throw([&] { return plan_bind(p, grads, params, exp_avg, exp_avg_sq); });
+}
+
 int bca_plan_set_decay_mask(bca_plan* p, const uint8_t* decay) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   for (uint32_t t = 0; t < p->n_tensors; ++t) p->decay[t] = decay ? (decay[t] != 0) : 1;
   if (p->device < 0 || !p->bound) return BCA_OK;  // the next bind writes the flags
   DeviceGuard g(p->device);
-  hipError_t e = upload_all_tables(p);
-  if (e != hipSuccess) {
-    p->bound = false;
-    return fail_hip(e, "uploading the chunk tables");
-  }
-  return BCA_OK;
+  return no_throw([&] {
+    hipError_t e = upload_all_tables(p);
+    if (e != hipSuccess) {
+      p->bound = false;
+      return fail_hip(e, "uploading the chunk tables");
+    }
+    return (int)BCA_OK;
+  });
 }
 
 void bca_plan_destroy(bca_plan* p) {
@@ -598,16 +618,19 @@ int bca_plan_profile(bca_plan* p, uint32_t max_calls) {
   (void)hipDeviceSynchronize();
   free_profile(p);
   const size_t per_call = events_per_call(p);
-  for (size_t i = 0; i < max_calls * per_call; ++i) {
-    hipEvent_t ev;
-    hipError_t e = hipEventCreate(&ev);
-    if (e != hipSuccess) {
-      free_profile(p);
-      return fail_hip(e, "hipEventCreate");
+  return no_throw([&] {
+    p->prof_events.reserve(max_calls * per_call);
+    for (size_t i = 0; i < max_calls * per_call; ++i) {
+      hipEvent_t ev;
+      hipError_t e = hipEventCreate(&ev);
+      if (e != hipSuccess) {
+        free_profile(p);
+        return fail_hip(e, "hipEventCreate");
+      }
+      p->prof_events.push_back(ev);
     }
-    p->prof_events.push_back(ev);
-  }
-  return BCA_OK;
+    return (int)BCA_OK;
+  });
 }
 
 int bca_plan_profile_read(bca_plan* p, double* ms, uint32_t* n_calls) {
@@ -733,8 +756,10 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
   float* cf = coefs ? coefs : p->d_coefs;
   int32_t* st = status ? status : p->d_status;
   const size_t per_call = events_per_call(p);
-  hipEvent_t* ev = nullptr;  // events of this call when profiling has room left
-  if (!(skip && !multi) && (size_t)(p->prof_calls + 1) * per_call <= p->prof_events.size())
+  // events of this call when profiling has room left; a call that needs every norm first runs as one
+  // group whatever the plan's groups are, so it does not fit the per-group event layout: not profiled
+  hipEvent_t* ev = nullptr;
+  if (!skip && (size_t)(p->prof_calls + 1) * per_call <= p->prof_events.size())
     ev = &p->prof_events[(size_t)p->prof_calls++ * per_call];
 
   if (!multi && !skip) {
@@ -751,15 +776,16 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
 
   // Several launches.  The skip decision covers all buckets, so that mode takes one
   // group: all norms first, then one Adam sweep that checks the status word.
-  std::vector<std::pair<uint32_t, uint32_t>> one_group(1, std::make_pair(0u, p->n_buckets));
-  const auto& groups = skip ? one_group : p->groups;
+  const std::pair<uint32_t, uint32_t> all_buckets(0u, p->n_buckets);
+  const std::pair<uint32_t, uint32_t>* groups = skip ? &all_buckets : p->groups.data();
+  const size_t n_groups = skip ? 1 : p->groups.size();
   if (ev) (void)hipEventRecord(*ev++, s);
   // With groups, a group's gradients are read twice in quick succession (norm,
   // then Adam) and are kept cacheable; everything else streams.
-  const bool keep = groups.size() > 1;
+  const bool keep = n_groups > 1;
   bool first = true;
-  for (const auto& gr : groups) {
-    const uint32_t b0 = gr.first, b1 = gr.second;
+  for (size_t gi = 0; gi < n_groups; ++gi) {
+    const uint32_t b0 = groups[gi].first, b1 = groups[gi].second;
     const Table& TN = p->norm_tab;
     const Table& TA = p->apply_tab;
     const uint32_t cn0 = TN.bucket_off[b0], nn = TN.bucket_off[b1] - cn0;

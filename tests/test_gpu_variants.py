@@ -358,3 +358,46 @@ def test_clip_lamb_single_launch_equals_the_separate_launches_bit_for_bit():
             assert all(bits_equal(ref[i], other[i]) for i in (3, 4, 5, 6))
         # other chunk cuts: other partial sums, so trust ratios may differ in the last bits; moments and gradients do not
         assert np.array_equal(ref[1], outs[3][1]) and bits_equal(ref[4], outs[3][4]) and bits_equal(ref[6], outs[3][6])
+
+
+# ------------------------------------------------------------------ per-kernel timing
+
+
+@pytest.mark.parametrize("tuning", [dict(), dict(tune_flags=B.BCA_TUNE_MULTI_LAUNCH, group_bytes=200_000)],
+                         ids=["single_launch", "multi_launch_groups"])
+def test_profiling_counts_ordinary_calls_only_and_leaves_results_alone(tuning):
+    """Profiled calls give the same bits as unprofiled ones; a call that needs every norm first (skip on
+    non-finite, whole-gradient clipping) runs as one group and is not recorded, whatever the plan's groups."""
+    w = small_bert("large")
+    p, m, v = state_of(w)
+    g = w.grads()
+    norms = oracle.bucket_norms(w.layout, g)
+    thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
+
+    def run(profiled):
+        d = Device(w.layout, g, p, m, v, **tuning)
+        if tuning:
+            assert d.plan.n_groups > 1
+        if profiled:
+            d.plan.profile(4)
+        t = d.thresholds(thr)
+        for step, flags in ((1, 0), (2, B.BCA_SKIP_STEP_ON_NONFINITE), (3, 0), (4, B.BCA_CLIP_WHOLE_GRADIENT)):
+            whole = torch.empty(w.layout.n_buckets + 1, dtype=torch.float32, device="cuda")
+            d.plan.bucket_clip_adam(t if flags != B.BCA_CLIP_WHOLE_GRADIENT else d.thresholds(np.asarray([1e30])),
+                                    hyper(w.hyper), step, flags, norms=whole, coefs=d.coefs, status=d.status)
+        d.sync()
+        out = None
+        if profiled:
+            out = d.plan.profile_read()
+            assert d.plan.profile_read()[1] == 0          # reading starts a new series
+            d.plan.profile(0)
+        state = (to_host(d.p), to_host(d.m), to_host(d.v))
+        d.close()
+        return state, out
+
+    plain, _ = run(False)
+    prof, (ms, n) = run(True)
+    assert n == 2
+    assert all(np.isfinite(x) and x >= 0 for x in ms) and ms[2] > 0
+    for a, b in zip(plain, prof):
+        assert bits_equal(a, b)
