@@ -1,17 +1,26 @@
 // Load-balancing simulation for gfx950 (MI355X): host entry points and kernels.
 // See lbs.h for what is simulated and for the contract of every call.
 //
-// One workgroup (256 threads, four wavefronts) runs one trial.  The dataset's
-// cumulative histogram sits in LDS; a draw is one SplitMix64 output (a handful of
-// 64-bit integer operations) and a binary search over the histogram.  Nothing here
-// is a contraction or a stream over HBM: the work is integer ALU and LDS traffic,
-// the outputs are two words per trial.
-//   NONE / STRATIFIED : a thread owns whole GPUs; 16 draws, one sum each.
-//   LOCAL_*           : a wavefront owns a node: its lanes draw the node's pool into
-//                       LDS (padded to a power of two with a sentinel above every
-//                       length), sort it there with a bitonic network (log^2 stages
-//                       of independent compare-exchanges, one pair per lane), and add
-//                       up each GPU's column in raster or snake order.
+// One workgroup (256 threads, four wavefronts) runs one trial.  Nothing here is a
+// contraction or a stream over HBM: the work is integer ALU, cross-lane traffic and
+// LDS, the outputs are two words per trial.
+//
+// A draw is one SplitMix64 output (a handful of 64-bit integer operations) and the
+// inverse of the cumulative histogram at the index it selects.  The histogram sits in
+// LDS, and so does a guide table made when the dataset is created: for every range
+// the draws can come from (the whole dataset, each stratum) and every value of the
+// draw's upper 9 bits, the smallest and the largest length that such a draw can
+// select.  The search for the length then runs over that interval only (mostly one
+// or two candidates instead of ten halvings of [1, max_len]).
+//   NONE / STRATIFIED : a thread owns whole GPUs; local_batch draws, one sum each.
+//   LOCAL_*           : a wavefront owns a node.  Its lanes draw the node's pool into
+//                       registers (entry i of the pool in register i / 64 of lane
+//                       i % 64, padded to a multiple of 64 with a sentinel above every
+//                       length) and sort it there with a bitonic network: a
+//                       compare-exchange at distance < 64 is a cross-lane exchange, one
+//                       at distance >= 64 pairs two registers of the same lane.  The
+//                       sorted pool goes to LDS once, where each GPU's column is added
+//                       up in raster or snake order.
 //   GLOBAL            : lengths are small integers, so the trial's pool of
 //                       n_gpus * local_batch draws is sorted by counting: an LDS
 //                       histogram, a block-wide prefix sum, and the entry at sorted
@@ -23,6 +32,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <new>
 #include <string>
@@ -30,17 +40,23 @@
 
 #include "lbs.h"
 
+namespace lbs {
+constexpr uint32_t kGuideBits = 9, kGuideSize = 1u << kGuideBits;
+}
+
 struct lbs_dataset {
   int device = -1;
   uint32_t max_len = 0, n_strata = 0;
   std::vector<uint32_t> cum, stratum_end;
   uint32_t* d_cum = nullptr;
+  uint32_t* d_guide = nullptr;  // (1 + n_strata) tables of kGuideSize entries: the whole dataset, then each stratum
 };
 
 namespace lbs {
 namespace {
 
 constexpr uint32_t kBlock = 256, kWaves = 4;
+constexpr uint64_t kTrialsPerLaunch = 1ull << 22;  // a launch stays below 2^32 threads
 
 thread_local std::string g_error;
 int fail(int code, const std::string& msg) {
@@ -51,21 +67,25 @@ int fail(int code, const std::string& msg) {
 struct Params {  // by-value kernel argument
   uint32_t max_len, local_batch, gpus_per_node, n_gpus, snake, stratified;
   uint32_t total;                             // dataset size
-  uint32_t slot_lo[LBS_MAX_LOCAL_BATCH];      // stratified: entries before the stratum of a GPU's j-th draw
-  uint32_t slot_size[LBS_MAX_LOCAL_BATCH];    //             entries in that stratum
+  uint32_t n_guide;                           // guide tables the kernel loads (1: whole dataset; else one per stratum)
+  uint32_t slot_lo[LBS_MAX_LOCAL_BATCH];      // a GPU's j-th draw: dataset entries before its range (0 / its stratum),
+  uint32_t slot_size[LBS_MAX_LOCAL_BATCH];    //   entries in that range,
+  uint32_t slot_guide[LBS_MAX_LOCAL_BATCH];   //   and where that range's guide table starts in LDS
   uint64_t seed, first_trial;
 };
 
-__device__ __forceinline__ uint64_t splitmix64(uint64_t seed, uint64_t k) {
-  uint64_t z = seed + (k + 1) * 0x9E3779B97F4A7C15ull;
+// SplitMix64: output number k + 1 of the generator seeded with `seed` is mix(state(seed, k)); the state
+// advances by kGamma per draw, so consecutive draws cost one 64-bit addition, not a multiplication.
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint64_t state(uint64_t seed, uint64_t k) { return seed + (k + 1) * kGamma; }
+__device__ __forceinline__ uint64_t mix(uint64_t z) {
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
   return z ^ (z >> 31);
 }
 
-// Smallest l in [1, max_len] with counts[l] > index (counts is non-decreasing).
-__device__ __forceinline__ uint32_t first_above(const uint32_t* counts, uint32_t max_len, uint32_t index) {
-  uint32_t lo = 1, hi = max_len;
+// Smallest l in [lo, hi] with counts[l] > index (counts is non-decreasing and counts[hi] > index).
+__device__ __forceinline__ uint32_t first_above(const uint32_t* counts, uint32_t lo, uint32_t hi, uint32_t index) {
   while (lo < hi) {
     const uint32_t mid = (lo + hi) >> 1;
     if (counts[mid] > index) hi = mid;
@@ -74,18 +94,25 @@ __device__ __forceinline__ uint32_t first_above(const uint32_t* counts, uint32_t
   return lo;
 }
 
-// Length of the j-th sequence GPU `gpu` retrieves in trial `trial`.
-__device__ __forceinline__ uint32_t draw(const Params& P, const uint32_t* s_cum, uint64_t trial, uint32_t gpu, uint32_t j) {
-  const uint64_t k = (trial * P.n_gpus + gpu) * (uint64_t)P.local_batch + j;
-  const uint64_t u = splitmix64(P.seed, k) >> 32;
-  const uint32_t index = P.stratified ? P.slot_lo[j] + (uint32_t)((u * P.slot_size[j]) >> 32)
-                                      : (uint32_t)((u * P.total) >> 32);
-  return first_above(s_cum, P.max_len, index);
+// Length selected by the draw with generator state z out of the `size` dataset entries that follow the
+// first `before` ones; `guide` is that range's table.
+__device__ __forceinline__ uint32_t draw(const uint32_t* s_cum, const uint32_t* guide, uint64_t z, uint32_t before,
+                                         uint32_t size) {
+  const uint32_t u = (uint32_t)(mix(z) >> 32);
+  const uint32_t index = before + __umulhi(u, size);
+  const uint32_t span = guide[u >> (32u - kGuideBits)];  // lengths a draw with these upper bits can select
+  return first_above(s_cum, span & 0xffffu, span >> 16, index);
 }
 
-__device__ __forceinline__ void load_histogram(uint32_t* s_cum, const uint32_t* __restrict__ cum, uint32_t max_len) {
-  for (uint32_t i = threadIdx.x; i <= max_len; i += kBlock) s_cum[i] = cum[i];
+// Histogram and guide tables into LDS; returns where the guide tables start.
+__device__ __forceinline__ uint32_t* load_tables(uint32_t* s_dyn, const Params& P, const uint32_t* __restrict__ cum,
+                                                 const uint32_t* __restrict__ guide) {
+  uint32_t* s_guide = s_dyn + P.max_len + 1u;
+  for (uint32_t i = threadIdx.x; i <= P.max_len; i += kBlock) s_dyn[i] = cum[i];
+  const uint32_t* src = guide + (P.stratified ? kGuideSize : 0u);  // table 0 is the whole dataset's
+  for (uint32_t i = threadIdx.x; i < P.n_guide * kGuideSize; i += kBlock) s_guide[i] = src[i];
   __syncthreads();
+  return s_guide;
 }
 
 // Combines the threads' running minimum and maximum and lets thread 0 publish the trial's result.
@@ -114,89 +141,183 @@ __global__ __launch_bounds__(64) void k_lbs_clear(unsigned long long* sums) {
 
 // NONE and STRATIFIED: no redistribution.
 __global__ __launch_bounds__(kBlock) void k_lbs_keep(const Params P, const uint32_t* __restrict__ cum,
-                                                      uint32_t* trial_min, uint32_t* trial_max,
-                                                      unsigned long long* sums) {
-  __shared__ uint32_t s_cum[LBS_MAX_LEN + 1];
+                                                      const uint32_t* __restrict__ guide, uint32_t* trial_min,
+                                                      uint32_t* trial_max, unsigned long long* sums) {
+  extern __shared__ uint32_t s_dyn[];  // histogram, guide tables
   __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
-  load_histogram(s_cum, cum, P.max_len);
-  const uint64_t trial = P.first_trial + blockIdx.x;
+  const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
+  const uint64_t k_trial = (P.first_trial + blockIdx.x) * P.n_gpus * (uint64_t)P.local_batch;  // the trial's first draw
   uint32_t lo = 0xffffffffu, hi = 0u;
   for (uint32_t g = threadIdx.x; g < P.n_gpus; g += kBlock) {
+    uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
     uint32_t tokens = 0;
-    for (uint32_t j = 0; j < P.local_batch; ++j) tokens += draw(P, s_cum, trial, g, j);
+    for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
+      tokens += draw(s_dyn, s_guide + P.slot_guide[j], z, P.slot_lo[j], P.slot_size[j]);
     lo = min(lo, tokens), hi = max(hi, tokens);
   }
   finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
 }
 
-// LOCAL_RASTER and LOCAL_SNAKE: pool, sort and deal within every node.
+// Median of three: with c = 0 it is min(a, b), with c = 0xffffffff it is max(a, b) (one v_med3_u32).
+__device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) {
+  return max(min(a, b), min(max(a, b), c));
+}
+
+// The value that lane ^ 2^LJ holds.  Within a row of 16 lanes the exchange is a data-parallel move of the
+// vector unit (quad permutation, shifts by 4 written to alternate banks of four lanes, rotation by 8);
+// across rows it goes through the LDS crossbar.
+template <int LJ>
+__device__ __forceinline__ uint32_t from_partner(uint32_t x) {
+  const int v = (int)x;
+  if (LJ == 0) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false);  // quad_perm [1,0,3,2]
+  if (LJ == 1) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false);  // quad_perm [2,3,0,1]
+  if (LJ == 2) {
+    const int t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xf, 0x5, false);   // lanes 0-3, 8-11 of a row read lane + 4
+    return (uint32_t)__builtin_amdgcn_update_dpp(t, v, 0x114, 0xf, 0xA, false);  // lanes 4-7, 12-15 read lane - 4
+  }
+  if (LJ == 3) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  return (uint32_t)__shfl_xor(v, 1 << LJ, 64);
+}
+
+__device__ __forceinline__ uint32_t partner_of(uint32_t x, int lj) {  // lj is a constant after unrolling
+  switch (lj) {
+    case 0: return from_partner<0>(x);
+    case 1: return from_partner<1>(x);
+    case 2: return from_partner<2>(x);
+    case 3: return from_partner<3>(x);
+    case 4: return from_partner<4>(x);
+    default: return from_partner<5>(x);
+  }
+}
+
+// Sorts the 64 * E values held by a wavefront (value i in v[i / 64] of lane i % 64) into ascending order of i.
+// bit[b] is all ones in lanes whose bit b is set and 0 elsewhere (b < 6).
+template <int E>
+__device__ __forceinline__ void bitonic_sort(uint32_t (&v)[E], const uint32_t (&bit)[6]) {
+  constexpr int kLog = 6 + (E == 1 ? 0 : E == 2 ? 1 : E == 4 ? 2 : E == 8 ? 3 : 4);
+#pragma unroll
+  for (int lk = 1; lk <= kLog; ++lk) {       // merge sorted runs of 2^(lk-1) into runs of k = 2^lk, directions alternating
+#pragma unroll
+    for (int lj = lk - 1; lj >= 0; --lj) {   // compare-exchange at distance j = 2^lj
+      if (lj >= 6) {                         // both entries in this lane
+        const int je = 1 << (lj - 6);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          if (e & je) continue;
+          const bool ascending = ((e >> (lk - 6)) & 1) == 0;  // lk >= 7: the run's direction depends on e alone
+          const uint32_t a = v[e], b = v[e | je];
+          v[e] = ascending ? min(a, b) : max(a, b);
+          v[e | je] = ascending ? max(a, b) : min(a, b);
+        }
+      } else {                               // the other entry is in lane ^ j
+        // The lane with the pair's smaller index keeps the minimum in an ascending run and the maximum in a
+        // descending one; the other lane the opposite: `keep` is 0 where the minimum stays, all ones elsewhere.
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const uint32_t descending = lk < 6 ? bit[lk < 6 ? lk : 0] : (((e >> (lk - 6)) & 1) ? 0xffffffffu : 0u);
+          const uint32_t keep = bit[lj] ^ descending;
+          v[e] = median3(v[e], partner_of(v[e], lj), keep);
+        }
+      }
+    }
+  }
+}
+
+// LOCAL_RASTER and LOCAL_SNAKE: pool, sort and deal within every node.  E = registers per lane: 64 * E >= the pool.
+// IN_LANES: gpus_per_node is a power of two up to 32.  Then sorted entry i = e * 64 + lane lies in column
+// lane % gpus_per_node of row e * (64 / gpus_per_node) + lane / gpus_per_node, whose parity is that of
+// lane / gpus_per_node for every e, and the deal is a sum within the lane, a mirror exchange inside odd rows
+// (snake) and a butterfly over the lane bits above the column: no LDS and no barrier.  Otherwise the sorted
+// pool goes to LDS and one lane per GPU walks its column.
+template <int E, bool IN_LANES>
 __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint32_t* __restrict__ cum,
-                                                       uint32_t* trial_min, uint32_t* trial_max,
-                                                       unsigned long long* sums) {
-  __shared__ uint32_t s_cum[LBS_MAX_LEN + 1];
-  __shared__ uint32_t s_pool[kWaves][LBS_MAX_NODE_POOL];
+                                                       const uint32_t* __restrict__ guide, uint32_t* trial_min,
+                                                       uint32_t* trial_max, unsigned long long* sums) {
+  extern __shared__ uint32_t s_dyn[];  // histogram, guide tables, (not IN_LANES) one sorted pool per wavefront
   __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
-  load_histogram(s_cum, cum, P.max_len);
-  const uint64_t trial = P.first_trial + blockIdx.x;
+  const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   const uint32_t n_nodes = P.n_gpus / P.gpus_per_node;
   const uint32_t pool = P.gpus_per_node * P.local_batch;
-  uint32_t padded = 2;  // the network sorts a power of two
-  while (padded < pool) padded <<= 1;
-  uint32_t* mine = s_pool[wave];
+  uint32_t* sorted = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize + wave * pool;
+  // pool entry i = e * 64 + lane is draw i % local_batch of GPU i / local_batch of the node, for every node alike
+  uint32_t before[E], size[E], goff[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const uint32_t i = (uint32_t)e * 64u + lane, j = i % P.local_batch;
+    const bool real = i < pool;
+    before[e] = real ? P.slot_lo[j] : 0u, size[e] = real ? P.slot_size[j] : 0u, goff[e] = real ? P.slot_guide[j] : 0u;
+  }
+  uint32_t bit[6];
+#pragma unroll
+  for (int b = 0; b < 6; ++b) bit[b] = 0u - ((lane >> b) & 1u);
+  const bool odd_row = ((lane / P.gpus_per_node) & 1u) != 0u;  // IN_LANES only
+  const uint64_t k_trial = (P.first_trial + blockIdx.x) * P.n_gpus * (uint64_t)P.local_batch;
   uint32_t lo = 0xffffffffu, hi = 0u;
-  // Every wavefront makes the same number of rounds and stages, so the barriers below are
-  // met by all; a wavefront without a node in the last round only keeps them company.
+  // Every wavefront makes the same number of rounds, so the barriers below (not IN_LANES) are met by all; a
+  // wavefront without a node in the last round only keeps them company.
   for (uint32_t base = 0; base < n_nodes; base += kWaves) {
     const uint32_t node = base + wave;
     const bool active = node < n_nodes;
-    if (active)
-      for (uint32_t i = lane; i < padded; i += 64u)
-        mine[i] = i < pool ? draw(P, s_cum, trial, node * P.gpus_per_node + i / P.local_batch, i % P.local_batch)
-                           : 0xffffffffu;
-    __syncthreads();
-    for (uint32_t k = 2; k <= padded; k <<= 1)
-      for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-        if (active)
-          for (uint32_t t = lane; t < (padded >> 1); t += 64u) {
-            const uint32_t a = ((t & ~(j - 1u)) << 1) | (t & (j - 1u));  // t with a 0 inserted at j's bit
-            const uint32_t b = a | j;
-            const uint32_t x = mine[a], y = mine[b];
-            const bool ascending = (a & k) == 0u;
-            if ((x > y) == ascending) mine[a] = y, mine[b] = x;
-          }
-        __syncthreads();
+    if (active) {
+      const uint64_t z_node = state(P.seed, k_trial + (uint64_t)node * pool);  // a node's draws are consecutive
+      uint32_t v[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const uint32_t i = (uint32_t)e * 64u + lane;
+        v[e] = i < pool ? draw(s_dyn, s_guide + goff[e], z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
       }
-    if (active)
-      for (uint32_t c = lane; c < P.gpus_per_node; c += 64u) {
+      bitonic_sort<E>(v, bit);
+      if (IN_LANES) {
         uint32_t tokens = 0;
-        for (uint32_t r = 0; r < P.local_batch; ++r) {
-          const uint32_t col = (P.snake && (r & 1u)) ? P.gpus_per_node - 1u - c : c;  // position in the row dealt to GPU c
-          tokens += mine[r * P.gpus_per_node + col];
+#pragma unroll
+        for (int e = 0; e < E; ++e) tokens += (uint32_t)e * 64u + lane < pool ? v[e] : 0u;  // the padding sorts to the end
+        if (P.snake) {  // an odd row is dealt right to left: its column c goes to GPU gpus_per_node - 1 - c
+          const uint32_t mirrored = (uint32_t)__shfl_xor((int)tokens, (int)(P.gpus_per_node - 1u), 64);
+          tokens = odd_row ? mirrored : tokens;
         }
-        lo = min(lo, tokens), hi = max(hi, tokens);
+        for (uint32_t m = P.gpus_per_node; m < 64u; m <<= 1) tokens += (uint32_t)__shfl_xor((int)tokens, (int)m, 64);
+        lo = min(lo, tokens), hi = max(hi, tokens);  // every lane now holds the total of GPU lane % gpus_per_node
+      } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const uint32_t i = (uint32_t)e * 64u + lane;
+          if (i < pool) sorted[i] = v[e];
+        }
       }
-    __syncthreads();
+    }
+    if (!IN_LANES) {
+      __syncthreads();
+      if (active)
+        for (uint32_t c = lane; c < P.gpus_per_node; c += 64u) {
+          uint32_t tokens = 0;
+          for (uint32_t r = 0; r < P.local_batch; ++r) {
+            const uint32_t col = (P.snake && (r & 1u)) ? P.gpus_per_node - 1u - c : c;  // position in the row dealt to GPU c
+            tokens += sorted[r * P.gpus_per_node + col];
+          }
+          lo = min(lo, tokens), hi = max(hi, tokens);
+        }
+      __syncthreads();
+    }
   }
   finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
 }
 
 // GLOBAL: pool, sort and deal over all GPUs.
 __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uint32_t* __restrict__ cum,
-                                                        uint32_t* trial_min, uint32_t* trial_max,
-                                                        unsigned long long* sums) {
-  __shared__ uint32_t s_cum[LBS_MAX_LEN + 1];
-  __shared__ uint32_t s_cnt[LBS_MAX_LEN + 1];  // first a histogram of the trial's draws, then its running sum
+                                                        const uint32_t* __restrict__ guide, uint32_t* trial_min,
+                                                        uint32_t* trial_max, unsigned long long* sums) {
+  extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram
   __shared__ uint32_t s_scan[kBlock];
   __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
-  load_histogram(s_cum, cum, P.max_len);
-  const uint64_t trial = P.first_trial + blockIdx.x;
+  const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
+  uint32_t* s_cnt = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize;  // first counts of the trial's draws, then their running sum
   const uint32_t tid = threadIdx.x;
   for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_cnt[i] = 0u;
   __syncthreads();
   const uint32_t pool = P.n_gpus * P.local_batch;
-  for (uint32_t i = tid; i < pool; i += kBlock)
-    atomicAdd(&s_cnt[draw(P, s_cum, trial, i / P.local_batch, i % P.local_batch)], 1u);
+  uint64_t z = state(P.seed, (P.first_trial + blockIdx.x) * (uint64_t)pool + tid);
+  for (uint32_t i = tid; i < pool; i += kBlock, z += kBlock * kGamma) atomicAdd(&s_cnt[draw(s_dyn, s_guide, z, 0u, P.total)], 1u);
   __syncthreads();
   // running sum over lengths: thread t owns a contiguous piece, pieces are combined by a doubling scan
   const uint32_t per = (P.max_len + 1u + kBlock - 1u) / kBlock;
@@ -219,11 +340,35 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
   __syncthreads();
   uint32_t lo = 0xffffffffu, hi = 0u;
   for (uint32_t c = tid; c < P.n_gpus; c += kBlock) {
-    uint32_t tokens = 0;
-    for (uint32_t r = 0; r < P.local_batch; ++r) tokens += first_above(s_cnt, P.max_len, r * P.n_gpus + c);
+    uint32_t tokens = 0, l = 1;
+    for (uint32_t r = 0; r < P.local_batch; ++r) {  // sorted positions r * n_gpus + c grow with r, and so do their lengths
+      l = first_above(s_cnt, l, P.max_len, r * P.n_gpus + c);
+      tokens += l;
+    }
     lo = min(lo, tokens), hi = max(hi, tokens);
   }
   finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
+}
+
+// Host: length of dataset entry `index` (entries ordered by length).
+uint32_t length_of(const std::vector<uint32_t>& cum, uint32_t index) {
+  return (uint32_t)(std::upper_bound(cum.begin() + 1, cum.end(), index) - cum.begin());
+}
+
+// Guide table of the `size` entries after the first `before`: for every value of a draw's upper kGuideBits
+// bits, the smallest (low half) and the largest (high half) length that such a draw selects.  The index a
+// draw selects grows with the draw, and the length with the index, so the two ends bound everything between.
+void fill_guide(uint32_t* out, const std::vector<uint32_t>& cum, uint32_t before, uint32_t size) {
+  for (uint32_t ub = 0; ub < kGuideSize; ++ub) {
+    const uint64_t u_min = (uint64_t)ub << (32u - kGuideBits), u_max = u_min + (1ull << (32u - kGuideBits)) - 1u;
+    if (size == 0) {
+      out[ub] = 1u | (1u << 16);  // never drawn from
+      continue;
+    }
+    const uint32_t l_min = length_of(cum, before + (uint32_t)((u_min * size) >> 32));
+    const uint32_t l_max = length_of(cum, before + (uint32_t)((u_max * size) >> 32));
+    out[ub] = l_min | (l_max << 16);
+  }
 }
 
 }  // namespace
@@ -235,8 +380,8 @@ extern "C" {
 
 const char* lbs_last_error(void) { return g_error.c_str(); }
 
-int lbs_dataset_create(lbs_dataset** out, int device, uint32_t max_len, const uint32_t* cum, uint32_t n_strata,
-                       const uint32_t* stratum_end) {
+static int dataset_create(lbs_dataset** out, int device, uint32_t max_len, const uint32_t* cum, uint32_t n_strata,
+                          const uint32_t* stratum_end) {
   if (!out) return fail(LBS_ERR_NULL, "out is NULL");
   *out = nullptr;
   if (!cum || !stratum_end) return fail(LBS_ERR_NULL, "cum or stratum_end is NULL");
@@ -253,39 +398,60 @@ int lbs_dataset_create(lbs_dataset** out, int device, uint32_t max_len, const ui
       return fail(LBS_ERR_ARG, "stratum_end must be increasing and lie in [1, max_len]");
   }
   if (stratum_end[n_strata - 1] != max_len) return fail(LBS_ERR_ARG, "the last stratum must end at max_len");
-  lbs_dataset* ds = new (std::nothrow) lbs_dataset;
-  if (!ds) return fail(LBS_ERR_HIP, "out of host memory");
-  ds->device = device, ds->max_len = max_len, ds->n_strata = n_strata;
+  lbs_dataset* ds = new lbs_dataset;
+  *out = ds;  // from here on the caller's wrapper frees it on failure
+  ds->max_len = max_len, ds->n_strata = n_strata;
   ds->cum.assign(cum, cum + max_len + 1);
   ds->stratum_end.assign(stratum_end, stratum_end + n_strata);
   if (device >= 0) {
+    std::vector<uint32_t> guide((size_t)(1 + n_strata) * kGuideSize);
+    fill_guide(guide.data(), ds->cum, 0, cum[max_len]);
+    for (uint32_t s = 0; s < n_strata; ++s) {
+      const uint32_t before = cum[s == 0 ? 0 : stratum_end[s - 1]];
+      fill_guide(guide.data() + (size_t)(1 + s) * kGuideSize, ds->cum, before, cum[stratum_end[s]] - before);
+    }
     int prev = -1;
     (void)hipGetDevice(&prev);
     hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess) ds->device = device;
     if (e == hipSuccess) e = hipMalloc((void**)&ds->d_cum, (max_len + 1) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemcpy(ds->d_cum, cum, (max_len + 1) * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMalloc((void**)&ds->d_guide, guide.size() * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemcpy(ds->d_guide, guide.data(), guide.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (prev >= 0 && prev != device) (void)hipSetDevice(prev);
-    if (e != hipSuccess) {
-      if (ds->d_cum) (void)hipFree(ds->d_cum);
-      delete ds;
-      return fail(LBS_ERR_HIP, std::string("uploading the histogram: ") + hipGetErrorString(e));
-    }
+    if (e != hipSuccess) return fail(LBS_ERR_HIP, std::string("uploading the histogram: ") + hipGetErrorString(e));
   }
-  *out = ds;
   return 0;
 }
 
 void lbs_dataset_destroy(lbs_dataset* ds) {
   if (!ds) return;
-  if (ds->device >= 0 && ds->d_cum) {
+  if (ds->device >= 0 && (ds->d_cum || ds->d_guide)) {
     int prev = -1;
     (void)hipGetDevice(&prev);
     (void)hipSetDevice(ds->device);
     (void)hipDeviceSynchronize();
-    (void)hipFree(ds->d_cum);
+    if (ds->d_cum) (void)hipFree(ds->d_cum);
+    if (ds->d_guide) (void)hipFree(ds->d_guide);
     if (prev >= 0 && prev != ds->device) (void)hipSetDevice(prev);
   }
   delete ds;
+}
+
+int lbs_dataset_create(lbs_dataset** out, int device, uint32_t max_len, const uint32_t* cum, uint32_t n_strata,
+                       const uint32_t* stratum_end) {
+  int rc;
+  try {  // no C++ exception crosses the C boundary
+    rc = dataset_create(out, device, max_len, cum, n_strata, stratum_end);
+  } catch (...) {
+    rc = LBS_ERR_HIP;
+    g_error.clear();  // out of host memory: nothing is allocated to say so
+  }
+  if (rc != 0 && out && *out) {
+    lbs_dataset_destroy(*out);
+    *out = nullptr;
+  }
+  return rc;
 }
 
 int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min, uint32_t* trial_max, uint64_t* sums,
@@ -301,20 +467,25 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   Params P{};
   P.max_len = ds->max_len, P.local_batch = run->local_batch, P.gpus_per_node = run->gpus_per_node;
   P.n_gpus = run->n_gpus, P.snake = run->method == LBS_LOCAL_SNAKE, P.stratified = stratified;
-  P.total = ds->cum[ds->max_len], P.seed = run->seed, P.first_trial = run->first_trial;
+  P.total = ds->cum[ds->max_len], P.seed = run->seed;
+  P.n_guide = stratified ? ds->n_strata : 1u;
   if (stratified) {
     uint32_t j = 0;
     for (uint32_t s = 0; s < ds->n_strata; ++s) {
       const uint32_t lo = ds->cum[s == 0 ? 0 : ds->stratum_end[s - 1]], size = ds->cum[ds->stratum_end[s]] - lo;
       if (run->quota[s] && size == 0) return fail(LBS_ERR_ARG, "a stratum with a quota has no entries");
       if ((uint64_t)j + run->quota[s] > run->local_batch) return fail(LBS_ERR_ARG, "the quotas exceed local_batch");
-      for (uint32_t q = 0; q < run->quota[s]; ++q, ++j) P.slot_lo[j] = lo, P.slot_size[j] = size;
+      for (uint32_t q = 0; q < run->quota[s]; ++q, ++j) P.slot_lo[j] = lo, P.slot_size[j] = size, P.slot_guide[j] = s * kGuideSize;
     }
     if (j != run->local_batch) return fail(LBS_ERR_ARG, "the quotas must add up to local_batch");
+  } else {
+    for (uint32_t j = 0; j < run->local_batch; ++j) P.slot_lo[j] = 0, P.slot_size[j] = P.total, P.slot_guide[j] = 0;
   }
+  uint32_t pool = 0;
   if (local) {
     if (run->gpus_per_node == 0 || run->n_gpus % run->gpus_per_node) return fail(LBS_ERR_ARG, "n_gpus must be a multiple of gpus_per_node");
     if ((uint64_t)run->gpus_per_node * run->local_batch > LBS_MAX_NODE_POOL) return fail(LBS_ERR_LIMIT, "gpus_per_node * local_batch exceeds LBS_MAX_NODE_POOL");
+    pool = run->gpus_per_node * run->local_batch;
   }
   if (!sums) return fail(LBS_ERR_NULL, "sums is NULL");
   if (ds->device < 0) return fail(LBS_ERR_HOST, "host-only dataset (device -1) cannot run kernels");
@@ -325,11 +496,29 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   unsigned long long* ds_sums = reinterpret_cast<unsigned long long*>(sums);
   hipLaunchKernelGGL(k_lbs_clear, dim3(1), dim3(64), 0, s, ds_sums);
   hipError_t e = hipGetLastError();
-  if (e == hipSuccess && run->n_trials > 0) {
-    const dim3 grid((uint32_t)run->n_trials), block(kBlock);
-    if (local) hipLaunchKernelGGL(k_lbs_local, grid, block, 0, s, P, ds->d_cum, trial_min, trial_max, ds_sums);
-    else if (run->method == LBS_GLOBAL) hipLaunchKernelGGL(k_lbs_global, grid, block, 0, s, P, ds->d_cum, trial_min, trial_max, ds_sums);
-    else hipLaunchKernelGGL(k_lbs_keep, grid, block, 0, s, P, ds->d_cum, trial_min, trial_max, ds_sums);
+  // dynamic LDS in words: histogram, guide tables, then the sorted pools (local) or the trial's histogram (global)
+  const uint32_t tables = ds->max_len + 1u + P.n_guide * kGuideSize;
+  const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u : 0u));
+  for (uint64_t done = 0; e == hipSuccess && done < run->n_trials; done += kTrialsPerLaunch) {
+    const dim3 grid((uint32_t)std::min(kTrialsPerLaunch, run->n_trials - done)), block(kBlock);
+    P.first_trial = run->first_trial + done;
+    uint32_t* tmin = trial_min ? trial_min + done : nullptr;
+    uint32_t* tmax = trial_max ? trial_max + done : nullptr;
+    if (local) {
+      const uint32_t gpn = run->gpus_per_node;
+      const bool in_lanes = gpn <= 32 && (gpn & (gpn - 1u)) == 0;
+      void (*kernel)(const Params, const uint32_t*, const uint32_t*, uint32_t*, uint32_t*, unsigned long long*) =
+          pool <= 64    ? (in_lanes ? k_lbs_local<1, true> : k_lbs_local<1, false>)
+          : pool <= 128 ? (in_lanes ? k_lbs_local<2, true> : k_lbs_local<2, false>)
+          : pool <= 256 ? (in_lanes ? k_lbs_local<4, true> : k_lbs_local<4, false>)
+          : pool <= 512 ? (in_lanes ? k_lbs_local<8, true> : k_lbs_local<8, false>)
+                        : (in_lanes ? k_lbs_local<16, true> : k_lbs_local<16, false>);
+      hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+    } else if (run->method == LBS_GLOBAL) {
+      hipLaunchKernelGGL(k_lbs_global, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+    } else {
+      hipLaunchKernelGGL(k_lbs_keep, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+    }
     e = hipGetLastError();
   }
   if (prev >= 0 && prev != ds->device) (void)hipSetDevice(prev);

@@ -55,6 +55,12 @@ def test_ragged_sizes_and_other_strata(method):
     check(cum, (50, 201, 333), method, 7, 1, 9, [2, 4, 1], seed=6, n=5)
     check(cum, (50, 201, 333), method, 7, 9, 9, [0, 7, 0], seed=7, n=5)
     check(CUM, ENDS, method, 64, 16, 32, [1, 1, 1, 61], seed=8, n=3)
+    # node sizes on both sides of what is dealt within the lanes (powers of two up to 32) and through LDS
+    check(CUM, ENDS, method, 16, 4, 36, [4, 4, 4, 4], seed=9, n=4)
+    check(CUM, ENDS, method, 5, 32, 96, [1, 1, 1, 2], seed=10, n=4)
+    check(CUM, ENDS, method, 3, 64, 128, [1, 0, 1, 1], seed=11, n=4)
+    check(CUM, ENDS, method, 1, 2, 6, [0, 0, 1, 0], seed=12, n=4)
+    check(CUM, ENDS, method, 2, 24, 48, [1, 0, 0, 1], seed=13, n=4)
 
 
 def test_degenerate_dataset_single_gpu_zero_trials_and_fig3_quota():
