@@ -179,12 +179,15 @@ def lbs_bench(a, dev):
         cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
     # dominant kernel: k_lbs_local (two of the five methods).  Vector instructions it executes, from a rocprofv3
-    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 8.843e9 wavefront
-    # instructions per 100 000 trials at 1 024 GPUs = 345 lane-operation slots per draw (64 lanes per instruction).
-    ops_per_draw = 345
+    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 3.309e9 wavefront
+    # instructions per 100 000 trials at 1 024 GPUs = 129 lane-operation slots per draw (64 lanes per instruction).
+    # Peak: a SIMD issues a 64-lane move, add or xor in 2 cycles and a multiply, minimum or median in 4 (measured);
+    # the bound taken is every instruction at the faster rate, 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T
+    # lane-operations/s, which is also the rate behind the chip's 157.3 TFLOP/s of fp32 vector FMAs.
+    ops_per_draw = 129
     t_local = (per_method[lbs.LBS_LOCAL_RASTER] + per_method[lbs.LBS_LOCAL_SNAKE]) / 2 * 1e-3
     achieved = ops_per_draw * n * G * b / t_local / 1e12
-    peak = 256 * 4 * 16 * 2.4e9 / 1e12          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s
+    peak = 256 * 4 * 32 * 2.4e9 / 1e12
     print(json.dumps({
         "metric": "load-balancing simulation throughput (sequence draws simulated per second, five methods)",
         "value": round(draws / (ms * 1e-3) / 1e9, 3), "unit": "G draws/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -192,7 +195,7 @@ def lbs_bench(a, dev):
         "data": "synthetic",
         "config": {"workload": f"Table 5 setting: {G} simulated GPUs, local batch {b}, nodes of {P}, {n} trials per method, "
                                f"piecewise-uniform length histogram with the printed stratum shares, quota {quota}"},
-        "roofline": {"bound": "alu", "kernel": "k_lbs_local (draws, bitonic sort per node in LDS, raster / snake deal)",
+        "roofline": {"bound": "alu", "kernel": "k_lbs_local (draws, bitonic sort of each node's pool in registers, raster / snake deal)",
                      "achieved": round(achieved, 2), "peak": round(peak, 1), "unit": "T lane-ops/s",
                      "frac": round(achieved / peak, 3), "traffic": None, "ops_per_draw": ops_per_draw,
                      "ms_per_launch": round(t_local * 1e3, 3)},

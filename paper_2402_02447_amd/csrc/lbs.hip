@@ -1,9 +1,9 @@
 // Load-balancing simulation for gfx950 (MI355X): host entry points and kernels.
 // See lbs.h for what is simulated and for the contract of every call.
 //
-// One workgroup (256 threads, four wavefronts) runs one trial.  Nothing here is a
-// contraction or a stream over HBM: the work is integer ALU, cross-lane traffic and
-// LDS, the outputs are two words per trial.
+// A workgroup (256 threads, four wavefronts) runs one trial at a time and a share of
+// the call's trials in turn.  Nothing here is a contraction or a stream over HBM: the
+// work is integer ALU, cross-lane traffic and LDS, the outputs are two words per trial.
 //
 // A draw is one SplitMix64 output (a handful of 64-bit integer operations) and the
 // inverse of the cumulative histogram at the index it selects.  The histogram sits in
@@ -18,16 +18,17 @@
 //                       i % 64, padded to a multiple of 64 with a sentinel above every
 //                       length) and sort it there with a bitonic network: a
 //                       compare-exchange at distance < 64 is a cross-lane exchange, one
-//                       at distance >= 64 pairs two registers of the same lane.  The
-//                       sorted pool goes to LDS once, where each GPU's column is added
-//                       up in raster or snake order.
+//                       at distance >= 64 pairs two registers of the same lane.  For a
+//                       node of 1, 2, 4, ... 32 GPUs each GPU's column of the sorted pool
+//                       is then summed across lanes; else the pool goes to LDS once, where
+//                       each GPU's column is added up in raster or snake order.
 //   GLOBAL            : lengths are small integers, so the trial's pool of
 //                       n_gpus * local_batch draws is sorted by counting: an LDS
 //                       histogram, a block-wide prefix sum, and the entry at sorted
 //                       position q found by binary search in the running counts.
 // Per-trial minimum and maximum are combined with shuffles and LDS; the two sums
-// over trials with 64-bit integer atomics (integer addition is associative, so the
-// result does not depend on the order).
+// over trials are kept per workgroup and added up with 64-bit integer atomics at its
+// end (integer addition is associative, so the result does not depend on the order).
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -49,6 +50,7 @@ struct lbs_dataset {
   uint32_t max_len = 0, n_strata = 0;
   std::vector<uint32_t> cum, stratum_end;
   uint32_t* d_cum = nullptr;
+  uint32_t n_cus = 1;           // compute units of the device
   uint32_t* d_guide = nullptr;  // (1 + n_strata) tables of kGuideSize entries: the whole dataset, then each stratum
 };
 
@@ -56,7 +58,7 @@ namespace lbs {
 namespace {
 
 constexpr uint32_t kBlock = 256, kWaves = 4;
-constexpr uint64_t kTrialsPerLaunch = 1ull << 22;  // a launch stays below 2^32 threads
+constexpr uint32_t kGridPerCu = 32;  // workgroups launched per compute unit (at most 8 are resident at a time)
 
 thread_local std::string g_error;
 int fail(int code, const std::string& msg) {
@@ -72,6 +74,7 @@ struct Params {  // by-value kernel argument
   uint32_t slot_size[LBS_MAX_LOCAL_BATCH];    //   entries in that range,
   uint32_t slot_guide[LBS_MAX_LOCAL_BATCH];   //   and where that range's guide table starts in LDS
   uint64_t seed, first_trial;
+  uint32_t n_trials;
 };
 
 // SplitMix64: output number k + 1 of the generator seeded with `seed` is mix(state(seed, k)); the state
@@ -115,23 +118,43 @@ __device__ __forceinline__ uint32_t* load_tables(uint32_t* s_dyn, const Params& 
   return s_guide;
 }
 
-// Combines the threads' running minimum and maximum and lets thread 0 publish the trial's result.
-__device__ __forceinline__ void finish_trial(uint32_t lo, uint32_t hi, uint32_t* s_lo, uint32_t* s_hi,
-                                             uint32_t* trial_min, uint32_t* trial_max, unsigned long long* sums) {
+// A workgroup loads the tables once and then runs trials blockIdx.x, blockIdx.x + gridDim.x, ... of the
+// call, so the grid need only fill the chip, and thread 0 carries the workgroup's share of the two sums.
+
+// Wavefront minima and maxima of a trial, double-buffered by the parity of the workgroup's trial count: a
+// wavefront can be one trial ahead of thread 0, never two (the barrier in between needs all of them).
+struct Finish {
+  uint32_t lo[2][kWaves], hi[2][kWaves];
+};
+
+// Combines the threads' minimum and maximum of trial t (the round-th this workgroup runs); thread 0 stores
+// them and adds them to its running sums.
+__device__ __forceinline__ void finish_trial(uint32_t lo, uint32_t hi, Finish& f, uint32_t round, uint32_t t,
+                                             uint32_t* trial_min, uint32_t* trial_max, unsigned long long& sum_lo,
+                                             unsigned long long& sum_hi) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     lo = min(lo, (uint32_t)__shfl_xor((int)lo, off, 64));
     hi = max(hi, (uint32_t)__shfl_xor((int)hi, off, 64));
   }
-  if ((threadIdx.x & 63u) == 0) s_lo[threadIdx.x >> 6] = lo, s_hi[threadIdx.x >> 6] = hi;
+  const uint32_t buf = round & 1u;
+  if ((threadIdx.x & 63u) == 0) f.lo[buf][threadIdx.x >> 6] = lo, f.hi[buf][threadIdx.x >> 6] = hi;
   __syncthreads();
   if (threadIdx.x == 0) {
-    lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
-    hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
-    if (trial_min) trial_min[blockIdx.x] = lo;
-    if (trial_max) trial_max[blockIdx.x] = hi;
-    atomicAdd(&sums[0], (unsigned long long)lo);
-    atomicAdd(&sums[1], (unsigned long long)hi);
+    lo = min(min(f.lo[buf][0], f.lo[buf][1]), min(f.lo[buf][2], f.lo[buf][3]));
+    hi = max(max(f.hi[buf][0], f.hi[buf][1]), max(f.hi[buf][2], f.hi[buf][3]));
+    if (trial_min) trial_min[t] = lo;
+    if (trial_max) trial_max[t] = hi;
+    sum_lo += lo, sum_hi += hi;
+  }
+}
+
+// Thread 0 adds the workgroup's sums to the call's.
+__device__ __forceinline__ void publish_sums(unsigned long long* sums, unsigned long long sum_lo,
+                                             unsigned long long sum_hi) {
+  if (threadIdx.x == 0) {
+    atomicAdd(&sums[0], sum_lo);
+    atomicAdd(&sums[1], sum_hi);
   }
 }
 
@@ -144,18 +167,22 @@ __global__ __launch_bounds__(kBlock) void k_lbs_keep(const Params P, const uint3
                                                       const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                       uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, guide tables
-  __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
+  __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
-  const uint64_t k_trial = (P.first_trial + blockIdx.x) * P.n_gpus * (uint64_t)P.local_batch;  // the trial's first draw
-  uint32_t lo = 0xffffffffu, hi = 0u;
-  for (uint32_t g = threadIdx.x; g < P.n_gpus; g += kBlock) {
-    uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
-    uint32_t tokens = 0;
-    for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
-      tokens += draw(s_dyn, s_guide + P.slot_guide[j], z, P.slot_lo[j], P.slot_size[j]);
-    lo = min(lo, tokens), hi = max(hi, tokens);
+  unsigned long long sum_lo = 0, sum_hi = 0;
+  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    const uint64_t k_trial = (P.first_trial + t) * P.n_gpus * (uint64_t)P.local_batch;  // the trial's first draw
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (uint32_t g = threadIdx.x; g < P.n_gpus; g += kBlock) {
+      uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
+      uint32_t tokens = 0;
+      for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
+        tokens += draw(s_dyn, s_guide + P.slot_guide[j], z, P.slot_lo[j], P.slot_size[j]);
+      lo = min(lo, tokens), hi = max(hi, tokens);
+    }
+    finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
   }
-  finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
+  publish_sums(sums, sum_lo, sum_hi);
 }
 
 // Median of three: with c = 0 it is min(a, b), with c = 0xffffffff it is max(a, b) (one v_med3_u32).
@@ -234,7 +261,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
                                                        const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                        uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, guide tables, (not IN_LANES) one sorted pool per wavefront
-  __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
+  __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   const uint32_t n_nodes = P.n_gpus / P.gpus_per_node;
@@ -252,55 +279,59 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
 #pragma unroll
   for (int b = 0; b < 6; ++b) bit[b] = 0u - ((lane >> b) & 1u);
   const bool odd_row = ((lane / P.gpus_per_node) & 1u) != 0u;  // IN_LANES only
-  const uint64_t k_trial = (P.first_trial + blockIdx.x) * P.n_gpus * (uint64_t)P.local_batch;
-  uint32_t lo = 0xffffffffu, hi = 0u;
-  // Every wavefront makes the same number of rounds, so the barriers below (not IN_LANES) are met by all; a
-  // wavefront without a node in the last round only keeps them company.
-  for (uint32_t base = 0; base < n_nodes; base += kWaves) {
-    const uint32_t node = base + wave;
-    const bool active = node < n_nodes;
-    if (active) {
-      const uint64_t z_node = state(P.seed, k_trial + (uint64_t)node * pool);  // a node's draws are consecutive
-      uint32_t v[E];
-#pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const uint32_t i = (uint32_t)e * 64u + lane;
-        v[e] = i < pool ? draw(s_dyn, s_guide + goff[e], z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
-      }
-      bitonic_sort<E>(v, bit);
-      if (IN_LANES) {
-        uint32_t tokens = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) tokens += (uint32_t)e * 64u + lane < pool ? v[e] : 0u;  // the padding sorts to the end
-        if (P.snake) {  // an odd row is dealt right to left: its column c goes to GPU gpus_per_node - 1 - c
-          const uint32_t mirrored = (uint32_t)__shfl_xor((int)tokens, (int)(P.gpus_per_node - 1u), 64);
-          tokens = odd_row ? mirrored : tokens;
-        }
-        for (uint32_t m = P.gpus_per_node; m < 64u; m <<= 1) tokens += (uint32_t)__shfl_xor((int)tokens, (int)m, 64);
-        lo = min(lo, tokens), hi = max(hi, tokens);  // every lane now holds the total of GPU lane % gpus_per_node
-      } else {
+  unsigned long long sum_lo = 0, sum_hi = 0;
+  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    const uint64_t k_trial = (P.first_trial + t) * P.n_gpus * (uint64_t)P.local_batch;
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    // Every wavefront makes the same number of rounds, so the barriers below (not IN_LANES) are met by all; a
+    // wavefront without a node in the last round only keeps them company.
+    for (uint32_t base = 0; base < n_nodes; base += kWaves) {
+      const uint32_t node = base + wave;
+      const bool active = node < n_nodes;
+      if (active) {
+        const uint64_t z_node = state(P.seed, k_trial + (uint64_t)node * pool);  // a node's draws are consecutive
+        uint32_t v[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const uint32_t i = (uint32_t)e * 64u + lane;
-          if (i < pool) sorted[i] = v[e];
+          v[e] = i < pool ? draw(s_dyn, s_guide + goff[e], z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
+        }
+        bitonic_sort<E>(v, bit);
+        if (IN_LANES) {
+          uint32_t tokens = 0;
+#pragma unroll
+          for (int e = 0; e < E; ++e) tokens += (uint32_t)e * 64u + lane < pool ? v[e] : 0u;  // the padding sorts to the end
+          if (P.snake) {  // an odd row is dealt right to left: its column c goes to GPU gpus_per_node - 1 - c
+            const uint32_t mirrored = (uint32_t)__shfl_xor((int)tokens, (int)(P.gpus_per_node - 1u), 64);
+            tokens = odd_row ? mirrored : tokens;
+          }
+          for (uint32_t m = P.gpus_per_node; m < 64u; m <<= 1) tokens += (uint32_t)__shfl_xor((int)tokens, (int)m, 64);
+          lo = min(lo, tokens), hi = max(hi, tokens);  // every lane now holds the total of GPU lane % gpus_per_node
+        } else {
+#pragma unroll
+          for (int e = 0; e < E; ++e) {
+            const uint32_t i = (uint32_t)e * 64u + lane;
+            if (i < pool) sorted[i] = v[e];
+          }
         }
       }
-    }
-    if (!IN_LANES) {
-      __syncthreads();
-      if (active)
-        for (uint32_t c = lane; c < P.gpus_per_node; c += 64u) {
-          uint32_t tokens = 0;
-          for (uint32_t r = 0; r < P.local_batch; ++r) {
-            const uint32_t col = (P.snake && (r & 1u)) ? P.gpus_per_node - 1u - c : c;  // position in the row dealt to GPU c
-            tokens += sorted[r * P.gpus_per_node + col];
+      if (!IN_LANES) {
+        __syncthreads();
+        if (active)
+          for (uint32_t c = lane; c < P.gpus_per_node; c += 64u) {
+            uint32_t tokens = 0;
+            for (uint32_t r = 0; r < P.local_batch; ++r) {
+              const uint32_t col = (P.snake && (r & 1u)) ? P.gpus_per_node - 1u - c : c;  // position in the row dealt to GPU c
+              tokens += sorted[r * P.gpus_per_node + col];
+            }
+            lo = min(lo, tokens), hi = max(hi, tokens);
           }
-          lo = min(lo, tokens), hi = max(hi, tokens);
-        }
-      __syncthreads();
+        __syncthreads();
+      }
     }
+    finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
   }
-  finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
+  publish_sums(sums, sum_lo, sum_hi);
 }
 
 // GLOBAL: pool, sort and deal over all GPUs.
@@ -309,45 +340,51 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
                                                         uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram
   __shared__ uint32_t s_scan[kBlock];
-  __shared__ uint32_t s_lo[kWaves], s_hi[kWaves];
+  __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
   uint32_t* s_cnt = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize;  // first counts of the trial's draws, then their running sum
   const uint32_t tid = threadIdx.x;
-  for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_cnt[i] = 0u;
-  __syncthreads();
   const uint32_t pool = P.n_gpus * P.local_batch;
-  uint64_t z = state(P.seed, (P.first_trial + blockIdx.x) * (uint64_t)pool + tid);
-  for (uint32_t i = tid; i < pool; i += kBlock, z += kBlock * kGamma) atomicAdd(&s_cnt[draw(s_dyn, s_guide, z, 0u, P.total)], 1u);
-  __syncthreads();
-  // running sum over lengths: thread t owns a contiguous piece, pieces are combined by a doubling scan
-  const uint32_t per = (P.max_len + 1u + kBlock - 1u) / kBlock;
+  const uint32_t per = (P.max_len + 1u + kBlock - 1u) / kBlock;  // lengths per thread in the running sum
   const uint32_t a = tid * per, b = min(a + per, P.max_len + 1u);
-  uint32_t piece = 0;
-  for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
-  s_scan[tid] = piece;
-  __syncthreads();
-  for (uint32_t d = 1; d < kBlock; d <<= 1) {
-    const uint32_t add = tid >= d ? s_scan[tid - d] : 0u;
+  unsigned long long sum_lo = 0, sum_hi = 0;
+  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    // the previous trial's last reads of s_cnt lie before the barrier in its finish_trial
+    for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_cnt[i] = 0u;
     __syncthreads();
-    s_scan[tid] += add;
+    uint64_t z = state(P.seed, (P.first_trial + t) * (uint64_t)pool + tid);
+    for (uint32_t i = tid; i < pool; i += kBlock, z += kBlock * kGamma)
+      atomicAdd(&s_cnt[draw(s_dyn, s_guide, z, 0u, P.total)], 1u);
     __syncthreads();
-  }
-  uint32_t run = s_scan[tid] - piece;  // draws with a length below this thread's piece
-  for (uint32_t i = a; i < b; ++i) {
-    run += s_cnt[i];
-    s_cnt[i] = run;  // draws of length <= i
-  }
-  __syncthreads();
-  uint32_t lo = 0xffffffffu, hi = 0u;
-  for (uint32_t c = tid; c < P.n_gpus; c += kBlock) {
-    uint32_t tokens = 0, l = 1;
-    for (uint32_t r = 0; r < P.local_batch; ++r) {  // sorted positions r * n_gpus + c grow with r, and so do their lengths
-      l = first_above(s_cnt, l, P.max_len, r * P.n_gpus + c);
-      tokens += l;
+    // running sum over lengths: a thread owns a contiguous piece, pieces are combined by a doubling scan
+    uint32_t piece = 0;
+    for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
+    s_scan[tid] = piece;
+    __syncthreads();
+    for (uint32_t d = 1; d < kBlock; d <<= 1) {
+      const uint32_t add = tid >= d ? s_scan[tid - d] : 0u;
+      __syncthreads();
+      s_scan[tid] += add;
+      __syncthreads();
     }
-    lo = min(lo, tokens), hi = max(hi, tokens);
+    uint32_t run = s_scan[tid] - piece;  // draws with a length below this thread's piece
+    for (uint32_t i = a; i < b; ++i) {
+      run += s_cnt[i];
+      s_cnt[i] = run;  // draws of length <= i
+    }
+    __syncthreads();
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (uint32_t c = tid; c < P.n_gpus; c += kBlock) {
+      uint32_t tokens = 0, l = 1;
+      for (uint32_t r = 0; r < P.local_batch; ++r) {  // sorted positions r * n_gpus + c grow with r, and so do their lengths
+        l = first_above(s_cnt, l, P.max_len, r * P.n_gpus + c);
+        tokens += l;
+      }
+      lo = min(lo, tokens), hi = max(hi, tokens);
+    }
+    finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
   }
-  finish_trial(lo, hi, s_lo, s_hi, trial_min, trial_max, sums);
+  publish_sums(sums, sum_lo, sum_hi);
 }
 
 // Host: length of dataset entry `index` (entries ordered by length).
@@ -414,6 +451,9 @@ static int dataset_create(lbs_dataset** out, int device, uint32_t max_len, const
     (void)hipGetDevice(&prev);
     hipError_t e = hipSetDevice(device);
     if (e == hipSuccess) ds->device = device;
+    int n_cus = 0;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (e == hipSuccess) ds->n_cus = (uint32_t)std::max(n_cus, 1);
     if (e == hipSuccess) e = hipMalloc((void**)&ds->d_cum, (max_len + 1) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemcpy(ds->d_cum, cum, (max_len + 1) * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMalloc((void**)&ds->d_guide, guide.size() * sizeof(uint32_t));
@@ -499,11 +539,10 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   // dynamic LDS in words: histogram, guide tables, then the sorted pools (local) or the trial's histogram (global)
   const uint32_t tables = ds->max_len + 1u + P.n_guide * kGuideSize;
   const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u : 0u));
-  for (uint64_t done = 0; e == hipSuccess && done < run->n_trials; done += kTrialsPerLaunch) {
-    const dim3 grid((uint32_t)std::min(kTrialsPerLaunch, run->n_trials - done)), block(kBlock);
-    P.first_trial = run->first_trial + done;
-    uint32_t* tmin = trial_min ? trial_min + done : nullptr;
-    uint32_t* tmax = trial_max ? trial_max + done : nullptr;
+  if (e == hipSuccess && run->n_trials > 0) {
+    // trials cost the same, so a few workgroups per resident slot balance; each loops over its share of the trials
+    const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
+    P.first_trial = run->first_trial, P.n_trials = (uint32_t)run->n_trials;
     if (local) {
       const uint32_t gpn = run->gpus_per_node;
       const bool in_lanes = gpn <= 32 && (gpn & (gpn - 1u)) == 0;
@@ -513,11 +552,11 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
           : pool <= 256 ? (in_lanes ? k_lbs_local<4, true> : k_lbs_local<4, false>)
           : pool <= 512 ? (in_lanes ? k_lbs_local<8, true> : k_lbs_local<8, false>)
                         : (in_lanes ? k_lbs_local<16, true> : k_lbs_local<16, false>);
-      hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+      hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     } else if (run->method == LBS_GLOBAL) {
-      hipLaunchKernelGGL(k_lbs_global, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+      hipLaunchKernelGGL(k_lbs_global, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     } else {
-      hipLaunchKernelGGL(k_lbs_keep, grid, block, lds, s, P, ds->d_cum, ds->d_guide, tmin, tmax, ds_sums);
+      hipLaunchKernelGGL(k_lbs_keep, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     }
     e = hipGetLastError();
   }

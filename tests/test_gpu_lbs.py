@@ -75,6 +75,13 @@ def test_degenerate_dataset_single_gpu_zero_trials_and_fig3_quota():
     check(CUM, ENDS, lbs.LBS_LOCAL_SNAKE, 16, 8, 64, [5, 2, 3, 6], seed=4, n=100)
 
 
+@pytest.mark.parametrize("method", [lbs.LBS_NONE, lbs.LBS_STRATIFIED, lbs.LBS_LOCAL_RASTER, lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL])
+def test_more_trials_than_workgroups_so_that_each_runs_several(method):
+    # a call launches at most 32 workgroups per compute unit; beyond that a workgroup runs trials in turn
+    n = 256 * 32 * 2 + 123
+    check(CUM, ENDS, method, 4, 2 if method != lbs.LBS_LOCAL_SNAKE else 3, 12, [1, 1, 1, 1], seed=31, n=n, first=7)
+
+
 def test_max_len_1024_and_many_gpus():
     cum = W.length_histogram_piecewise_uniform(3_000_000, (256, 512, 768, 1024), (0.1, 0.2, 0.3, 0.4))
     for method in (lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL):
