@@ -24,8 +24,9 @@
 //                       each GPU's column is added up in raster or snake order.
 //   GLOBAL            : lengths are small integers, so the trial's pool of
 //                       n_gpus * local_batch draws is sorted by counting: an LDS
-//                       histogram, a block-wide prefix sum, and the entry at sorted
-//                       position q found by binary search in the running counts.
+//                       histogram and a block-wide running sum give every length its
+//                       range of sorted positions, which it spreads over the GPUs
+//                       (position q goes to GPU q % n_gpus) through a difference array.
 // Per-trial minimum and maximum are combined with shuffles and LDS; the two sums
 // over trials are kept per workgroup and added up with 64-bit integer atomics at its
 // end (integer addition is associative, so the result does not depend on the order).
@@ -58,6 +59,7 @@ namespace lbs {
 namespace {
 
 constexpr uint32_t kBlock = 256, kWaves = 4;
+constexpr uint32_t kMaxSpreadGpus = 8192;  // k_lbs_global keeps one LDS word per GPU up to here
 constexpr uint32_t kGridPerCu = 32;  // workgroups launched per compute unit (at most 8 are resident at a time)
 
 thread_local std::string g_error;
@@ -334,53 +336,101 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
   publish_sums(sums, sum_lo, sum_hi);
 }
 
-// GLOBAL: pool, sort and deal over all GPUs.
+// Inclusive running sum over the workgroup of one value per thread (s_scan: kBlock words); all threads call it.
+__device__ __forceinline__ uint32_t block_running_sum(uint32_t* s_scan, uint32_t value) {
+  const uint32_t tid = threadIdx.x;
+  s_scan[tid] = value;
+  __syncthreads();
+  for (uint32_t d = 1; d < kBlock; d <<= 1) {
+    const uint32_t add = tid >= d ? s_scan[tid - d] : 0u;
+    __syncthreads();
+    s_scan[tid] += add;
+    __syncthreads();
+  }
+  return s_scan[tid];
+}
+
+// GLOBAL: pool, sort and deal over all GPUs.  The pool is sorted by counting (lengths are small integers):
+// after the running sum, the entries of length l hold sorted positions cnt[l-1] .. cnt[l] - 1, and position q
+// goes to GPU q % n_gpus.
+// SPREAD (n_gpus <= kMaxSpreadGpus): every length adds itself to the GPUs its positions fall on, as a
+// difference array over the GPUs: whole turns round all GPUs go to a common base, the rest is a circular
+// range [first, first + rest) marked at its two ends; a running sum over the GPUs then gives every GPU's tokens.
+// Otherwise every GPU looks up the length at each of its local_batch positions by binary search.
+template <bool SPREAD>
 __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uint32_t* __restrict__ cum,
                                                         const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                         uint32_t* trial_max, unsigned long long* sums) {
-  extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram
+  extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram, (SPREAD) one word per GPU
   __shared__ uint32_t s_scan[kBlock];
+  __shared__ uint32_t s_base;
   __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
   uint32_t* s_cnt = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize;  // first counts of the trial's draws, then their running sum
+  uint32_t* s_gpu = s_cnt + P.max_len + 1u;                           // SPREAD: difference array over the GPUs
   const uint32_t tid = threadIdx.x;
   const uint32_t pool = P.n_gpus * P.local_batch;
   const uint32_t per = (P.max_len + 1u + kBlock - 1u) / kBlock;  // lengths per thread in the running sum
   const uint32_t a = tid * per, b = min(a + per, P.max_len + 1u);
+  const uint32_t per_gpu = (P.n_gpus + kBlock - 1u) / kBlock;    // SPREAD: GPUs per thread in theirs
+  const uint32_t ga = min(tid * per_gpu, P.n_gpus), gb = min(ga + per_gpu, P.n_gpus);
   unsigned long long sum_lo = 0, sum_hi = 0;
   for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
-    // the previous trial's last reads of s_cnt lie before the barrier in its finish_trial
+    // the previous trial's last reads of s_cnt and s_gpu lie before the barrier in its finish_trial
     for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_cnt[i] = 0u;
+    if (SPREAD) {
+      for (uint32_t i = tid; i < P.n_gpus; i += kBlock) s_gpu[i] = 0u;
+      if (tid == 0) s_base = 0u;
+    }
     __syncthreads();
     uint64_t z = state(P.seed, (P.first_trial + t) * (uint64_t)pool + tid);
     for (uint32_t i = tid; i < pool; i += kBlock, z += kBlock * kGamma)
       atomicAdd(&s_cnt[draw(s_dyn, s_guide, z, 0u, P.total)], 1u);
     __syncthreads();
-    // running sum over lengths: a thread owns a contiguous piece, pieces are combined by a doubling scan
+    // running sum over lengths: a thread owns a contiguous piece, the pieces' sums are combined across threads
     uint32_t piece = 0;
     for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
-    s_scan[tid] = piece;
-    __syncthreads();
-    for (uint32_t d = 1; d < kBlock; d <<= 1) {
-      const uint32_t add = tid >= d ? s_scan[tid - d] : 0u;
-      __syncthreads();
-      s_scan[tid] += add;
-      __syncthreads();
-    }
-    uint32_t run = s_scan[tid] - piece;  // draws with a length below this thread's piece
-    for (uint32_t i = a; i < b; ++i) {
-      run += s_cnt[i];
-      s_cnt[i] = run;  // draws of length <= i
-    }
-    __syncthreads();
+    uint32_t run = block_running_sum(s_scan, piece) - piece;  // draws with a length below this thread's piece
     uint32_t lo = 0xffffffffu, hi = 0u;
-    for (uint32_t c = tid; c < P.n_gpus; c += kBlock) {
-      uint32_t tokens = 0, l = 1;
-      for (uint32_t r = 0; r < P.local_batch; ++r) {  // sorted positions r * n_gpus + c grow with r, and so do their lengths
-        l = first_above(s_cnt, l, P.max_len, r * P.n_gpus + c);
-        tokens += l;
+    if (SPREAD) {
+      uint32_t whole_turns = 0;
+      for (uint32_t l = a; l < b; ++l) {  // entries of length l: positions run .. run + n - 1
+        const uint32_t n = s_cnt[l];
+        if (n != 0u) {
+          const uint32_t turns = n / P.n_gpus, rest = n - turns * P.n_gpus, first = run % P.n_gpus;
+          whole_turns += turns * l;
+          if (rest != 0u) {  // unsigned wrap-around is harmless: the sums that are read come out below 2^32
+            const uint32_t end = first + rest;
+            atomicAdd(&s_gpu[first], l);
+            if (end < P.n_gpus) atomicAdd(&s_gpu[end], 0u - l);
+            if (end > P.n_gpus) atomicAdd(&s_gpu[0], l), atomicAdd(&s_gpu[end - P.n_gpus], 0u - l);
+          }
+        }
+        run += n;
       }
-      lo = min(lo, tokens), hi = max(hi, tokens);
+      if (whole_turns != 0u) atomicAdd(&s_base, whole_turns);
+      __syncthreads();
+      uint32_t mine = 0;
+      for (uint32_t g = ga; g < gb; ++g) mine += s_gpu[g];
+      uint32_t tokens = block_running_sum(s_scan, mine) - mine + s_base;  // ... of the GPU before this thread's first
+      for (uint32_t g = ga; g < gb; ++g) {
+        tokens += s_gpu[g];
+        lo = min(lo, tokens), hi = max(hi, tokens);
+      }
+    } else {
+      for (uint32_t i = a; i < b; ++i) {
+        run += s_cnt[i];
+        s_cnt[i] = run;  // draws of length <= i
+      }
+      __syncthreads();
+      for (uint32_t c = tid; c < P.n_gpus; c += kBlock) {
+        uint32_t tokens = 0, l = 1;
+        for (uint32_t r = 0; r < P.local_batch; ++r) {  // sorted positions r * n_gpus + c grow with r, and so do their lengths
+          l = first_above(s_cnt, l, P.max_len, r * P.n_gpus + c);
+          tokens += l;
+        }
+        lo = min(lo, tokens), hi = max(hi, tokens);
+      }
     }
     finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
   }
@@ -538,7 +588,8 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   hipError_t e = hipGetLastError();
   // dynamic LDS in words: histogram, guide tables, then the sorted pools (local) or the trial's histogram (global)
   const uint32_t tables = ds->max_len + 1u + P.n_guide * kGuideSize;
-  const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u : 0u));
+  const bool spread = run->method == LBS_GLOBAL && run->n_gpus <= kMaxSpreadGpus;
+  const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u + (spread ? run->n_gpus : 0u) : 0u));
   if (e == hipSuccess && run->n_trials > 0) {
     // trials cost the same, so a few workgroups per resident slot balance; each loops over its share of the trials
     const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
@@ -554,7 +605,8 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
                         : (in_lanes ? k_lbs_local<16, true> : k_lbs_local<16, false>);
       hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     } else if (run->method == LBS_GLOBAL) {
-      hipLaunchKernelGGL(k_lbs_global, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
+      hipLaunchKernelGGL(spread ? k_lbs_global<true> : k_lbs_global<false>, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min,
+                         trial_max, ds_sums);
     } else {
       hipLaunchKernelGGL(k_lbs_keep, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     }

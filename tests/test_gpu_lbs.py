@@ -88,6 +88,18 @@ def test_max_len_1024_and_many_gpus():
         check(cum, (256, 512, 768, 1024), method, 16, 8, 4096, [2, 3, 5, 6], seed=9, n=6)
 
 
+def test_global_presorting_few_gpus_many_gpus_and_few_lengths():
+    # fewer GPUs than entries of one length (whole turns round all GPUs), the largest system that keeps a word per
+    # GPU in LDS and the first beyond it, and a dataset of two lengths
+    check(CUM, ENDS, lbs.LBS_GLOBAL, 64, 1, 3, None, seed=14, n=9)
+    check(CUM, ENDS, lbs.LBS_GLOBAL, 2, 1, 8192, None, seed=15, n=3)
+    check(CUM, ENDS, lbs.LBS_GLOBAL, 2, 1, 8193, None, seed=16, n=3)
+    cum = np.zeros(41, np.uint32)
+    cum[7:] = 5
+    cum[40] = 9                                             # five sequences of length 7, four of length 40
+    check(cum, (40,), lbs.LBS_GLOBAL, 16, 1, 50, None, seed=17, n=20)
+
+
 def test_runs_on_a_side_stream_and_trials_split_across_calls():
     quota = [6, 3, 2, 5]
     with lbs.Dataset(CUM, ENDS, device=0) as ds:
