@@ -198,13 +198,13 @@ __device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) 
 template <int LJ>
 __device__ __forceinline__ uint32_t from_partner(uint32_t x) {
   const int v = (int)x;
-  if (LJ == 0) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false);  // quad_perm [1,0,3,2]
-  if (LJ == 1) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false);  // quad_perm [2,3,0,1]
+  if (LJ == 0) return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
+  if (LJ == 1) return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
   if (LJ == 2) {
-    const int t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xf, 0x5, false);   // lanes 0-3, 8-11 of a row read lane + 4
+    const int t = __builtin_amdgcn_mov_dpp(v, 0x104, 0xf, 0x5, true);            // lanes 0-3, 8-11 of a row read lane + 4
     return (uint32_t)__builtin_amdgcn_update_dpp(t, v, 0x114, 0xf, 0xA, false);  // lanes 4-7, 12-15 read lane - 4
   }
-  if (LJ == 3) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  if (LJ == 3) return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x128, 0xf, 0xf, true);  // row_ror:8
   return (uint32_t)__shfl_xor(v, 1 << LJ, 64);
 }
 
