@@ -80,7 +80,8 @@ typedef struct lbs_run {
 /* Runs the trials.  trial_min / trial_max (DEVICE [n_trials], either may be NULL)
  * receive every trial's smallest / largest per-GPU token count; sums (DEVICE [2],
  * required) receives the totals of the two over the trials (the paper's averages are
- * sums[i] / n_trials).  One workgroup per trial. */
+ * sums[i] / n_trials).  A call is a small clearing kernel and one simulation kernel whose
+ * workgroups each run a share of the trials; it allocates nothing and keeps no state. */
 int lbs_simulate(const lbs_dataset* ds, const lbs_run* run /*HOST*/, uint32_t* trial_min /*DEVICE or NULL*/,
                  uint32_t* trial_max /*DEVICE or NULL*/, uint64_t* sums /*DEVICE [2]*/, void* stream);
 
