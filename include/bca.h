@@ -108,7 +108,9 @@ typedef struct bca_tuning {
                             each workgroup reserves without using them, which caps the workgroups resident
                             per compute unit (160 KiB each) -- the sweep streams fastest with few
                             wavefronts in flight.  0: default (48 KiB); 1: none; at most 65536       */
-  uint32_t reserved;     /* must be 0 */
+  uint32_t spin_limit;   /* fused calls: polls of a bucket's ready word after which a waiting work item gives
+                            up and BCA_STATUS_TIMEOUT is reported; 0: default (2^18, about a second).  Small
+                            values exist for tests of that path: every kernel still ends normally        */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */

@@ -50,7 +50,7 @@ class _Adam(C.Structure):
 class _Tuning(C.Structure):
     _fields_ = [("chunk_norm", C.c_uint32), ("chunk_apply", C.c_uint32), ("grid_norm", C.c_uint32),
                 ("grid_apply", C.c_uint32), ("unroll_apply", C.c_uint32), ("flags", C.c_uint32),
-                ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("reserved", C.c_uint32)]
+                ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("spin_limit", C.c_uint32)]
 
 
 @dataclass
@@ -159,7 +159,8 @@ class Plan:
     def __init__(self, tensor_numel: Sequence[int], bucket_seg_off: Sequence[int], seg_tensor: Sequence[int],
                  seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
                  chunk_norm: int = 0, chunk_apply: int = 0, grid_norm: int = 0, grid_apply: int = 0,
-                 unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0, adam_lds_reserve: int = 0):
+                 unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0, adam_lds_reserve: int = 0,
+                 spin_limit: int = 0):
         L = load_library()
         self._L = L
         self._h = C.c_void_p()
@@ -170,7 +171,7 @@ class Plan:
         for i in range(n_seg):
             segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
         tune = _Tuning(chunk_norm, chunk_apply, grid_norm, grid_apply, unroll_apply, tune_flags, group_bytes,
-                       adam_lds_reserve, 0)
+                       adam_lds_reserve, spin_limit)
         _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
                                  len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
                                  C.byref(tune)))

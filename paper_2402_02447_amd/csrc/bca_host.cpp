@@ -299,6 +299,7 @@ StepState step_state(const bca_plan* p) {
   ss.norm_bucket_off = p->norm_tab.d_bucket_off;
   ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
   ss.apply_to_lamb = p->d_apply_to_lamb, ss.lamb_sums = p->d_lamb_sums;
+  ss.spin_limit = p->spin_limit;
   return ss;
 }
 
@@ -405,8 +406,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
     }
     if (tuning->flags & ~(BCA_TUNE_MULTI_LAUNCH | BCA_TUNE_STAGE_TABLE_LDS | BCA_TUNE_TICKETS))
       return fail(BCA_ERR_RANGE, "unknown tuning flag bits");
-    if (tuning->adam_lds_reserve > 65536 || tuning->reserved != 0)
-      return fail(BCA_ERR_RANGE, "adam_lds_reserve must be at most 65536 and reserved 0");
+    if (tuning->adam_lds_reserve > 65536) return fail(BCA_ERR_RANGE, "adam_lds_reserve must be at most 65536");
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
@@ -429,6 +429,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
   p->tune_flags = tuning ? tuning->flags : 0;
   p->adam_lds_reserve = (tuning && tuning->adam_lds_reserve) ? (tuning->adam_lds_reserve == 1 ? 0 : tuning->adam_lds_reserve)
                                                               : kDefaultAdamLdsReserve;
+  p->spin_limit = (tuning && tuning->spin_limit) ? tuning->spin_limit : kDefaultSpinLimit;
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
   p->decay.assign(n_tensors, 1);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);

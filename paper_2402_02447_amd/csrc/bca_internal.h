@@ -73,6 +73,7 @@ constexpr uint64_t kDefaultGroupElems = 8ull << 20;
 // BERT-Large 1.614 -> 1.537 ms, BERT-Base 0.529 -> 0.511 ms).  48 KiB of the 160 KiB LDS per workgroup give that.
 // The fused single-launch step does not gain from it (its items wait on each other) and does not use it.
 constexpr uint32_t kDefaultAdamLdsReserve = 48u << 10;
+constexpr uint32_t kDefaultSpinLimit = 1u << 18;  // polls of a ready word before a waiting item gives up (about a second)
 
 // How a streaming kernel is launched.
 struct Launch {
@@ -99,6 +100,7 @@ struct StepState {
   uint32_t* ctl;                    // [kCtlWords] ticket counter, epoch
   const uint32_t* apply_to_lamb;    // LAMB: place of every apply-table chunk in the tensor-major table
   double* lamb_sums;                // LAMB: two sums per chunk, in tensor-major order
+  uint32_t spin_limit;              // polls of a ready word before a waiting item gives up
 };
 
 // Kernel launchers (bca_kernels.hip).  All enqueue on `stream` and return the
@@ -159,6 +161,7 @@ struct bca_plan {
   uint32_t grid_norm = 0, grid_apply = 0;  // 0: one workgroup per chunk
   uint32_t unroll_apply = 1;
   uint32_t adam_lds_reserve = 0;  // bytes; see bca_tuning::adam_lds_reserve
+  uint32_t spin_limit = 0;        // see bca_tuning::spin_limit (default already applied)
   uint32_t tune_flags = 0;
   bool bound = false;
   std::vector<uint64_t> tensor_numel;

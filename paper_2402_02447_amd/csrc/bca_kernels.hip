@@ -739,11 +739,9 @@ __global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict_
 //    workgroup only leaves its own list once it is used up, and then I was taken.
 //    So XCD y has a free slot or a running non-waiter, starts another workgroup,
 //    and list y advances to I.
-// The wait is bounded all the same: after kSpinLimit polls the item is skipped,
+// The wait is bounded all the same: after StepState::spin_limit polls the item is skipped,
 // an abort word makes every other waiter give up at its next look, and
 // BCA_STATUS_TIMEOUT is reported, so the grid always drains.
-
-constexpr uint32_t kSpinLimit = 1u << 18;  // polls of a ready word before an Adam item gives up (about a second)
 
 // Resets the per-call state: takes a new epoch, clears the ticket, the arrival
 // counters and the caller's status word (k_step only ORs into it).
@@ -776,7 +774,7 @@ __device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b,
     uint32_t polls = 0;
     for (;;) {
       r = __hip_atomic_load(&st.ready[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if ((uint32_t)(r >> 32) == epoch || ++polls > kSpinLimit) break;
+      if ((uint32_t)(r >> 32) == epoch || ++polls > st.spin_limit) break;
       // once one wait has expired every other waiter gives up at its next look
       if ((polls & 63u) == 0 && __hip_atomic_load(&st.ctl[kCtlAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
         break;

@@ -632,3 +632,28 @@ def test_hyper_parameter_extremes(hp, step):
         dev.sync()
         assert bits_equal(to_host(dev.p), p) and not bits_equal(to_host(dev.m), m)
         dev.close()
+
+
+# ------------------------------------------------------------------ the bounded wait of the fused calls
+
+
+def test_expired_wait_is_reported_every_kernel_ends_and_later_calls_are_unaffected():
+    """With a spin limit of one poll, the Adam items that start while their bucket's squared norm is still
+    being read give up at once: the call returns, the kernels end, the status word carries the time-out bit.
+    The same tensors then go through a plan with the default limit and match the oracle."""
+    numels = [3_000_000, 1_500_000]
+    lay = W.layout_flat_split(numels, 4_500_000)                     # one bucket: every Adam item waits for one norm
+    g = W.normal_tensors(numels, 41, "g", 1e-3, threads=1)
+    p, m, v = (W.normal_tensors(numels, 41, "p", 0.02, threads=1), W.normal_tensors(numels, 41, "m", 3e-3, threads=1),
+               W.warm_second_moment(numels, 41, threads=1))
+    hp = W.Hyper()
+    thr = np.asarray([0.5 * oracle.bucket_norms(lay, g)[0]], np.float32)
+    d = Device(lay, g, p, m, v, spin_limit=1)
+    d.plan.bucket_clip_adam(d.thresholds(thr), hyper(hp), 5, 0, d.norms, d.coefs, d.status)
+    d.sync()
+    assert int(d.status.item()) & B.BCA_STATUS_TIMEOUT
+    d.plan.bucket_clip(0, 1, d.thresholds(thr), d.norms, d.coefs, d.status)     # the clip-only call waits the same way
+    d.sync()
+    assert int(d.status.item()) & B.BCA_STATUS_TIMEOUT
+    d.close()
+    run_fused(lay, g, p, m, v, thr, hp, 5)
