@@ -82,6 +82,21 @@ def test_more_trials_than_workgroups_so_that_each_runs_several(method):
     check(CUM, ENDS, method, 4, 2 if method != lbs.LBS_LOCAL_SNAKE else 3, 12, [1, 1, 1, 1], seed=31, n=n, first=7)
 
 
+@pytest.mark.parametrize("method", [lbs.LBS_NONE, lbs.LBS_STRATIFIED, lbs.LBS_LOCAL_RASTER, lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL])
+def test_full_size_run_as_benchmarked_sampled_trials_and_sums(method):
+    """100 000 trials at 1 024 GPUs, the call bench.py times: sampled trials against the oracle run on that
+    trial alone, and the two sums against the per-trial outputs."""
+    quota = [int(q) for q in W.stratum_quota(CUM, ENDS, 16)]
+    n, G = 100_000, 1024
+    with lbs.Dataset(CUM, ENDS, device=torch.cuda.current_device()) as ds:
+        gmin, gmax, g0, g1 = run_gpu(ds, method, 16, 8, G, quota, 2024, n)
+    assert g0 == int(gmin.astype(np.uint64).sum()) and g1 == int(gmax.astype(np.uint64).sum())
+    rng = np.random.default_rng(77 + method)
+    for t in [0, 1, n - 1, 8191, 8192] + [int(x) for x in rng.integers(0, n, 25)]:
+        omin, omax, _, _ = O.simulate(CUM, ENDS, quota, 16, 8, G, method, 2024, 1, first_trial=t)
+        assert (int(gmin[t]), int(gmax[t])) == (int(omin[0]), int(omax[0])), (method, t)
+
+
 def test_max_len_1024_and_many_gpus():
     cum = W.length_histogram_piecewise_uniform(3_000_000, (256, 512, 768, 1024), (0.1, 0.2, 0.3, 0.4))
     for method in (lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL):
