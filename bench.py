@@ -179,12 +179,12 @@ def lbs_bench(a, dev):
         cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
     # dominant kernel: k_lbs_local (two of the five methods).  Vector instructions it executes, from a rocprofv3
-    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 2.746e9 wavefront
-    # instructions per 100 000 trials at 1 024 GPUs = 107 lane-operation slots per draw (64 lanes per instruction).
+    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 2.721e9 wavefront
+    # instructions per 100 000 trials at 1 024 GPUs = 106 lane-operation slots per draw (64 lanes per instruction).
     # Peak: a SIMD issues a 64-lane move, add or xor in 2 cycles and a multiply, minimum or median in 4 (measured);
     # the bound taken is every instruction at the faster rate, 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T
     # lane-operations/s, which is also the rate behind the chip's 157.3 TFLOP/s of fp32 vector FMAs.
-    ops_per_draw = 107
+    ops_per_draw = 106
     t_local = (per_method[lbs.LBS_LOCAL_RASTER] + per_method[lbs.LBS_LOCAL_SNAKE]) / 2 * 1e-3
     achieved = ops_per_draw * n * G * b / t_local / 1e12
     peak = 256 * 4 * 32 * 2.4e9 / 1e12

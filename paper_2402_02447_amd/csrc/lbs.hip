@@ -9,8 +9,8 @@
 // inverse of the cumulative histogram at the index it selects.  The histogram sits in
 // LDS, and so does a guide table made when the dataset is created: for every range
 // the draws can come from (the whole dataset, each stratum) and every value of the
-// draw's upper 9 bits, the smallest and the largest length that such a draw can
-// select.  The search for the length then runs over that interval only (mostly one
+// draw's upper 11 (whole dataset) or 9 (stratum) bits, the smallest and the largest
+// length that such a draw can select.  The search for the length then runs over that interval only (mostly one
 // or two candidates instead of ten halvings of [1, max_len]).
 //   NONE / STRATIFIED : a thread owns whole GPUs; local_batch draws, one sum each.
 //   LOCAL_*           : a wavefront owns a node.  Its lanes draw the node's pool into
@@ -43,6 +43,8 @@
 #include "lbs.h"
 
 namespace lbs {
+// guide tables: indexed by a draw's upper 11 bits for the whole dataset, by its upper 9 bits for a stratum
+constexpr uint32_t kWholeGuideBits = 11, kWholeGuideSize = 1u << kWholeGuideBits;
 constexpr uint32_t kGuideBits = 9, kGuideSize = 1u << kGuideBits;
 }
 
@@ -52,7 +54,7 @@ struct lbs_dataset {
   std::vector<uint32_t> cum, stratum_end;
   uint32_t* d_cum = nullptr;
   uint32_t n_cus = 1;           // compute units of the device
-  uint32_t* d_guide = nullptr;  // (1 + n_strata) tables of kGuideSize entries: the whole dataset, then each stratum
+  uint32_t* d_guide = nullptr;  // the whole dataset's table (kWholeGuideSize entries), then one of kGuideSize per stratum
 };
 
 namespace lbs {
@@ -71,7 +73,8 @@ int fail(int code, const std::string& msg) {
 struct Params {  // by-value kernel argument
   uint32_t max_len, local_batch, gpus_per_node, n_gpus, snake, stratified;
   uint32_t total;                             // dataset size
-  uint32_t n_guide;                           // guide tables the kernel loads (1: whole dataset; else one per stratum)
+  uint32_t guide_words;                       // guide entries the kernel loads (the whole dataset's table, or all strata's)
+  uint32_t guide_shift;                       // a draw's upper 32 - guide_shift bits index its table
   uint32_t slot_lo[LBS_MAX_LOCAL_BATCH];      // a GPU's j-th draw: dataset entries before its range (0 / its stratum),
   uint32_t slot_size[LBS_MAX_LOCAL_BATCH];    //   entries in that range,
   uint32_t slot_guide[LBS_MAX_LOCAL_BATCH];   //   and where that range's guide table starts in LDS
@@ -101,11 +104,11 @@ __device__ __forceinline__ uint32_t first_above(const uint32_t* counts, uint32_t
 
 // Length selected by the draw with generator state z out of the `size` dataset entries that follow the
 // first `before` ones; `guide` is that range's table.
-__device__ __forceinline__ uint32_t draw(const uint32_t* s_cum, const uint32_t* guide, uint64_t z, uint32_t before,
-                                         uint32_t size) {
+__device__ __forceinline__ uint32_t draw(const uint32_t* s_cum, const uint32_t* guide, uint32_t guide_shift, uint64_t z,
+                                         uint32_t before, uint32_t size) {
   const uint32_t u = (uint32_t)(mix(z) >> 32);
   const uint32_t index = before + __umulhi(u, size);
-  const uint32_t span = guide[u >> (32u - kGuideBits)];  // lengths a draw with these upper bits can select
+  const uint32_t span = guide[u >> guide_shift];  // lengths a draw with these upper bits can select
   return first_above(s_cum, span & 0xffffu, span >> 16, index);
 }
 
@@ -114,8 +117,8 @@ __device__ __forceinline__ uint32_t* load_tables(uint32_t* s_dyn, const Params& 
                                                  const uint32_t* __restrict__ guide) {
   uint32_t* s_guide = s_dyn + P.max_len + 1u;
   for (uint32_t i = threadIdx.x; i <= P.max_len; i += kBlock) s_dyn[i] = cum[i];
-  const uint32_t* src = guide + (P.stratified ? kGuideSize : 0u);  // table 0 is the whole dataset's
-  for (uint32_t i = threadIdx.x; i < P.n_guide * kGuideSize; i += kBlock) s_guide[i] = src[i];
+  const uint32_t* src = guide + (P.stratified ? kWholeGuideSize : 0u);  // the whole dataset's table comes first
+  for (uint32_t i = threadIdx.x; i < P.guide_words; i += kBlock) s_guide[i] = src[i];
   __syncthreads();
   return s_guide;
 }
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_keep(const Params P, const uint3
       uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
       uint32_t tokens = 0;
       for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
-        tokens += draw(s_dyn, s_guide + P.slot_guide[j], z, P.slot_lo[j], P.slot_size[j]);
+        tokens += draw(s_dyn, s_guide + P.slot_guide[j], P.guide_shift, z, P.slot_lo[j], P.slot_size[j]);
       lo = min(lo, tokens), hi = max(hi, tokens);
     }
     finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   const uint32_t n_nodes = P.n_gpus / P.gpus_per_node;
   const uint32_t pool = P.gpus_per_node * P.local_batch;
-  uint32_t* sorted = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize + wave * pool;
+  uint32_t* sorted = s_dyn + P.max_len + 1u + P.guide_words + wave * pool;
   // pool entry i = e * 64 + lane is draw i % local_batch of GPU i / local_batch of the node, for every node alike
   uint32_t before[E], size[E], goff[E];
 #pragma unroll
@@ -296,7 +299,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const uint32_t i = (uint32_t)e * 64u + lane;
-          v[e] = i < pool ? draw(s_dyn, s_guide + goff[e], z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
+          v[e] = i < pool ? draw(s_dyn, s_guide + goff[e], P.guide_shift, z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
         }
         bitonic_sort<E>(v, bit);
         if (IN_LANES) {
@@ -366,7 +369,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
   __shared__ uint32_t s_base;
   __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
-  uint32_t* s_cnt = s_dyn + P.max_len + 1u + P.n_guide * kGuideSize;  // first counts of the trial's draws, then their running sum
+  uint32_t* s_cnt = s_dyn + P.max_len + 1u + P.guide_words;  // first counts of the trial's draws, then their running sum
   uint32_t* s_gpu = s_cnt + P.max_len + 1u;                           // SPREAD: difference array over the GPUs
   const uint32_t tid = threadIdx.x;
   const uint32_t pool = P.n_gpus * P.local_batch;
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
     __syncthreads();
     uint64_t z = state(P.seed, (P.first_trial + t) * (uint64_t)pool + tid);
     for (uint32_t i = tid; i < pool; i += kBlock, z += kBlock * kGamma)
-      atomicAdd(&s_cnt[draw(s_dyn, s_guide, z, 0u, P.total)], 1u);
+      atomicAdd(&s_cnt[draw(s_dyn, s_guide, P.guide_shift, z, 0u, P.total)], 1u);
     __syncthreads();
     // running sum over lengths: a thread owns a contiguous piece, the pieces' sums are combined across threads
     uint32_t piece = 0;
@@ -442,12 +445,12 @@ uint32_t length_of(const std::vector<uint32_t>& cum, uint32_t index) {
   return (uint32_t)(std::upper_bound(cum.begin() + 1, cum.end(), index) - cum.begin());
 }
 
-// Guide table of the `size` entries after the first `before`: for every value of a draw's upper kGuideBits
+// Guide table of the `size` entries after the first `before`: for every value of a draw's upper `bits`
 // bits, the smallest (low half) and the largest (high half) length that such a draw selects.  The index a
 // draw selects grows with the draw, and the length with the index, so the two ends bound everything between.
-void fill_guide(uint32_t* out, const std::vector<uint32_t>& cum, uint32_t before, uint32_t size) {
-  for (uint32_t ub = 0; ub < kGuideSize; ++ub) {
-    const uint64_t u_min = (uint64_t)ub << (32u - kGuideBits), u_max = u_min + (1ull << (32u - kGuideBits)) - 1u;
+void fill_guide(uint32_t* out, uint32_t bits, const std::vector<uint32_t>& cum, uint32_t before, uint32_t size) {
+  for (uint32_t ub = 0; ub < (1u << bits); ++ub) {
+    const uint64_t u_min = (uint64_t)ub << (32u - bits), u_max = u_min + (1ull << (32u - bits)) - 1u;
     if (size == 0) {
       out[ub] = 1u | (1u << 16);  // never drawn from
       continue;
@@ -491,11 +494,11 @@ static int dataset_create(lbs_dataset** out, int device, uint32_t max_len, const
   ds->cum.assign(cum, cum + max_len + 1);
   ds->stratum_end.assign(stratum_end, stratum_end + n_strata);
   if (device >= 0) {
-    std::vector<uint32_t> guide((size_t)(1 + n_strata) * kGuideSize);
-    fill_guide(guide.data(), ds->cum, 0, cum[max_len]);
+    std::vector<uint32_t> guide(kWholeGuideSize + (size_t)n_strata * kGuideSize);
+    fill_guide(guide.data(), kWholeGuideBits, ds->cum, 0, cum[max_len]);
     for (uint32_t s = 0; s < n_strata; ++s) {
       const uint32_t before = cum[s == 0 ? 0 : stratum_end[s - 1]];
-      fill_guide(guide.data() + (size_t)(1 + s) * kGuideSize, ds->cum, before, cum[stratum_end[s]] - before);
+      fill_guide(guide.data() + kWholeGuideSize + (size_t)s * kGuideSize, kGuideBits, ds->cum, before, cum[stratum_end[s]] - before);
     }
     int prev = -1;
     (void)hipGetDevice(&prev);
@@ -558,7 +561,8 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   P.max_len = ds->max_len, P.local_batch = run->local_batch, P.gpus_per_node = run->gpus_per_node;
   P.n_gpus = run->n_gpus, P.snake = run->method == LBS_LOCAL_SNAKE, P.stratified = stratified;
   P.total = ds->cum[ds->max_len], P.seed = run->seed;
-  P.n_guide = stratified ? ds->n_strata : 1u;
+  P.guide_words = stratified ? ds->n_strata * kGuideSize : kWholeGuideSize;
+  P.guide_shift = 32u - (stratified ? kGuideBits : kWholeGuideBits);
   if (stratified) {
     uint32_t j = 0;
     for (uint32_t s = 0; s < ds->n_strata; ++s) {
@@ -587,7 +591,7 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   hipLaunchKernelGGL(k_lbs_clear, dim3(1), dim3(64), 0, s, ds_sums);
   hipError_t e = hipGetLastError();
   // dynamic LDS in words: histogram, guide tables, then the sorted pools (local) or the trial's histogram (global)
-  const uint32_t tables = ds->max_len + 1u + P.n_guide * kGuideSize;
+  const uint32_t tables = ds->max_len + 1u + P.guide_words;
   const bool spread = run->method == LBS_GLOBAL && run->n_gpus <= kMaxSpreadGpus;
   const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u + (spread ? run->n_gpus : 0u) : 0u));
   if (e == hipSuccess && run->n_trials > 0) {
