@@ -37,9 +37,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="benchmark configuration: 2 BERT-Base 25 MiB, 3 BERT-Large 50 MiB, 4 fp16 1 MiB, 5 4 MiB")
-    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms", "lbs"],
+    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms", "whole_clip_adam", "per_bucket", "lbs"],
                     help="what one step is: the fused bucket_clip_adam (headline, default), adam_step alone, "
-                         "bucket_clip_lamb, lamb_step, bucket_clip_norms alone, or (lbs) the load-balancing "
+                         "bucket_clip_lamb, lamb_step, bucket_clip_norms alone, whole-gradient clipping + Adam, the paper's "
+                         "order (bucket_clip bucket by bucket, then adam_step), or (lbs) the load-balancing "
                          "simulation: one step = --lbs-trials trials of each of the five methods")
     ap.add_argument("--lbs-trials", type=int, default=100000)
     ap.add_argument("--lbs-gpus", type=int, default=1024)
@@ -78,6 +79,27 @@ def other_ops(a, w, plan, g, p, m, v, dev):
     status = torch.zeros(1, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
     step = [w.first_step]
+    thr_whole = torch.ones(1, dtype=torch.float32, device=dev)
+    norms_whole = torch.zeros(lay.n_buckets + 1, dtype=torch.float32, device=dev)
+
+    # per_bucket scales g in place, so a fixed threshold would clip once and never again: the thresholds start at
+    # 0.9 x the smallest bucket norm and shrink by 0.9 per step (precomputed, one row per step), so that every
+    # bucket clips in every step and the bytes moved stay the same
+    n_calls = [0]
+    thr_rows = None
+    if a.op == "per_bucket":
+        plan.bucket_clip_norms(0, lay.n_buckets, norms, stream)
+        base = 0.9 * float(norms.min().item())
+        rows = a.warmup + 2 * a.steps
+        thr_rows = base * (0.9 ** torch.arange(rows, dtype=torch.float64, device=dev)).to(torch.float32)[:, None].repeat(
+            1, lay.n_buckets).contiguous()
+
+    def per_bucket():
+        t = thr_rows[n_calls[0]]
+        n_calls[0] += 1
+        for b in range(lay.n_buckets):
+            plan.bucket_clip(b, b + 1, t, norms, coefs, status, stream)
+        plan.adam_step(hp, step[0], stream)
     # algorithmic bytes per element: every sweep's reads and writes, nothing assumed cached
     ops = {
         "adam": (lambda: plan.adam_step(hp, step[0], stream), 24 + gb,
@@ -88,6 +110,15 @@ def other_ops(a, w, plan, g, p, m, v, dev):
                  "lamb_step: k_lamb_moments (g p m v read, m v written), k_lamb_trust, k_lamb_update (p m v read, p written)"),
         "clip_lamb": (lambda: plan.bucket_clip_lamb(thr, hp, step[0], 0, norms, coefs, trust, status, stream),
                       gb + (gb + 12 + 8) + (12 + 4), "bucket_clip_lamb: k_sqnorm + k_finalize, then the three LAMB kernels"),
+        # the paper's two baselines (Sec. 3.2): one coefficient from the whole gradient's norm, so every norm
+        # comes before any update and g crosses HBM twice
+        "whole_clip_adam": (lambda: plan.bucket_clip_adam(thr_whole, hp, step[0], B.BCA_CLIP_WHOLE_GRADIENT, norms_whole,
+                                                           coefs, status, stream),
+                            gb + 24 + gb, "bucket_clip_adam, whole-gradient clipping: k_sqnorm, k_finalize, k_whole_coef, k_adam"),
+        # Alg. 1 in the paper's order, without the all-reduce: every bucket clipped by a call of its own (norm, then
+        # scale in place: every bucket of this workload clips), then Adam on the stored gradients
+        "per_bucket": (per_bucket, gb + 2 * gb + 24 + gb,
+                       "bucket_clip per bucket (k_prepare_range + k_clip each), then adam_step (k_adam)"),
     }
     fn, per_elt, what = ops[a.op]
 
@@ -123,7 +154,7 @@ def other_ops(a, w, plan, g, p, m, v, dev):
                      "bytes_per_elt": per_elt,
                      "ms_per_launch": round(med, 4)},
         "cpu_baseline": None, "ms_per_step_median": round(med, 4), "ms_per_step_min": round(per[0], 4),
-        "status": int(status.item()),
+        "status": int(status.item()), "buckets_clipped_last_step": int((coefs < 1).sum().item()),
     }))
 
 
