@@ -15,6 +15,25 @@ import workloads as W
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def test_binding_constants_equal_the_headers():
+    """Every #define of include/bca.h and include/lbs.h that the bindings mirror has the same value there."""
+    import ctypes as C
+    from paper_2402_02447_amd import binding, lbs
+    for header, module in (("bca.h", binding), ("lbs.h", lbs)):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        defines = dict(re.findall(r"#define\s+((?:BCA|LBS)_[A-Z0-9_]+)\s+\(?(-?\d+)u?\)?", text))
+        mirrored = [k for k in defines if hasattr(module, k)]
+        assert len(mirrored) >= 9, (header, mirrored)
+        for k in mirrored:
+            assert getattr(module, k) == int(defines[k]), (header, k)
+        # error codes are mirrored as a code -> name table
+        table = binding._ERR_NAMES if module is binding else lbs._ERR
+        errs = {int(v): k for k, v in defines.items() if "_ERR_" in k}
+        assert errs == table, (header, errs, table)
+    # struct layouts the C side and ctypes must agree on (C99 layout rules: natural alignment)
+    assert C.sizeof(binding._Segment) == 24 and C.sizeof(binding._Tuning) == 40 and C.sizeof(lbs._Run) == 72
+
+
 def test_library_loads_and_exports_every_declared_symbol():
     L = B.load_library()
     header = open(os.path.join(ROOT, "include", "bca.h")).read()
