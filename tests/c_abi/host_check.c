@@ -35,6 +35,8 @@ int main(void) {
   memset(&tune, 0, sizeof tune);
   tune.chunk_norm = 1024, tune.chunk_apply = 1024;
 
+  printf("sizeof bca_segment %u bca_tuning %u bca_adam %u lbs_run %u\n", (unsigned)sizeof(bca_segment), (unsigned)sizeof(bca_tuning),
+         (unsigned)sizeof(bca_adam), (unsigned)sizeof(lbs_run));
   CHECK(bca_version() >= 1);
   CHECK(bca_plan_create(&plan, -1, 2, numel, 2, seg_off, segs, BCA_GRAD_BF16, &tune) == BCA_OK);
   CHECK(bca_plan_num_buckets(plan) == 2);

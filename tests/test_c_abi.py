@@ -27,6 +27,13 @@ def test_c99_program_builds_against_the_headers_and_runs(tmp_path):
         pass
     r = subprocess.run([exe], capture_output=True, text=True, env=env)
     assert r.returncode == 0 and "c abi ok" in r.stdout, r.stdout + r.stderr
+    # the ctypes mirrors of the structs have the sizes the C compiler gives them
+    import ctypes as C
+    import re
+    from paper_2402_02447_amd import binding, lbs
+    sizes = dict(re.findall(r"(\w+) (\d+)", r.stdout.split("sizeof", 1)[1].splitlines()[0]))
+    assert int(sizes["bca_segment"]) == C.sizeof(binding._Segment) and int(sizes["bca_tuning"]) == C.sizeof(binding._Tuning)
+    assert int(sizes["bca_adam"]) == C.sizeof(binding._Adam) and int(sizes["lbs_run"]) == C.sizeof(lbs._Run)
 
 
 def _torch_lib_env():
