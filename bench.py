@@ -176,10 +176,10 @@ def lbs_bench(a, dev):
     ds = lbs.Dataset(cum, ends, device=0)
     stream = torch.cuda.current_stream()
     sums = {m: torch.zeros(2, dtype=torch.int64, device=dev) for m in names}
+    sums_all = torch.zeros((5, 2), dtype=torch.int64, device=dev)
 
-    def one_step():
-        for m in names:
-            ds.lbs_simulate(m, b, P, G, quota, 2024, n, sums[m], stream=stream)
+    def one_step():     # the five methods of Table 5 on shared draws: one lbs_simulate_all call, one kernel
+        ds.lbs_simulate_all(b, P, G, quota, 2024, n, sums_all, stream=stream)
     for _ in range(a.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -196,8 +196,9 @@ def lbs_bench(a, dev):
         e1.record(stream)
         torch.cuda.synchronize()
         per_method[m] = e0.elapsed_time(e1)
+    assert all(int(sums[m][0]) == int(sums_all[m][0]) and int(sums[m][1]) == int(sums_all[m][1]) for m in names)
     table = {names[m]: {"avg_min": round(int(sums[m][0]) / n, 1), "avg_max": round(int(sums[m][1]) / n, 1),
-                        "ms": round(per_method[m], 3)} for m in names}
+                        "ms_alone": round(per_method[m], 3)} for m in names}
     draws = 5 * n * G * b
     cpu = None
     if not a.no_cpu_baseline:
@@ -209,27 +210,37 @@ def lbs_bench(a, dev):
         dt = time.perf_counter() - t1
         cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
-    # dominant kernel: k_lbs_local (two of the five methods).  Vector instructions it executes, from a rocprofv3
-    # --pmc SQ_INSTS_VALU run of this command (profiles/lbs_table5_setting_kernel_stats.txt): 2.721e9 wavefront
-    # instructions per 100 000 trials at 1 024 GPUs = 106 lane-operation slots per draw (64 lanes per instruction).
-    # Peak: a SIMD issues a 64-lane move, add or xor in 2 cycles and a multiply, minimum or median in 4 (measured);
-    # the bound taken is every instruction at the faster rate, 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T
-    # lane-operations/s, which is also the rate behind the chip's 157.3 TFLOP/s of fp32 vector FMAs.
-    ops_per_draw = 106
-    t_local = (per_method[lbs.LBS_LOCAL_RASTER] + per_method[lbs.LBS_LOCAL_SNAKE]) / 2 * 1e-3
-    achieved = ops_per_draw * n * G * b / t_local / 1e12
+    # The step is one kernel, k_lbs_all.  Vector instructions it executes, from a rocprofv3 --pmc SQ_INSTS_VALU run of
+    # this command (profiles/lbs_table5_setting_kernel_stats.txt): 4.131e9 wavefront instructions per 100 000 trials at
+    # 1 024 GPUs, i.e. 2 x 1.638e9 draws made (one set from the whole dataset, one stratified) = 80.7 lane-operation
+    # slots per draw made (64 lanes per instruction).  Peak: a SIMD issues a 64-lane move, add or xor in 2 cycles and
+    # a multiply, minimum or median in 4 (measured); the bound taken is every instruction at the faster rate,
+    # 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-operations/s, which is also the rate behind the chip's
+    # 157.3 TFLOP/s of fp32 vector FMAs.
+    ops_per_draw_made = 80.7
+    draws_made = 2 * n * G * b
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(a.steps):
+        one_step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t_all = e0.elapsed_time(e1) / a.steps * 1e-3
+    achieved = ops_per_draw_made * draws_made / t_all / 1e12
     peak = 256 * 4 * 32 * 2.4e9 / 1e12
     print(json.dumps({
-        "metric": "load-balancing simulation throughput (sequence draws simulated per second, five methods)",
+        "metric": "load-balancing simulation throughput (sequence draws simulated per second over the five methods, "
+                  "which share two sets of draws)",
         "value": round(draws / (ms * 1e-3) / 1e9, 3), "unit": "G draws/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32/u64",
         "data": "synthetic",
         "config": {"workload": f"Table 5 setting: {G} simulated GPUs, local batch {b}, nodes of {P}, {n} trials per method, "
                                f"piecewise-uniform length histogram with the printed stratum shares, quota {quota}"},
-        "roofline": {"bound": "alu", "kernel": "k_lbs_local (draws, bitonic sort of each node's pool in registers, raster / snake deal)",
+        "roofline": {"bound": "alu", "kernel": "k_lbs_all (both sets of draws, counting sort over all GPUs, bitonic sort of each "
+                                               "node's pool in registers, the five methods' deals)",
                      "achieved": round(achieved, 2), "peak": round(peak, 1), "unit": "T lane-ops/s",
-                     "frac": round(achieved / peak, 3), "traffic": None, "ops_per_draw": ops_per_draw,
-                     "ms_per_launch": round(t_local * 1e3, 3)},
+                     "frac": round(achieved / peak, 3), "traffic": None, "ops_per_draw_made": ops_per_draw_made,
+                     "draws_made_per_step": draws_made, "ms_per_launch": round(t_all * 1e3, 3)},
         "cpu_baseline": cpu, "table": table,
     }))
     ds.close()

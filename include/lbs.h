@@ -85,6 +85,15 @@ typedef struct lbs_run {
 int lbs_simulate(const lbs_dataset* ds, const lbs_run* run /*HOST*/, uint32_t* trial_min /*DEVICE or NULL*/,
                  uint32_t* trial_max /*DEVICE or NULL*/, uint64_t* sums /*DEVICE [2]*/, void* stream);
 
+/* All five methods of one run in method order (run->method is ignored): exactly what five lbs_simulate calls
+ * that differ in `method` only compute, since draw number k of a run does not depend on the method -- LBS_NONE
+ * and LBS_GLOBAL see the same draws from the whole dataset, LBS_STRATIFIED and the two LOCAL methods the same
+ * stratified draws.  When gpus_per_node and local_batch are powers of two (at most 32 and 64) and n_gpus is at
+ * most 8192, one kernel makes each set of draws once; otherwise the five methods run one after the other.
+ * trial_min / trial_max: DEVICE [5][n_trials] or NULL; sums: DEVICE [5][2]. */
+int lbs_simulate_all(const lbs_dataset* ds, const lbs_run* run /*HOST*/, uint32_t* trial_min /*DEVICE or NULL*/,
+                     uint32_t* trial_max /*DEVICE or NULL*/, uint64_t* sums /*DEVICE [5][2]*/, void* stream);
+
 const char* lbs_last_error(void);
 
 #ifdef __cplusplus

@@ -222,6 +222,36 @@ __device__ __forceinline__ uint32_t partner_of(uint32_t x, int lj) {  // lj is a
   }
 }
 
+// Sum of x over the lanes that differ from this one only in lane bits lo_bit .. hi_bit - 1 (the same two numbers
+// for the whole workgroup): a butterfly, highest bit first, whose steps inside a row of 16 lanes are DPP moves.
+// Written as a switch that is entered at the first step and left after the last, so that only the steps
+// asked for are executed.
+__device__ __forceinline__ uint32_t butterfly_sum(uint32_t x, uint32_t lo_bit, uint32_t hi_bit) {
+  if (hi_bit <= lo_bit) return x;
+  switch (hi_bit) {
+    default: x += from_partner<5>(x); if (lo_bit == 5u) break; [[fallthrough]];
+    case 5: x += from_partner<4>(x); if (lo_bit == 4u) break; [[fallthrough]];
+    case 4: x += from_partner<3>(x); if (lo_bit == 3u) break; [[fallthrough]];
+    case 3: x += from_partner<2>(x); if (lo_bit == 2u) break; [[fallthrough]];
+    case 2: x += from_partner<1>(x); if (lo_bit == 1u) break; [[fallthrough]];
+    case 1: x += from_partner<0>(x);
+  }
+  return x;
+}
+
+// The value of the lane whose position inside its group of n lanes (n a power of two up to 32) is mirrored.
+__device__ __forceinline__ uint32_t from_mirror(uint32_t x, uint32_t n) {
+  const int v = (int)x;
+  switch (n) {
+    case 1: return x;
+    case 2: return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+    case 4: return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x1B, 0xf, 0xf, true);   // quad_perm [3,2,1,0]
+    case 8: return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    case 16: return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x140, 0xf, 0xf, true); // row_mirror
+    default: return (uint32_t)__shfl_xor(v, (int)(n - 1u), 64);
+  }
+}
+
 // Sorts the 64 * E values held by a wavefront (value i in v[i / 64] of lane i % 64) into ascending order of i.
 // bit[b] is all ones in lanes whose bit b is set and 0 elsewhere (b < 6).
 template <int E>
@@ -284,6 +314,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
 #pragma unroll
   for (int b = 0; b < 6; ++b) bit[b] = 0u - ((lane >> b) & 1u);
   const bool odd_row = ((lane / P.gpus_per_node) & 1u) != 0u;  // IN_LANES only
+  const uint32_t gpn_bit = (uint32_t)__ffs((int)P.gpus_per_node) - 1u;  // IN_LANES: gpus_per_node = 2^gpn_bit
   unsigned long long sum_lo = 0, sum_hi = 0;
   for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
     const uint64_t k_trial = (P.first_trial + t) * P.n_gpus * (uint64_t)P.local_batch;
@@ -307,10 +338,10 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
 #pragma unroll
           for (int e = 0; e < E; ++e) tokens += (uint32_t)e * 64u + lane < pool ? v[e] : 0u;  // the padding sorts to the end
           if (P.snake) {  // an odd row is dealt right to left: its column c goes to GPU gpus_per_node - 1 - c
-            const uint32_t mirrored = (uint32_t)__shfl_xor((int)tokens, (int)(P.gpus_per_node - 1u), 64);
+            const uint32_t mirrored = from_mirror(tokens, P.gpus_per_node);
             tokens = odd_row ? mirrored : tokens;
           }
-          for (uint32_t m = P.gpus_per_node; m < 64u; m <<= 1) tokens += (uint32_t)__shfl_xor((int)tokens, (int)m, 64);
+          tokens = butterfly_sum(tokens, gpn_bit, 6u);
           lo = min(lo, tokens), hi = max(hi, tokens);  // every lane now holds the total of GPU lane % gpus_per_node
         } else {
 #pragma unroll
@@ -339,18 +370,22 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
   publish_sums(sums, sum_lo, sum_hi);
 }
 
-// Inclusive running sum over the workgroup of one value per thread (s_scan: kBlock words); all threads call it.
+// Inclusive running sum over the workgroup of one value per thread (s_scan: kWaves words); all
+// threads call it.  Within a wavefront by shuffles, across the four wavefronts through LDS: two barriers.
 __device__ __forceinline__ uint32_t block_running_sum(uint32_t* s_scan, uint32_t value) {
-  const uint32_t tid = threadIdx.x;
-  s_scan[tid] = value;
-  __syncthreads();
-  for (uint32_t d = 1; d < kBlock; d <<= 1) {
-    const uint32_t add = tid >= d ? s_scan[tid - d] : 0u;
-    __syncthreads();
-    s_scan[tid] += add;
-    __syncthreads();
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  uint32_t x = value;
+#pragma unroll
+  for (uint32_t off = 1; off < 64u; off <<= 1) {
+    const uint32_t below = (uint32_t)__shfl_up((int)x, off, 64);
+    if (lane >= off) x += below;
   }
-  return s_scan[tid];
+  if (lane == 63u) s_scan[wave] = x;
+  __syncthreads();
+  uint32_t before = 0;
+  for (uint32_t w = 0; w < wave; ++w) before += s_scan[w];
+  __syncthreads();  // s_scan may be written again right after
+  return x + before;
 }
 
 // GLOBAL: pool, sort and deal over all GPUs.  The pool is sorted by counting (lengths are small integers):
@@ -365,7 +400,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
                                                         const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                         uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram, (SPREAD) one word per GPU
-  __shared__ uint32_t s_scan[kBlock];
+  __shared__ uint32_t s_scan[kWaves];
   __shared__ uint32_t s_base;
   __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
@@ -438,6 +473,168 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
     finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
   }
   publish_sums(sums, sum_lo, sum_hi);
+}
+
+// ---- all five methods on one set of draws ----------------------------------------
+// NONE and GLOBAL use the same draws from the whole dataset, STRATIFIED and the two LOCAL methods the same
+// stratified draws (draw number k of a run does not depend on the method), so one pass makes each set once:
+// first a thread per GPU draws from the whole dataset, sums its GPU's tokens (NONE) and counts the lengths
+// for the counting sort (GLOBAL, as in k_lbs_global<true>); then a wavefront per node draws the stratified
+// pool into registers, adds up each GPU's own draws (STRATIFIED: local_batch consecutive pool entries, a
+// butterfly over the low lane bits), sorts and deals twice (LOCAL_RASTER, LOCAL_SNAKE, as in
+// k_lbs_local<E, true>).  Needs gpus_per_node and local_batch to be powers of two (<= 32 and <= 64).
+constexpr uint32_t kMethods = 5;
+struct FinishAll {
+  uint32_t lo[2][kMethods][kWaves], hi[2][kMethods][kWaves];
+};
+
+template <int E>
+__global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32_t* __restrict__ cum,
+                                                     const uint32_t* __restrict__ guide, uint32_t* trial_min,
+                                                     uint32_t* trial_max, unsigned long long* sums) {
+  extern __shared__ uint32_t s_dyn[];  // histogram, all guide tables, the trial's own histogram, one word per GPU
+  __shared__ uint32_t s_scan[kWaves];
+  __shared__ uint32_t s_base;
+  __shared__ FinishAll s_fin;
+  const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
+  uint32_t* s_whole = s_dyn + P.max_len + 1u;          // guide table of the whole dataset
+  uint32_t* s_strata = s_whole + kWholeGuideSize;      // guide tables of the strata
+  uint32_t* s_cnt = s_whole + P.guide_words;
+  uint32_t* s_gpu = s_cnt + P.max_len + 1u;
+  for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_dyn[i] = cum[i];
+  for (uint32_t i = tid; i < P.guide_words; i += kBlock) s_whole[i] = guide[i];
+  __syncthreads();
+
+  const uint32_t pool_all = P.n_gpus * P.local_batch;
+  const uint32_t per = (P.max_len + 1u + kBlock - 1u) / kBlock;
+  const uint32_t a = tid * per, b = min(a + per, P.max_len + 1u);
+  const uint32_t per_gpu = (P.n_gpus + kBlock - 1u) / kBlock;
+  const uint32_t ga = min(tid * per_gpu, P.n_gpus), gb = min(ga + per_gpu, P.n_gpus);
+  const uint32_t n_nodes = P.n_gpus / P.gpus_per_node;
+  const uint32_t pool = P.gpus_per_node * P.local_batch;
+  uint32_t before[E], size[E], goff[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const uint32_t i = (uint32_t)e * 64u + lane, j = i % P.local_batch;
+    const bool real = i < pool;
+    before[e] = real ? P.slot_lo[j] : 0u, size[e] = real ? P.slot_size[j] : 0u, goff[e] = real ? P.slot_guide[j] : 0u;
+  }
+  uint32_t bit[6];
+#pragma unroll
+  for (int q = 0; q < 6; ++q) bit[q] = 0u - ((lane >> q) & 1u);
+  const bool odd_row = ((lane / P.gpus_per_node) & 1u) != 0u;
+  const uint32_t gpn_bit = (uint32_t)__ffs((int)P.gpus_per_node) - 1u, batch_bit = (uint32_t)__ffs((int)P.local_batch) - 1u;
+  unsigned long long sum_lo[kMethods] = {0, 0, 0, 0, 0}, sum_hi[kMethods] = {0, 0, 0, 0, 0};
+
+  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    uint32_t lo[kMethods], hi[kMethods];
+#pragma unroll
+    for (uint32_t q = 0; q < kMethods; ++q) lo[q] = 0xffffffffu, hi[q] = 0u;
+    const uint64_t k_trial = (P.first_trial + t) * (uint64_t)pool_all;  // the trial's first draw
+    // ---- draws from the whole dataset: NONE, and the counts for GLOBAL
+    for (uint32_t i = tid; i <= P.max_len; i += kBlock) s_cnt[i] = 0u;
+    for (uint32_t i = tid; i < P.n_gpus; i += kBlock) s_gpu[i] = 0u;
+    if (tid == 0) s_base = 0u;
+    __syncthreads();
+    for (uint32_t g = tid; g < P.n_gpus; g += kBlock) {
+      uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
+      uint32_t tokens = 0;
+      for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma) {
+        const uint32_t l = draw(s_dyn, s_whole, 32u - kWholeGuideBits, z, 0u, P.total);
+        tokens += l;
+        atomicAdd(&s_cnt[l], 1u);
+      }
+      lo[LBS_NONE] = min(lo[LBS_NONE], tokens), hi[LBS_NONE] = max(hi[LBS_NONE], tokens);
+    }
+    __syncthreads();
+    {
+      uint32_t piece = 0;
+      for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
+      uint32_t run = block_running_sum(s_scan, piece) - piece;
+      uint32_t whole_turns = 0;
+      for (uint32_t l = a; l < b; ++l) {
+        const uint32_t n = s_cnt[l];
+        if (n != 0u) {
+          const uint32_t turns = n / P.n_gpus, rest = n - turns * P.n_gpus, first = run % P.n_gpus;
+          whole_turns += turns * l;
+          if (rest != 0u) {
+            const uint32_t end = first + rest;
+            atomicAdd(&s_gpu[first], l);
+            if (end < P.n_gpus) atomicAdd(&s_gpu[end], 0u - l);
+            if (end > P.n_gpus) atomicAdd(&s_gpu[0], l), atomicAdd(&s_gpu[end - P.n_gpus], 0u - l);
+          }
+        }
+        run += n;
+      }
+      if (whole_turns != 0u) atomicAdd(&s_base, whole_turns);
+      __syncthreads();
+      uint32_t mine = 0;
+      for (uint32_t g = ga; g < gb; ++g) mine += s_gpu[g];
+      uint32_t tokens = block_running_sum(s_scan, mine) - mine + s_base;
+      for (uint32_t g = ga; g < gb; ++g) {
+        tokens += s_gpu[g];
+        lo[LBS_GLOBAL] = min(lo[LBS_GLOBAL], tokens), hi[LBS_GLOBAL] = max(hi[LBS_GLOBAL], tokens);
+      }
+    }
+    // ---- stratified draws, a wavefront per node: STRATIFIED, LOCAL_RASTER, LOCAL_SNAKE (no LDS writes, no barriers)
+    for (uint32_t node = wave; node < n_nodes; node += kWaves) {
+      const uint64_t z_node = state(P.seed, k_trial + (uint64_t)node * pool);
+      uint32_t v[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const uint32_t i = (uint32_t)e * 64u + lane;
+        v[e] = i < pool ? draw(s_dyn, s_strata + goff[e], 32u - kGuideBits, z_node + i * kGamma, before[e], size[e]) : 0xffffffffu;
+      }
+#pragma unroll
+      for (int e = 0; e < E; ++e) {  // a GPU's own draws are local_batch consecutive pool entries
+        const bool real = (uint32_t)e * 64u + lane < pool;
+        const uint32_t own = butterfly_sum(real ? v[e] : 0u, 0u, batch_bit);
+        if (real) lo[LBS_STRATIFIED] = min(lo[LBS_STRATIFIED], own), hi[LBS_STRATIFIED] = max(hi[LBS_STRATIFIED], own);
+      }
+      bitonic_sort<E>(v, bit);
+      uint32_t column = 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) column += (uint32_t)e * 64u + lane < pool ? v[e] : 0u;
+      const uint32_t mirrored = from_mirror(column, P.gpus_per_node);
+      const uint32_t raster = butterfly_sum(column, gpn_bit, 6u);
+      const uint32_t snake = butterfly_sum(odd_row ? mirrored : column, gpn_bit, 6u);
+      lo[LBS_LOCAL_RASTER] = min(lo[LBS_LOCAL_RASTER], raster), hi[LBS_LOCAL_RASTER] = max(hi[LBS_LOCAL_RASTER], raster);
+      lo[LBS_LOCAL_SNAKE] = min(lo[LBS_LOCAL_SNAKE], snake), hi[LBS_LOCAL_SNAKE] = max(hi[LBS_LOCAL_SNAKE], snake);
+    }
+    // ---- the trial's five results
+    const uint32_t buf = round & 1u;
+#pragma unroll
+    for (uint32_t q = 0; q < kMethods; ++q) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        lo[q] = min(lo[q], (uint32_t)__shfl_xor((int)lo[q], off, 64));
+        hi[q] = max(hi[q], (uint32_t)__shfl_xor((int)hi[q], off, 64));
+      }
+      if (lane == 0) s_fin.lo[buf][q][wave] = lo[q], s_fin.hi[buf][q][wave] = hi[q];
+    }
+    __syncthreads();  // also: this trial's last reads of s_cnt and s_gpu lie before the next trial's clearing
+    if (tid == 0) {
+#pragma unroll
+      for (uint32_t q = 0; q < kMethods; ++q) {
+        const uint32_t l = min(min(s_fin.lo[buf][q][0], s_fin.lo[buf][q][1]), min(s_fin.lo[buf][q][2], s_fin.lo[buf][q][3]));
+        const uint32_t h = max(max(s_fin.hi[buf][q][0], s_fin.hi[buf][q][1]), max(s_fin.hi[buf][q][2], s_fin.hi[buf][q][3]));
+        if (trial_min) trial_min[(size_t)q * P.n_trials + t] = l;
+        if (trial_max) trial_max[(size_t)q * P.n_trials + t] = h;
+        sum_lo[q] += l, sum_hi[q] += h;
+      }
+    }
+  }
+  if (tid == 0) {
+#pragma unroll
+    for (uint32_t q = 0; q < kMethods; ++q) {
+      atomicAdd(&sums[2u * q], sum_lo[q]);
+      atomicAdd(&sums[2u * q + 1u], sum_hi[q]);
+    }
+  }
+}
+
+__global__ __launch_bounds__(64) void k_lbs_clear_all(unsigned long long* sums) {
+  if (threadIdx.x < 2u * kMethods) sums[threadIdx.x] = 0ull;
 }
 
 // Host: length of dataset entry `index` (entries ordered by length).
@@ -547,19 +744,20 @@ int lbs_dataset_create(lbs_dataset** out, int device, uint32_t max_len, const ui
   return rc;
 }
 
-int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min, uint32_t* trial_max, uint64_t* sums,
-                 void* stream) {
+// One method of a run (run->method is not looked at).
+static int simulate_one(const lbs_dataset* ds, const lbs_run* run, uint32_t method, uint32_t* trial_min, uint32_t* trial_max,
+                        uint64_t* sums, void* stream) {
   if (!ds || !run) return fail(LBS_ERR_NULL, "dataset or run is NULL");
-  if (run->method > LBS_GLOBAL) return fail(LBS_ERR_ARG, "unknown method");
+  if (method > LBS_GLOBAL) return fail(LBS_ERR_ARG, "unknown method");
   if (run->local_batch == 0 || run->n_gpus == 0) return fail(LBS_ERR_ARG, "local_batch and n_gpus must be positive");
   if (run->local_batch > LBS_MAX_LOCAL_BATCH) return fail(LBS_ERR_LIMIT, "local_batch exceeds LBS_MAX_LOCAL_BATCH");
   if ((uint64_t)run->n_gpus * run->local_batch >= (1ull << 31)) return fail(LBS_ERR_LIMIT, "n_gpus * local_batch must stay below 2^31");
   if (run->n_trials >= (1ull << 31)) return fail(LBS_ERR_LIMIT, "n_trials must stay below 2^31");
-  const bool stratified = run->method == LBS_STRATIFIED || run->method == LBS_LOCAL_RASTER || run->method == LBS_LOCAL_SNAKE;
-  const bool local = run->method == LBS_LOCAL_RASTER || run->method == LBS_LOCAL_SNAKE;
+  const bool stratified = method == LBS_STRATIFIED || method == LBS_LOCAL_RASTER || method == LBS_LOCAL_SNAKE;
+  const bool local = method == LBS_LOCAL_RASTER || method == LBS_LOCAL_SNAKE;
   Params P{};
   P.max_len = ds->max_len, P.local_batch = run->local_batch, P.gpus_per_node = run->gpus_per_node;
-  P.n_gpus = run->n_gpus, P.snake = run->method == LBS_LOCAL_SNAKE, P.stratified = stratified;
+  P.n_gpus = run->n_gpus, P.snake = method == LBS_LOCAL_SNAKE, P.stratified = stratified;
   P.total = ds->cum[ds->max_len], P.seed = run->seed;
   P.guide_words = stratified ? ds->n_strata * kGuideSize : kWholeGuideSize;
   P.guide_shift = 32u - (stratified ? kGuideBits : kWholeGuideBits);
@@ -592,8 +790,8 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
   hipError_t e = hipGetLastError();
   // dynamic LDS in words: histogram, guide tables, then the sorted pools (local) or the trial's histogram (global)
   const uint32_t tables = ds->max_len + 1u + P.guide_words;
-  const bool spread = run->method == LBS_GLOBAL && run->n_gpus <= kMaxSpreadGpus;
-  const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : run->method == LBS_GLOBAL ? ds->max_len + 1u + (spread ? run->n_gpus : 0u) : 0u));
+  const bool spread = method == LBS_GLOBAL && run->n_gpus <= kMaxSpreadGpus;
+  const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : method == LBS_GLOBAL ? ds->max_len + 1u + (spread ? run->n_gpus : 0u) : 0u));
   if (e == hipSuccess && run->n_trials > 0) {
     // trials cost the same, so a few workgroups per resident slot balance; each loops over its share of the trials
     const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
@@ -608,12 +806,69 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min,
           : pool <= 512 ? (in_lanes ? k_lbs_local<8, true> : k_lbs_local<8, false>)
                         : (in_lanes ? k_lbs_local<16, true> : k_lbs_local<16, false>);
       hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
-    } else if (run->method == LBS_GLOBAL) {
+    } else if (method == LBS_GLOBAL) {
       hipLaunchKernelGGL(spread ? k_lbs_global<true> : k_lbs_global<false>, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min,
                          trial_max, ds_sums);
     } else {
       hipLaunchKernelGGL(k_lbs_keep, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     }
+    e = hipGetLastError();
+  }
+  if (prev >= 0 && prev != ds->device) (void)hipSetDevice(prev);
+  if (e != hipSuccess) return fail(LBS_ERR_HIP, std::string("launching the simulation: ") + hipGetErrorString(e));
+  return 0;
+}
+
+int lbs_simulate(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min, uint32_t* trial_max, uint64_t* sums,
+                 void* stream) {
+  if (!ds || !run) return fail(LBS_ERR_NULL, "dataset or run is NULL");
+  return simulate_one(ds, run, run->method, trial_min, trial_max, sums, stream);
+}
+
+int lbs_simulate_all(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_min, uint32_t* trial_max, uint64_t* sums,
+                     void* stream) {
+  if (!ds || !run) return fail(LBS_ERR_NULL, "dataset or run is NULL");
+  if (!sums) return fail(LBS_ERR_NULL, "sums is NULL");
+  const uint32_t gpn = run->gpus_per_node, lb = run->local_batch, G = run->n_gpus;
+  const uint32_t guide_words = kWholeGuideSize + ds->n_strata * kGuideSize;
+  const size_t lds = sizeof(uint32_t) * (2u * (size_t)(ds->max_len + 1u) + guide_words + G);
+  const bool one_pass = gpn != 0 && gpn <= 32 && (gpn & (gpn - 1u)) == 0 && lb != 0 && lb <= LBS_MAX_LOCAL_BATCH &&
+                        (lb & (lb - 1u)) == 0 && G != 0 && G % gpn == 0 && G <= kMaxSpreadGpus && lds <= (60u << 10) &&
+                        (uint64_t)gpn * lb <= LBS_MAX_NODE_POOL && ds->device >= 0 && run->n_trials > 0 &&
+                        run->n_trials < (1ull << 31);
+  if (!one_pass) {  // every other case, errors included: method by method
+    for (uint32_t m = 0; m < kMethods; ++m) {
+      const int rc = simulate_one(ds, run, m, trial_min ? trial_min + (size_t)m * run->n_trials : nullptr,
+                                  trial_max ? trial_max + (size_t)m * run->n_trials : nullptr, sums + 2u * m, stream);
+      if (rc != 0) return rc;
+    }
+    return 0;
+  }
+  Params P{};
+  P.max_len = ds->max_len, P.local_batch = lb, P.gpus_per_node = gpn, P.n_gpus = G, P.stratified = 1;
+  P.total = ds->cum[ds->max_len], P.seed = run->seed, P.first_trial = run->first_trial, P.n_trials = (uint32_t)run->n_trials;
+  P.guide_words = guide_words;
+  uint32_t j = 0;
+  for (uint32_t s = 0; s < ds->n_strata; ++s) {
+    const uint32_t lo = ds->cum[s == 0 ? 0 : ds->stratum_end[s - 1]], size = ds->cum[ds->stratum_end[s]] - lo;
+    if (run->quota[s] && size == 0) return fail(LBS_ERR_ARG, "a stratum with a quota has no entries");
+    if ((uint64_t)j + run->quota[s] > lb) return fail(LBS_ERR_ARG, "the quotas exceed local_batch");
+    for (uint32_t q = 0; q < run->quota[s]; ++q, ++j) P.slot_lo[j] = lo, P.slot_size[j] = size, P.slot_guide[j] = s * kGuideSize;
+  }
+  if (j != lb) return fail(LBS_ERR_ARG, "the quotas must add up to local_batch");
+  int prev = -1;
+  (void)hipGetDevice(&prev);
+  if (prev != ds->device && hipSetDevice(ds->device) != hipSuccess) return fail(LBS_ERR_HIP, "hipSetDevice failed");
+  hipStream_t s = (hipStream_t)stream;
+  unsigned long long* ds_sums = reinterpret_cast<unsigned long long*>(sums);
+  hipLaunchKernelGGL(k_lbs_clear_all, dim3(1), dim3(64), 0, s, ds_sums);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) {
+    const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
+    const uint32_t pool = gpn * lb;
+    void (*kernel)(const Params, const uint32_t*, const uint32_t*, uint32_t*, uint32_t*, unsigned long long*) =
+        pool <= 64 ? k_lbs_all<1> : pool <= 128 ? k_lbs_all<2> : pool <= 256 ? k_lbs_all<4> : pool <= 512 ? k_lbs_all<8> : k_lbs_all<16>;
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, P, ds->d_cum, ds->d_guide, trial_min, trial_max, ds_sums);
     e = hipGetLastError();
   }
   if (prev >= 0 && prev != ds->device) (void)hipSetDevice(prev);

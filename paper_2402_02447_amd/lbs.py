@@ -14,7 +14,7 @@ LBS_NONE, LBS_STRATIFIED, LBS_LOCAL_RASTER, LBS_LOCAL_SNAKE, LBS_GLOBAL = 0, 1, 
 LBS_MAX_LEN, LBS_MAX_STRATA, LBS_MAX_LOCAL_BATCH, LBS_MAX_NODE_POOL = 1024, 8, 64, 1024
 _ERR = {-1: "LBS_ERR_NULL", -2: "LBS_ERR_ARG", -3: "LBS_ERR_LIMIT", -4: "LBS_ERR_HIP", -5: "LBS_ERR_HOST"}
 
-EXPORTS = ["lbs_dataset_create", "lbs_dataset_destroy", "lbs_simulate", "lbs_last_error"]
+EXPORTS = ["lbs_dataset_create", "lbs_dataset_destroy", "lbs_simulate", "lbs_simulate_all", "lbs_last_error"]
 
 
 class LbsError(RuntimeError):
@@ -41,6 +41,7 @@ def _lib():
         L.lbs_dataset_destroy.argtypes = [vp]
         L.lbs_dataset_destroy.restype = None
         L.lbs_simulate.argtypes = [vp, C.POINTER(_Run), vp, vp, vp, vp]
+        L.lbs_simulate_all.argtypes = [vp, C.POINTER(_Run), vp, vp, vp, vp]
         L.lbs_last_error.restype = C.c_char_p
         for name in EXPORTS:
             getattr(L, name)
@@ -96,3 +97,14 @@ class Dataset:
             for i, q in enumerate(quota):
                 run.quota[i] = int(q)
         _check(self._L.lbs_simulate(self._h, C.byref(run), _ptr(trial_min), _ptr(trial_max), _ptr(sums), _stream(stream)))
+
+    def lbs_simulate_all(self, local_batch: int, gpus_per_node: int, n_gpus: int, quota: Sequence[int], seed: int,
+                         n_trials: int, sums, trial_min=None, trial_max=None, first_trial: int = 0, stream=None) -> None:
+        """All five methods on the same draws.  sums: device buffer of 5 x 2 uint64; trial_min / trial_max: device
+        buffers of 5 x n_trials uint32 or None."""
+        run = _Run(0, local_batch, gpus_per_node, n_gpus, (C.c_uint32 * LBS_MAX_STRATA)(), seed, first_trial, n_trials)
+        if len(quota) > LBS_MAX_STRATA:
+            raise ValueError("too many strata")
+        for i, q in enumerate(quota):
+            run.quota[i] = int(q)
+        _check(self._L.lbs_simulate_all(self._h, C.byref(run), _ptr(trial_min), _ptr(trial_max), _ptr(sums), _stream(stream)))

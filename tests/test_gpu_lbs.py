@@ -173,3 +173,45 @@ def test_random_settings_all_methods(seed):
     for method in range(5):
         check(cum, ends, method, b, P, G, quota, seed=int(rng.integers(0, 2 ** 62)), n=int(rng.integers(1, 12)),
               first=int(rng.integers(0, 2 ** 40)))
+
+
+# ------------------------------------------------------------------ all five methods on one set of draws
+
+
+def check_all(cum, ends, b, P, G, quota, seed, n, first=0):
+    """lbs_simulate_all against the oracle run method by method."""
+    with lbs.Dataset(cum, ends, device=torch.cuda.current_device()) as ds:
+        sums = torch.full((5, 2), 77, dtype=torch.int64, device="cuda")
+        tmin = torch.full((5, max(n, 1)), 0xABCD, dtype=torch.int32, device="cuda")
+        tmax = torch.full((5, max(n, 1)), 0xABCD, dtype=torch.int32, device="cuda")
+        ds.lbs_simulate_all(b, P, G, quota, seed, n, sums, tmin, tmax, first_trial=first)
+        torch.cuda.synchronize()
+        sums2 = torch.full((5, 2), 55, dtype=torch.int64, device="cuda")
+        ds.lbs_simulate_all(b, P, G, quota, seed, n, sums2, first_trial=first)        # without the per-trial outputs
+        torch.cuda.synchronize()
+    gs, gmin, gmax = sums.cpu().numpy(), tmin.cpu().numpy().view(np.uint32), tmax.cpu().numpy().view(np.uint32)
+    assert np.array_equal(gs, sums2.cpu().numpy())
+    for method in range(5):
+        omin, omax, o0, o1 = O.simulate(cum, ends, quota, b, P, G, method, seed, n, first_trial=first)
+        assert np.array_equal(gmin[method, :n], omin), (method, np.flatnonzero(gmin[method, :n] != omin)[:5])
+        assert np.array_equal(gmax[method, :n], omax), (method, np.flatnonzero(gmax[method, :n] != omax)[:5])
+        assert (int(gs[method, 0]), int(gs[method, 1])) == (o0, o1), method
+
+
+def test_all_methods_in_one_pass_paper_setting_and_other_register_counts():
+    quota = [int(q) for q in W.stratum_quota(CUM, ENDS, 16)]
+    check_all(CUM, ENDS, 16, 8, 1024, quota, seed=11, n=150)
+    check_all(CUM, ENDS, 16, 4, 64, [5, 2, 3, 6], seed=12, n=20, first=123_456_789)       # pool of 64: one register per lane
+    check_all(CUM, ENDS, 64, 8, 32, [1, 1, 1, 61], seed=13, n=6)                            # pool of 512
+    check_all(CUM, ENDS, 32, 32, 64, [8, 8, 8, 8], seed=14, n=5)                            # pool of 1024
+    check_all(CUM, ENDS, 1, 1, 7, [0, 1, 0, 0], seed=15, n=9)                               # one draw per GPU, one GPU per node
+    check_all(CUM, ENDS, 2, 2, 8192, [1, 0, 0, 1], seed=16, n=3)                            # the most GPUs the one pass takes
+    check_all(CUM, ENDS, 4, 2, 12, [1, 1, 1, 1], seed=17, n=256 * 32 + 77, first=5)         # workgroups run several trials
+
+
+def test_all_methods_falls_back_to_one_method_at_a_time():
+    cum = W.length_histogram_piecewise_uniform(70_001, (50, 201, 333), (0.2, 0.5, 0.3))
+    check_all(cum, (50, 201, 333), 7, 3, 3 * 67, [2, 4, 1], seed=5, n=11)                  # neither size a power of two
+    check_all(CUM, ENDS, 16, 64, 128, [4, 4, 4, 4], seed=6, n=4)                            # node of 64 GPUs
+    check_all(CUM, ENDS, 2, 1, 8193, [1, 0, 0, 1], seed=7, n=2)                             # too many GPUs for a word each
+    check_all(CUM, ENDS, 16, 8, 64, [5, 2, 3, 6], seed=8, n=0)                              # no trials: sums cleared
