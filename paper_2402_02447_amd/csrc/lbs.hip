@@ -123,78 +123,6 @@ __device__ __forceinline__ uint32_t* load_tables(uint32_t* s_dyn, const Params& 
   return s_guide;
 }
 
-// A workgroup loads the tables once and then runs trials blockIdx.x, blockIdx.x + gridDim.x, ... of the
-// call, so the grid need only fill the chip, and thread 0 carries the workgroup's share of the two sums.
-
-// Wavefront minima and maxima of a trial, double-buffered by the parity of the workgroup's trial count: a
-// wavefront can be one trial ahead of thread 0, never two (the barrier in between needs all of them).
-struct Finish {
-  uint32_t lo[2][kWaves], hi[2][kWaves];
-};
-
-// Combines the threads' minimum and maximum of trial t (the round-th this workgroup runs); thread 0 stores
-// them and adds them to its running sums.
-__device__ __forceinline__ void finish_trial(uint32_t lo, uint32_t hi, Finish& f, uint32_t round, uint32_t t,
-                                             uint32_t* trial_min, uint32_t* trial_max, unsigned long long& sum_lo,
-                                             unsigned long long& sum_hi) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    lo = min(lo, (uint32_t)__shfl_xor((int)lo, off, 64));
-    hi = max(hi, (uint32_t)__shfl_xor((int)hi, off, 64));
-  }
-  const uint32_t buf = round & 1u;
-  if ((threadIdx.x & 63u) == 0) f.lo[buf][threadIdx.x >> 6] = lo, f.hi[buf][threadIdx.x >> 6] = hi;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    lo = min(min(f.lo[buf][0], f.lo[buf][1]), min(f.lo[buf][2], f.lo[buf][3]));
-    hi = max(max(f.hi[buf][0], f.hi[buf][1]), max(f.hi[buf][2], f.hi[buf][3]));
-    if (trial_min) trial_min[t] = lo;
-    if (trial_max) trial_max[t] = hi;
-    sum_lo += lo, sum_hi += hi;
-  }
-}
-
-// Thread 0 adds the workgroup's sums to the call's.
-__device__ __forceinline__ void publish_sums(unsigned long long* sums, unsigned long long sum_lo,
-                                             unsigned long long sum_hi) {
-  if (threadIdx.x == 0) {
-    atomicAdd(&sums[0], sum_lo);
-    atomicAdd(&sums[1], sum_hi);
-  }
-}
-
-__global__ __launch_bounds__(64) void k_lbs_clear(unsigned long long* sums) {
-  if (threadIdx.x < 2) sums[threadIdx.x] = 0ull;
-}
-
-// NONE and STRATIFIED: no redistribution.
-__global__ __launch_bounds__(kBlock) void k_lbs_keep(const Params P, const uint32_t* __restrict__ cum,
-                                                      const uint32_t* __restrict__ guide, uint32_t* trial_min,
-                                                      uint32_t* trial_max, unsigned long long* sums) {
-  extern __shared__ uint32_t s_dyn[];  // histogram, guide tables
-  __shared__ Finish s_finish;
-  const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
-  unsigned long long sum_lo = 0, sum_hi = 0;
-  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
-    const uint64_t k_trial = (P.first_trial + t) * P.n_gpus * (uint64_t)P.local_batch;  // the trial's first draw
-    uint32_t lo = 0xffffffffu, hi = 0u;
-    for (uint32_t g = threadIdx.x; g < P.n_gpus; g += kBlock) {
-      uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
-      uint32_t tokens = 0;
-      for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
-        tokens += draw(s_dyn, s_guide + P.slot_guide[j], P.guide_shift, z, P.slot_lo[j], P.slot_size[j]);
-      lo = min(lo, tokens), hi = max(hi, tokens);
-    }
-    finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
-  }
-  publish_sums(sums, sum_lo, sum_hi);
-}
-
-// Median of three: with c = 0 it is min(a, b), with c = 0xffffffff it is max(a, b) (one v_med3_u32).
-__device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) {
-  return max(min(a, b), min(max(a, b), c));
-}
-
 // The value that lane ^ 2^LJ holds.  Within a row of 16 lanes the exchange is a data-parallel move of the
 // vector unit (quad permutation, shifts by 4 written to alternate banks of four lanes, rotation by 8);
 // across rows it goes through the LDS crossbar.
@@ -250,6 +178,83 @@ __device__ __forceinline__ uint32_t from_mirror(uint32_t x, uint32_t n) {
     case 16: return (uint32_t)__builtin_amdgcn_mov_dpp(v, 0x140, 0xf, 0xf, true); // row_mirror
     default: return (uint32_t)__shfl_xor(v, (int)(n - 1u), 64);
   }
+}
+
+// Minimum and maximum over the wavefront, in every lane.
+__device__ __forceinline__ void wave_min_max(uint32_t& lo, uint32_t& hi) {
+#pragma unroll
+  for (int lj = 0; lj < 6; ++lj) {
+    lo = min(lo, partner_of(lo, lj));
+    hi = max(hi, partner_of(hi, lj));
+  }
+}
+
+// A workgroup loads the tables once and then runs trials blockIdx.x, blockIdx.x + gridDim.x, ... of the
+// call, so the grid need only fill the chip, and thread 0 carries the workgroup's share of the two sums.
+
+// Wavefront minima and maxima of a trial, double-buffered by the parity of the workgroup's trial count: a
+// wavefront can be one trial ahead of thread 0, never two (the barrier in between needs all of them).
+struct Finish {
+  uint32_t lo[2][kWaves], hi[2][kWaves];
+};
+
+// Combines the threads' minimum and maximum of trial t (the round-th this workgroup runs); thread 0 stores
+// them and adds them to its running sums.
+__device__ __forceinline__ void finish_trial(uint32_t lo, uint32_t hi, Finish& f, uint32_t round, uint32_t t,
+                                             uint32_t* trial_min, uint32_t* trial_max, unsigned long long& sum_lo,
+                                             unsigned long long& sum_hi) {
+  wave_min_max(lo, hi);
+  const uint32_t buf = round & 1u;
+  if ((threadIdx.x & 63u) == 0) f.lo[buf][threadIdx.x >> 6] = lo, f.hi[buf][threadIdx.x >> 6] = hi;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    lo = min(min(f.lo[buf][0], f.lo[buf][1]), min(f.lo[buf][2], f.lo[buf][3]));
+    hi = max(max(f.hi[buf][0], f.hi[buf][1]), max(f.hi[buf][2], f.hi[buf][3]));
+    if (trial_min) trial_min[t] = lo;
+    if (trial_max) trial_max[t] = hi;
+    sum_lo += lo, sum_hi += hi;
+  }
+}
+
+// Thread 0 adds the workgroup's sums to the call's.
+__device__ __forceinline__ void publish_sums(unsigned long long* sums, unsigned long long sum_lo,
+                                             unsigned long long sum_hi) {
+  if (threadIdx.x == 0) {
+    atomicAdd(&sums[0], sum_lo);
+    atomicAdd(&sums[1], sum_hi);
+  }
+}
+
+__global__ __launch_bounds__(64) void k_lbs_clear(unsigned long long* sums) {
+  if (threadIdx.x < 2) sums[threadIdx.x] = 0ull;
+}
+
+// NONE and STRATIFIED: no redistribution.
+__global__ __launch_bounds__(kBlock) void k_lbs_keep(const Params P, const uint32_t* __restrict__ cum,
+                                                      const uint32_t* __restrict__ guide, uint32_t* trial_min,
+                                                      uint32_t* trial_max, unsigned long long* sums) {
+  extern __shared__ uint32_t s_dyn[];  // histogram, guide tables
+  __shared__ Finish s_finish;
+  const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
+  unsigned long long sum_lo = 0, sum_hi = 0;
+  for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    const uint64_t k_trial = (P.first_trial + t) * P.n_gpus * (uint64_t)P.local_batch;  // the trial's first draw
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (uint32_t g = threadIdx.x; g < P.n_gpus; g += kBlock) {
+      uint64_t z = state(P.seed, k_trial + (uint64_t)g * P.local_batch);
+      uint32_t tokens = 0;
+      for (uint32_t j = 0; j < P.local_batch; ++j, z += kGamma)
+        tokens += draw(s_dyn, s_guide + P.slot_guide[j], P.guide_shift, z, P.slot_lo[j], P.slot_size[j]);
+      lo = min(lo, tokens), hi = max(hi, tokens);
+    }
+    finish_trial(lo, hi, s_finish, round, t, trial_min, trial_max, sum_lo, sum_hi);
+  }
+  publish_sums(sums, sum_lo, sum_hi);
+}
+
+// Median of three: with c = 0 it is min(a, b), with c = 0xffffffff it is max(a, b) (one v_med3_u32).
+__device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) {
+  return max(min(a, b), min(max(a, b), c));
 }
 
 // Sorts the 64 * E values held by a wavefront (value i in v[i / 64] of lane i % 64) into ascending order of i.
@@ -605,11 +610,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32
     const uint32_t buf = round & 1u;
 #pragma unroll
     for (uint32_t q = 0; q < kMethods; ++q) {
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        lo[q] = min(lo[q], (uint32_t)__shfl_xor((int)lo[q], off, 64));
-        hi[q] = max(hi[q], (uint32_t)__shfl_xor((int)hi[q], off, 64));
-      }
+      wave_min_max(lo[q], hi[q]);
       if (lane == 0) s_fin.lo[buf][q][wave] = lo[q], s_fin.hi[buf][q][wave] = hi[q];
     }
     __syncthreads();  // also: this trial's last reads of s_cnt and s_gpu lie before the next trial's clearing
