@@ -494,14 +494,16 @@ struct FinishAll {
 };
 
 template <int E>
-__global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32_t* __restrict__ cum,
+__global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) void k_lbs_all(const Params P, const uint32_t* __restrict__ cum,
                                                      const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                      uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, all guide tables, the trial's own histogram, one word per GPU
   __shared__ uint32_t s_scan[kWaves];
   __shared__ uint32_t s_base;
   __shared__ FinishAll s_fin;
+  __shared__ unsigned long long s_sum[2u * kMethods];  // the workgroup's share of the sums, kept by thread 0
   const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
+  if (tid < 2u * kMethods) s_sum[tid] = 0ull;  // thread 0 first touches them after the first trial's barriers
   uint32_t* s_whole = s_dyn + P.max_len + 1u;          // guide table of the whole dataset
   uint32_t* s_strata = s_whole + kWholeGuideSize;      // guide tables of the strata
   uint32_t* s_cnt = s_whole + P.guide_words;
@@ -529,9 +531,9 @@ __global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32
   for (int q = 0; q < 6; ++q) bit[q] = 0u - ((lane >> q) & 1u);
   const bool odd_row = ((lane / P.gpus_per_node) & 1u) != 0u;
   const uint32_t gpn_bit = (uint32_t)__ffs((int)P.gpus_per_node) - 1u, batch_bit = (uint32_t)__ffs((int)P.local_batch) - 1u;
-  unsigned long long sum_lo[kMethods] = {0, 0, 0, 0, 0}, sum_hi[kMethods] = {0, 0, 0, 0, 0};
 
   for (uint32_t t = blockIdx.x, round = 0; t < P.n_trials; t += gridDim.x, ++round) {
+    const uint32_t buf = round & 1u;
     uint32_t lo[kMethods], hi[kMethods];
 #pragma unroll
     for (uint32_t q = 0; q < kMethods; ++q) lo[q] = 0xffffffffu, hi[q] = 0u;
@@ -581,6 +583,13 @@ __global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32
         lo[LBS_GLOBAL] = min(lo[LBS_GLOBAL], tokens), hi[LBS_GLOBAL] = max(hi[LBS_GLOBAL], tokens);
       }
     }
+    // these two are filed now, so that they need no registers during the sort
+    wave_min_max(lo[LBS_NONE], hi[LBS_NONE]);
+    wave_min_max(lo[LBS_GLOBAL], hi[LBS_GLOBAL]);
+    if (lane == 0) {
+      s_fin.lo[buf][LBS_NONE][wave] = lo[LBS_NONE], s_fin.hi[buf][LBS_NONE][wave] = hi[LBS_NONE];
+      s_fin.lo[buf][LBS_GLOBAL][wave] = lo[LBS_GLOBAL], s_fin.hi[buf][LBS_GLOBAL][wave] = hi[LBS_GLOBAL];
+    }
     // ---- stratified draws, a wavefront per node: STRATIFIED, LOCAL_RASTER, LOCAL_SNAKE (no LDS writes, no barriers)
     for (uint32_t node = wave; node < n_nodes; node += kWaves) {
       const uint64_t z_node = state(P.seed, k_trial + (uint64_t)node * pool);
@@ -607,9 +616,8 @@ __global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32
       lo[LBS_LOCAL_SNAKE] = min(lo[LBS_LOCAL_SNAKE], snake), hi[LBS_LOCAL_SNAKE] = max(hi[LBS_LOCAL_SNAKE], snake);
     }
     // ---- the trial's five results
-    const uint32_t buf = round & 1u;
 #pragma unroll
-    for (uint32_t q = 0; q < kMethods; ++q) {
+    for (uint32_t q = LBS_STRATIFIED; q <= LBS_LOCAL_SNAKE; ++q) {
       wave_min_max(lo[q], hi[q]);
       if (lane == 0) s_fin.lo[buf][q][wave] = lo[q], s_fin.hi[buf][q][wave] = hi[q];
     }
@@ -621,16 +629,13 @@ __global__ __launch_bounds__(kBlock) void k_lbs_all(const Params P, const uint32
         const uint32_t h = max(max(s_fin.hi[buf][q][0], s_fin.hi[buf][q][1]), max(s_fin.hi[buf][q][2], s_fin.hi[buf][q][3]));
         if (trial_min) trial_min[(size_t)q * P.n_trials + t] = l;
         if (trial_max) trial_max[(size_t)q * P.n_trials + t] = h;
-        sum_lo[q] += l, sum_hi[q] += h;
+        s_sum[2u * q] += l, s_sum[2u * q + 1u] += h;
       }
     }
   }
   if (tid == 0) {
 #pragma unroll
-    for (uint32_t q = 0; q < kMethods; ++q) {
-      atomicAdd(&sums[2u * q], sum_lo[q]);
-      atomicAdd(&sums[2u * q + 1u], sum_hi[q]);
-    }
+    for (uint32_t q = 0; q < 2u * kMethods; ++q) atomicAdd(&sums[q], s_sum[q]);
   }
 }
 
