@@ -85,6 +85,18 @@ typedef struct bca_adam {
   double weight_decay; /* decoupled: p <- p - lr * (u + wd * p)     */
 } bca_adam;
 
+/* The same hyper-parameters and the step count in DEVICE memory, for callers that replay a captured HIP graph
+ * and so cannot change host-side arguments between replays (what frameworks call a capturable optimizer).
+ * After bca_plan_set_device_hyper(plan, dev), adam_step, bucket_clip_adam, lamb_step and bucket_clip_lamb
+ * ignore their `hp` (may be NULL) and `step` arguments: each call first enqueues a one-thread kernel that
+ * reads *dev on the stream and derives the constants the sweeps use, so whatever the caller has written
+ * there on that stream before the call (or the replay) applies.  The values are not validated (the ranges
+ * of bca_adam, step >= 1): they are the caller's to keep in range.  dev = NULL goes back to host arguments. */
+typedef struct bca_adam_device {
+  double lr, beta1, beta2, eps, weight_decay;
+  uint64_t step; /* >= 1, counts the current update */
+} bca_adam_device;
+
 /* Launch tuning; zero in any field means "library default". */
 #define BCA_TUNE_MULTI_LAUNCH 1u    /* bucket_clip_adam as separate norm / finalize / Adam launches per
                                        bucket group instead of the single pipelined launch; likewise
@@ -149,6 +161,10 @@ int bca_plan_bind(bca_plan* plan, void* const* grads, float* const* params, floa
  * Affects adam_step, bucket_clip_adam, lamb_step and bucket_clip_lamb.  May be called
  * before or after bca_plan_bind; on a bound plan it is synchronous (rewrites the tables). */
 int bca_plan_set_decay_mask(bca_plan* plan, const uint8_t* decay /*HOST [n_tensors] or NULL*/);
+
+/* Take hyper-parameters and step from device memory (see bca_adam_device); dev must stay valid while set.
+ * BCA_ERR_UNBOUND on a host-only plan. */
+int bca_plan_set_device_hyper(bca_plan* plan, const bca_adam_device* dev /*DEVICE or NULL*/);
 
 void bca_plan_destroy(bca_plan* plan);
 

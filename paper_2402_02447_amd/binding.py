@@ -25,7 +25,7 @@ BCA_TABLE_NORM, BCA_TABLE_APPLY, BCA_TABLE_LAMB = 0, 1, 2
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
-EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_destroy", "bca_plan_num_buckets",
+EXPORTS = ["bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
            "bca_plan_num_groups", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
            "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error",
@@ -65,6 +65,17 @@ class AdamHyper:
         return _Adam(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay)
 
 
+def _hp(hp: Optional[AdamHyper]):
+    """byref of the C struct, or NULL (allowed once the plan takes hyper-parameters from device memory)."""
+    return C.byref(hp._c()) if hp is not None else None
+
+
+def pack_device_hyper(hp: Optional[AdamHyper], step: int) -> bytes:
+    """The 48 bytes of a bca_adam_device: copy them into a device buffer and hand that to Plan.set_device_hyper."""
+    import struct
+    return struct.pack("<5dQ", hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, step)
+
+
 def library_path() -> str:
     return os.environ.get("BCA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbca.so")
 
@@ -94,6 +105,7 @@ def load_library():
                                   C.POINTER(_Tuning)]
     L.bca_plan_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     L.bca_plan_set_decay_mask.argtypes = [vp, C.POINTER(C.c_uint8)]
+    L.bca_plan_set_device_hyper.argtypes = [vp, vp]
     L.bca_plan_destroy.argtypes = [vp]
     L.bca_plan_destroy.restype = None
     L.bca_plan_num_buckets.argtypes = [vp]
@@ -249,6 +261,12 @@ class Plan:
         buf = (C.c_uint8 * max(1, self.n_tensors)).from_buffer_copy(a.tobytes() or b"\0")
         _check(self._L.bca_plan_set_decay_mask(self._h, buf))
 
+    def set_device_hyper(self, dev) -> None:
+        """dev: a device buffer holding a bca_adam_device (see pack_device_hyper), or None for host arguments.
+        While set, the compute calls take hyper-parameters and step from there (hp may be None)."""
+        _check(self._L.bca_plan_set_device_hyper(self._h, _ptr(dev)))
+        self._hyper_dev = dev                                  # keep the buffer alive while set
+
     # -- per-kernel timing of the fused call
     def profile(self, max_calls: int) -> None:
         _check(self._L.bca_plan_profile(self._h, max_calls))
@@ -272,22 +290,18 @@ class Plan:
         _check(self._L.bucket_clip(self._h, b0, b1, _ptr(thresholds), _ptr(norms), _ptr(coefs), _ptr(status),
                                    _stream(stream)))
 
-    def adam_step(self, hp: AdamHyper, step: int, stream=None) -> None:
-        h = hp._c()
-        _check(self._L.adam_step(self._h, C.byref(h), step, _stream(stream)))
+    def adam_step(self, hp: Optional[AdamHyper], step: int, stream=None) -> None:
+        _check(self._L.adam_step(self._h, _hp(hp), step, _stream(stream)))
 
-    def bucket_clip_adam(self, thresholds, hp: AdamHyper, step: int, flags: int = 0, norms=None, coefs=None,
+    def bucket_clip_adam(self, thresholds, hp: Optional[AdamHyper], step: int, flags: int = 0, norms=None, coefs=None,
                          status=None, stream=None) -> None:
-        h = hp._c()
-        _check(self._L.bucket_clip_adam(self._h, _ptr(thresholds), C.byref(h), step, flags, _ptr(norms), _ptr(coefs),
+        _check(self._L.bucket_clip_adam(self._h, _ptr(thresholds), _hp(hp), step, flags, _ptr(norms), _ptr(coefs),
                                         _ptr(status), _stream(stream)))
 
-    def lamb_step(self, hp: AdamHyper, step: int, trust=None, stream=None) -> None:
-        h = hp._c()
-        _check(self._L.lamb_step(self._h, C.byref(h), step, _ptr(trust), _stream(stream)))
+    def lamb_step(self, hp: Optional[AdamHyper], step: int, trust=None, stream=None) -> None:
+        _check(self._L.lamb_step(self._h, _hp(hp), step, _ptr(trust), _stream(stream)))
 
-    def bucket_clip_lamb(self, thresholds, hp: AdamHyper, step: int, flags: int = 0, norms=None, coefs=None,
+    def bucket_clip_lamb(self, thresholds, hp: Optional[AdamHyper], step: int, flags: int = 0, norms=None, coefs=None,
                          trust=None, status=None, stream=None) -> None:
-        h = hp._c()
-        _check(self._L.bucket_clip_lamb(self._h, _ptr(thresholds), C.byref(h), step, flags, _ptr(norms), _ptr(coefs),
+        _check(self._L.bucket_clip_lamb(self._h, _ptr(thresholds), _hp(hp), step, flags, _ptr(norms), _ptr(coefs),
                                         _ptr(trust), _ptr(status), _stream(stream)))

@@ -250,6 +250,8 @@ void free_device(bca_plan* p) {
   if (p->d_trust) (void)hipFree(p->d_trust);
   if (p->d_lamb_scale) (void)hipFree(p->d_lamb_scale);
   p->d_tensor_off = nullptr, p->d_lamb_sums = nullptr, p->d_trust = nullptr, p->d_lamb_scale = nullptr;
+  if (p->d_adamk) (void)hipFree(p->d_adamk);
+  p->d_adamk = nullptr;
   if (p->d_coefs) (void)hipFree(p->d_coefs);
   if (p->d_status) (void)hipFree(p->d_status);
   p->d_partials = nullptr, p->d_norms = nullptr, p->d_coefs = nullptr, p->d_status = nullptr;
@@ -337,7 +339,14 @@ int check_range(const bca_plan* p, uint32_t b0, uint32_t b1) {
   return BCA_OK;
 }
 
-int make_adam_constants(const bca_adam* hp, uint64_t step, AdamK* k) {
+// The constants of one call: from the host arguments, or (hyper-parameters in device memory) a pointer to
+// the device copy that enqueue_hyper fills on the call's stream.
+int make_adam_constants(const bca_plan* p, const bca_adam* hp, uint64_t step, AdamK* k) {
+  *k = AdamK{};
+  if (p->hyper_dev != nullptr) {
+    k->from = p->d_adamk;
+    return BCA_OK;
+  }
   if (!hp) return fail(BCA_ERR_NULL, "hyper-parameters are NULL");
   if (step == 0) return fail(BCA_ERR_HPARAM, "step counts from 1");
   if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0)) return fail(BCA_ERR_HPARAM, "beta1 must lie in [0, 1)");
@@ -356,6 +365,13 @@ int make_adam_constants(const bca_adam* hp, uint64_t step, AdamK* k) {
   k->wd = (float)hp->weight_decay;
   k->lr = hp->lr;
   return BCA_OK;
+}
+
+// With hyper-parameters in device memory: the one-thread kernel that derives this call's constants.
+int enqueue_hyper(const bca_plan* p, hipStream_t stream) {
+  if (p->hyper_dev == nullptr) return BCA_OK;
+  const hipError_t e = launch_hyper(p->hyper_dev, p->d_adamk, stream);
+  return e == hipSuccess ? BCA_OK : fail_hip(e, "launching the hyper-parameter kernel");
 }
 
 // requested == 0: one workgroup per chunk.
@@ -483,6 +499,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
         (e = hipMalloc((void**)&p->d_norms, (nb + 1) * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_bucket_sq, nb * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_coefs, nb * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_adamk, sizeof(AdamK))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_status, sizeof(int32_t))) != hipSuccess ||
         (e = hipMemset(p->d_status, 0, sizeof(int32_t))) != hipSuccess)
       return fail_hip(e, "allocating plan memory");
@@ -550,6 +567,14 @@ int bca_plan_set_decay_mask(bca_plan* p, const uint8_t* decay) {
     }
     return (int)BCA_OK;
   });
+}
+
+int bca_plan_set_device_hyper(bca_plan* p, const bca_adam_device* dev) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan (device -1) has no device hyper-parameters");
+  if (((uintptr_t)dev) % 8u) return fail(BCA_ERR_ALIGN, "dev must be 8-byte aligned");
+  p->hyper_dev = dev;
+  return BCA_OK;
 }
 
 void bca_plan_destroy(bca_plan* p) {
@@ -728,9 +753,10 @@ int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, 
 int adam_step(bca_plan* p, const bca_adam* hp, uint64_t step, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   AdamK k;
-  if (int rc = make_adam_constants(hp, step, &k)) return rc;
+  if (int rc = make_adam_constants(p, hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
   DeviceGuard g(p->device);
+  if (int rc = enqueue_hyper(p, (hipStream_t)stream)) return rc;
   const Table& T = p->apply_tab;
   const uint32_t n = (uint32_t)T.chunks.size();
   hipError_t e = launch_adam(p->grad_dtype, T.d_chunks, 0, n, nullptr, false, nullptr, k,
@@ -746,13 +772,14 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
   if (flags & ~(BCA_WRITE_BACK_GRADS | BCA_SKIP_STEP_ON_NONFINITE | BCA_CLIP_WHOLE_GRADIENT))
     return fail(BCA_ERR_RANGE, "unknown flag bits");
   AdamK k;
-  if (int rc = make_adam_constants(hp, step, &k)) return rc;
+  if (int rc = make_adam_constants(p, hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
   const bool whole = (flags & BCA_CLIP_WHOLE_GRADIENT) != 0;
   const bool skip = (flags & BCA_SKIP_STEP_ON_NONFINITE) != 0 || whole;  // both need every norm before any update
   const bool multi = (p->tune_flags & BCA_TUNE_MULTI_LAUNCH) != 0;
   DeviceGuard g(p->device);
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = enqueue_hyper(p, s)) return rc;
   float* nm = norms ? norms : p->d_norms;
   float* cf = coefs ? coefs : p->d_coefs;
   int32_t* st = status ? status : p->d_status;
@@ -816,9 +843,10 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
 static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, uint64_t step, uint32_t flags,
                      float* norms, float* coefs, float* trust, int32_t* status, hipStream_t s) {
   AdamK k;
-  if (int rc = make_adam_constants(hp, step, &k)) return rc;
+  if (int rc = make_adam_constants(p, hp, step, &k)) return rc;
   if (int rc = check_ready(p)) return rc;
   DeviceGuard g(p->device);
+  if (int rc = enqueue_hyper(p, s)) return rc;
   const Table& TL = p->lamb_tab;
   const uint32_t nl = (uint32_t)TL.chunks.size();
   hipError_t e = hipSuccess;
@@ -846,7 +874,7 @@ static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     e = launch_lamb_moments(p->grad_dtype, TL.d_chunks, nl, nullptr, false, p->d_lamb_sums, k, s);
     if (e != hipSuccess) return fail_hip(e, "launching the LAMB moments kernel");
   }
-  e = launch_lamb_trust(p->d_lamb_sums, p->d_tensor_off, p->n_tensors, k.lr, trust ? trust : p->d_trust,
+  e = launch_lamb_trust(p->d_lamb_sums, p->d_tensor_off, p->n_tensors, k, trust ? trust : p->d_trust,
                         p->d_lamb_scale, s);
   if (e != hipSuccess) return fail_hip(e, "launching the LAMB trust-ratio kernel");
   e = launch_lamb_update(TL.d_chunks, nl, p->d_lamb_scale, k, s);

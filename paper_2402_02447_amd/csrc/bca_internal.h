@@ -56,6 +56,7 @@ struct AdamK {
   float neg_lr;  // -lr
   float wd;
   double lr;     // LAMB: the step -lr * trust_t is formed in fp64 per tensor and rounded once
+  const AdamK* from;  // device copy to use instead of this one (hyper-parameters kept in device memory), or null
 };
 
 constexpr uint32_t kBlock = 256;          // threads per workgroup (4 wavefronts)
@@ -145,7 +146,9 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t 
 // Stage 2: p <- p + scale_t * update, the update recomputed from the stored moments.
 hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const float* coefs, bool write_back,
                                double* sums, const AdamK& k, hipStream_t stream);
-hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, double lr,
+// Derives the sweeps' constants from hyper-parameters in device memory (one thread).
+hipError_t launch_hyper(const bca_adam_device* dev, AdamK* out, hipStream_t stream);
+hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, const AdamK& k,
                              float* trust, float* scale, hipStream_t stream);
 hipError_t launch_lamb_update(const Chunk* table, uint32_t n, const float* scale, const AdamK& k,
                               hipStream_t stream);
@@ -162,6 +165,8 @@ struct bca_plan {
   uint32_t unroll_apply = 1;
   uint32_t adam_lds_reserve = 0;  // bytes; see bca_tuning::adam_lds_reserve
   uint32_t spin_limit = 0;        // see bca_tuning::spin_limit (default already applied)
+  const bca_adam_device* hyper_dev = nullptr;  // hyper-parameters in device memory, when set
+  bca::AdamK* d_adamk = nullptr;  // the constants derived from them by k_hyper
   uint32_t tune_flags = 0;
   bool bound = false;
   std::vector<uint64_t> tensor_numel;

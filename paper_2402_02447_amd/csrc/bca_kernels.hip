@@ -444,6 +444,28 @@ __global__ __launch_bounds__(kBlock) void k_scale(const Chunk* __restrict__ tabl
 // Division and square root are the correctly rounded ones.
 // wd is the weight decay that applies to the element's tensor: k.wd, or 0 for a
 // tensor the decay mask exempts.
+// The constants a kernel works with: those passed by value, or the device copy they point to.
+__device__ __forceinline__ AdamK resolve(const AdamK& a) {
+  if (a.from != nullptr) return *a.from;
+  return a;
+}
+
+// Hyper-parameters in device memory -> the sweeps' constants, as the host derives them from a bca_adam.
+__global__ __launch_bounds__(64) void k_hyper(const bca_adam_device* __restrict__ dev, AdamK* __restrict__ out) {
+  if (threadIdx.x != 0) return;
+  const double t = (double)dev->step;
+  AdamK k;
+  k.b1 = (float)dev->beta1, k.omb1 = (float)(1.0 - dev->beta1);
+  k.b2 = (float)dev->beta2, k.omb2 = (float)(1.0 - dev->beta2);
+  k.rbc1 = (float)(1.0 / (1.0 - pow(dev->beta1, t))), k.rbc2 = (float)(1.0 / (1.0 - pow(dev->beta2, t)));
+  k.eps = (float)dev->eps;
+  k.neg_lr = (float)(-dev->lr);
+  k.wd = (float)dev->weight_decay;
+  k.lr = dev->lr;
+  k.from = nullptr;
+  *out = k;
+}
+
 __device__ __forceinline__ void adam_moments(float g, float& m, float& v, const AdamK& k) {
   m = __fmaf_rn(k.b1, m, k.omb1 * g);
   v = __fmaf_rn(k.b2, v, k.omb2 * (g * g));
@@ -548,8 +570,9 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
 template <int GDT, bool FUSED, bool WB, uint32_t U, bool GNT, bool STAGED>
 __global__ __launch_bounds__(kBlock) void k_adam(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
                                                   const float* __restrict__ coefs, const int32_t* skip_status,
-                                                  const AdamK k) {
+                                                  const AdamK ka) {
   if (skip_status != nullptr && (*skip_status & BCA_STATUS_NONFINITE)) return;
+  const AdamK k = resolve(ka);
   for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t) {
     float coef = 1.f;
     if constexpr (FUSED) coef = coefs[en.bucket];
@@ -636,8 +659,9 @@ __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, 
 template <int GDT, bool FUSED, bool WB>
 __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict__ table, uint32_t n,
                                                           const float* __restrict__ coefs,
-                                                          double* __restrict__ sums, const AdamK k) {
+                                                          double* __restrict__ sums, const AdamK ka) {
   __shared__ double s_pp[kWaves], s_uu[kWaves];
+  const AdamK k = resolve(ka);
   for (uint32_t ci = blockIdx.x; ci < n; ci += gridDim.x) {
     const Entry en = read_entry(&table[ci]);
     float coef = 1.f;
@@ -654,9 +678,10 @@ __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict
 // rounded once.  The order is fixed, so the ratios are reproducible.
 constexpr uint32_t kTrustBlock = 1024;
 __global__ __launch_bounds__(kTrustBlock) void k_lamb_trust(const double* __restrict__ sums,
-                                                             const uint32_t* __restrict__ tensor_off, double lr,
+                                                             const uint32_t* __restrict__ tensor_off, const AdamK ka,
                                                              float* __restrict__ trust, float* __restrict__ scale) {
   __shared__ double s_pp[kTrustBlock / 64], s_uu[kTrustBlock / 64];
+  const double lr = resolve(ka).lr;
   const uint32_t t = blockIdx.x, lo = tensor_off[t], hi = tensor_off[t + 1];
   double pp0 = 0.0, uu0 = 0.0, pp1 = 0.0, uu1 = 0.0;
   uint32_t c = lo + threadIdx.x;
@@ -679,8 +704,9 @@ __global__ __launch_bounds__(kTrustBlock) void k_lamb_trust(const double* __rest
 }
 
 __global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict__ table, uint32_t n,
-                                                         const float* __restrict__ scale, const AdamK k) {
+                                                         const float* __restrict__ scale, const AdamK ka) {
   const uint32_t tid = threadIdx.x;
+  const AdamK k = resolve(ka);
   for (uint32_t ci = blockIdx.x; ci < n; ci += gridDim.x) {
     const Entry en = read_entry(&table[ci]);
     const float sc = scale[en.tensor];
@@ -848,8 +874,9 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
 template <int GDT, bool WB, uint32_t U, bool TICKETS, bool LAMB>
 __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
                                                   const float* __restrict__ thresholds, float* __restrict__ norms,
-                                                  float* __restrict__ coefs, int32_t* status, const AdamK k) {
+                                                  float* __restrict__ coefs, int32_t* status, const AdamK ka) {
   __shared__ StepShared sh;
+  const AdamK k = resolve(ka);
   uint32_t ticket;
   if constexpr (TICKETS) {
     // Eight ticket counters, one per XCD: item 8 t + y is the t-th item of list y.  A
@@ -1138,10 +1165,15 @@ hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const fl
   return hipGetLastError();
 }
 
-hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, double lr,
+hipError_t launch_hyper(const bca_adam_device* dev, AdamK* out, hipStream_t stream) {
+  hipLaunchKernelGGL(k_hyper, dim3(1), dim3(64), 0, stream, dev, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, const AdamK& k,
                              float* trust, float* scale, hipStream_t stream) {
   if (n_tensors == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kTrustBlock), 0, stream, sums, tensor_off, lr, trust, scale);
+  hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kTrustBlock), 0, stream, sums, tensor_off, k, trust, scale);
   return hipGetLastError();
 }
 

@@ -401,3 +401,117 @@ def test_profiling_counts_ordinary_calls_only_and_leaves_results_alone(tuning):
     assert all(np.isfinite(x) and x >= 0 for x in ms) and ms[2] > 0
     for a, b in zip(plain, prof):
         assert bits_equal(a, b)
+
+
+# ------------------------------------------------------------------ hyper-parameters and step in device memory
+
+
+def device_hyper(hp, step):
+    return torch.frombuffer(bytearray(B.pack_device_hyper(hyper(hp), step)), dtype=torch.uint8).cuda()
+
+
+def test_hyper_parameters_from_device_memory_in_a_replayed_graph_follow_a_schedule():
+    """One captured fused step is replayed with the step count and the learning rate rewritten in device
+    memory before every replay (the case a captured graph cannot serve with host arguments); the state
+    after four steps matches the oracle run with the same schedule.  The host arguments are ignored."""
+    w = small_bert("multistep")
+    lay = w.layout
+    p, m, v = state_of(w)
+    norms0 = oracle.bucket_norms(lay, w.grads(0))
+    thr = (norms0 * (w.thresholds / 1.024)).astype(np.float32)
+    lrs = [1e-3, 2e-3, 5e-4, 1.5e-3]
+    d = Device(lay, w.grads(0), p, m, v)
+    dthr = d.thresholds(thr)
+    import dataclasses
+    hp_at = [dataclasses.replace(w.hyper, lr=lr) for lr in lrs]
+    dev = device_hyper(hp_at[0], 1)
+    d.plan.set_device_hyper(dev)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    scratch = Device(lay, w.grads(0), p, m, v)                       # warm-up happens on a twin, not on the state under test
+    scratch.plan.set_device_hyper(dev)
+    with torch.cuda.stream(s):
+        scratch.plan.bucket_clip_adam(dthr, None, 0, 0, scratch.norms, scratch.coefs, scratch.status, stream=s)
+        s.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cg, stream=s):
+            d.plan.bucket_clip_adam(dthr, None, 12345, 0, d.norms, d.coefs, d.status, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    op, om, ov = f64(p), f64(m), f64(v)
+    for k in range(4):
+        d.set_grads(w.grads(k))
+        dev.copy_(device_hyper(hp_at[k], k + 1))
+        torch.cuda.synchronize()
+        cg.replay()
+        torch.cuda.synchronize()
+        assert int(d.status.item()) == 0
+        oracle.bucket_clip_adam(lay, w.grads(k), op, om, ov, thr, step=k + 1, **hp_kwargs(hp_at[k]))
+        check_state("p", to_host(d.p), op)
+        check_state("m", to_host(d.m), om)
+        check_state("v", to_host(d.v), ov, strict_rel=True)
+    scratch.close()
+    d.close()
+
+
+def test_hyper_parameters_from_device_memory_every_entry_point_and_back_to_host_arguments():
+    w = small_bert("large")
+    lay = w.layout
+    p, m, v = state_of(w)
+    g = w.grads()
+    norms = oracle.bucket_norms(lay, g)
+    thr = (np.median(norms) * np.ones_like(norms)).astype(np.float32)
+    import dataclasses
+    hp = dataclasses.replace(w.hyper, lr=3e-3, beta1=0.8, beta2=0.99, eps=1e-7, weight_decay=0.02)
+    dev = device_hyper(hp, 9)
+    wrong = hyper(w.hyper)                                             # host arguments that must be ignored
+
+    def fresh():
+        d = Device(lay, g, p, m, v)
+        d.plan.set_device_hyper(dev)
+        return d
+
+    d = fresh()                                                         # adam_step
+    d.plan.adam_step(wrong, 77)
+    d.sync()
+    op, om, ov = f64(p), f64(m), f64(v)
+    oracle.adam_step(lay, g, op, om, ov, step=9, **hp_kwargs(hp))
+    check_state("p", to_host(d.p), op), check_state("v", to_host(d.v), ov, strict_rel=True)
+    d.close()
+
+    for flags in (0, B.BCA_CLIP_WHOLE_GRADIENT, B.BCA_SKIP_STEP_ON_NONFINITE):   # fused Adam: single launch and multi-launch routes
+        d = fresh()
+        nm = torch.zeros(lay.n_buckets + 1, dtype=torch.float32, device="cuda")
+        whole = flags == B.BCA_CLIP_WHOLE_GRADIENT
+        t = d.thresholds(np.asarray([0.5 * float(np.sqrt(np.sum(norms ** 2)))], np.float32) if whole else thr)
+        d.plan.bucket_clip_adam(t, None, 0, flags, nm, d.coefs, d.status)
+        d.sync()
+        op, om, ov = f64(p), f64(m), f64(v)
+        if flags == B.BCA_CLIP_WHOLE_GRADIENT:
+            oracle.whole_clip_adam(lay, g, op, om, ov, 0.5 * float(np.sqrt(np.sum(norms ** 2))), step=9, **hp_kwargs(hp))
+        else:
+            oracle.bucket_clip_adam(lay, g, op, om, ov, thr, step=9, **hp_kwargs(hp))
+        check_state("p", to_host(d.p), op), check_state("m", to_host(d.m), om)
+        check_state("v", to_host(d.v), ov, strict_rel=True)
+        d.close()
+
+    d = fresh()                                                         # LAMB, alone and behind the clip
+    d.plan.lamb_step(None, 0, d.trust)
+    d.sync()
+    op, om, ov = f64(p), f64(m), f64(v)
+    otrust = oracle.lamb_step(lay, g, op, om, ov, step=9, **hp_kwargs(hp))
+    check_norms(d.trust.cpu().numpy()[:lay.n_tensors], otrust)
+    check_state("p", to_host(d.p), op)
+    d.close()
+    d = fresh()
+    d.plan.bucket_clip_lamb(d.thresholds(thr), wrong, 3, 0, d.norms, d.coefs, d.trust, d.status)
+    d.sync()
+    op, om, ov = f64(p), f64(m), f64(v)
+    oracle.bucket_clip_lamb(lay, g, op, om, ov, thr, step=9, **hp_kwargs(hp))
+    check_state("p", to_host(d.p), op), check_state("v", to_host(d.v), ov, strict_rel=True)
+    # back to host arguments
+    d.plan.set_device_hyper(None)
+    d.plan.adam_step(hyper(w.hyper), 10)
+    d.sync()
+    oracle.adam_step(lay, g, op, om, ov, step=10, **hp_kwargs(w.hyper))
+    check_state("p", to_host(d.p), op)
+    d.close()

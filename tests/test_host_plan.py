@@ -224,6 +224,19 @@ def test_argument_errors_come_before_any_launch():
     assert e.value.code == -5
 
 
+def test_device_hyper_parameters_need_a_device_plan_and_pack_to_the_c_struct():
+    import struct
+    p = host_plan(W.layout_one_tensor_per_bucket([8, 8]))
+    with pytest.raises(B.BcaError) as e:
+        p.set_device_hyper(4096)
+    assert e.value.code == -5
+    raw = B.pack_device_hyper(B.AdamHyper(2e-3, 0.8, 0.99, 1e-7, 0.05), 41)
+    assert len(raw) == 48 and struct.unpack("<5dQ", raw) == (2e-3, 0.8, 0.99, 1e-7, 0.05, 41)
+    header = open(os.path.join(ROOT, "include", "bca.h")).read()
+    body = re.search(r"typedef struct bca_adam_device \{(.*?)\} bca_adam_device;", header, re.S).group(1)
+    assert re.sub(r"/\*.*?\*/", "", body, flags=re.S).split() == "double lr, beta1, beta2, eps, weight_decay; uint64_t step;".split()
+
+
 def test_a_device_plan_fails_loudly_without_a_gpu():
     import torch
     if torch.cuda.is_available():
