@@ -146,7 +146,14 @@ struct Grad<BCA_GRAD_F16> {
 #pragma unroll
     for (int q = 0; q < 8; ++q) f[q] = (float)x[q];
   }
-  // fp16 -> fp32 is exact (subnormals included); fp32 -> fp16 rounds to nearest even.
+  // fp16 -> fp32 is exact (subnormals included); fp32 -> fp16 rounds to nearest even.  What is stored is the
+  // fp32 value rounded once more: settled() keeps the compiler from folding the multiplication that made the
+  // value into the conversion (a mixed-precision multiply rounds the exact product to fp16 in one step, which
+  // differs from the two roundings on ties of the fp32 product, about one stored value in a thousand).
+  static __device__ __forceinline__ float settled(float x) {
+    asm volatile("" : "+v"(x));
+    return x;
+  }
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
     const f16x4 h = ldv<NT>(reinterpret_cast<const f16x4*>(base) + vec);
@@ -157,14 +164,14 @@ struct Grad<BCA_GRAD_F16> {
   template <bool NT>
   static __device__ __forceinline__ void store4(void* base, uint32_t vec, f32x4 x) {
     f16x4 h;
-    h.x = (_Float16)x.x, h.y = (_Float16)x.y, h.z = (_Float16)x.z, h.w = (_Float16)x.w;
+    h.x = (_Float16)settled(x.x), h.y = (_Float16)settled(x.y), h.z = (_Float16)settled(x.z), h.w = (_Float16)settled(x.w);
     stv<NT>(reinterpret_cast<f16x4*>(base) + vec, h);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
     return (float)reinterpret_cast<const _Float16*>(base)[i];
   }
   static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
-    reinterpret_cast<_Float16*>(base)[i] = (_Float16)x;
+    reinterpret_cast<_Float16*>(base)[i] = (_Float16)settled(x);
   }
 };
 

@@ -149,7 +149,7 @@ def run_lamb(layout, g, p, m, v, thr, hp, step, flags=0, offsets=None, decay=Non
            "v": check_state("v", to_host(dev.v), ov, strict_rel=True)}
     gg = to_host(dev.g)
     if thr is not None and flags & B.BCA_WRITE_BACK_GRADS:
-        check_scaled_grads(gg, og, g)
+        check_scaled_grads(gg, og, g, layout, dev.coefs.cpu().numpy())
     else:
         assert bits_equal(gg, g), "gradients must not be written without BCA_WRITE_BACK_GRADS"
     dev.close()
