@@ -34,7 +34,7 @@ def run_fused(layout, g, p, m, v, thr, hp, step, flags=0, offsets=None, decay=No
     out = {"norm_rel": check_norms(dev.norms.cpu().numpy(), onorm)}
     gcoef = dev.coefs.cpu().numpy()
     assert np.all(gcoef > 0) and np.all(gcoef <= 1)
-    assert np.allclose(gcoef, ocoef, rtol=2e-5, atol=0)
+    assert np.allclose(gcoef, ocoef, rtol=1e-6, atol=0)
     assert int(dev.status.item()) == ost
     out["p"] = check_state("p", to_host(dev.p), op)
     out["m"] = check_state("m", to_host(dev.m), om)
@@ -94,7 +94,7 @@ def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=Tr
     dev.sync()
     assert stat == ost
     gcoef = dev.coefs.cpu().numpy()
-    assert np.allclose(gcoef, ocoef, rtol=2e-5, atol=0)
+    assert np.allclose(gcoef, ocoef, rtol=1e-6, atol=0)
     og = type(g)(x.copy() for x in g)
     oracle.bucket_scale(layout, og, ocoef)
     check_scaled_grads(to_host(dev.g), og, g, layout, gcoef)

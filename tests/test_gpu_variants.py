@@ -142,7 +142,7 @@ def run_lamb(layout, g, p, m, v, thr, hp, step, flags=0, offsets=None, decay=Non
                                                             write_back=bool(flags & B.BCA_WRITE_BACK_GRADS),
                                                             decay=decay, **hp_kwargs(hp))
         check_norms(dev.norms.cpu().numpy(), onorm)
-        assert np.allclose(dev.coefs.cpu().numpy(), ocoef, rtol=2e-5, atol=0)
+        assert np.allclose(dev.coefs.cpu().numpy(), ocoef, rtol=1e-6, atol=0)
         assert int(dev.status.item()) == ost
     check_trust(dev.trust.cpu().numpy()[:nt], otrust)
     out = {"p": check_state("p", to_host(dev.p), op), "m": check_state("m", to_host(dev.m), om),
