@@ -478,7 +478,7 @@ def random_layout(rng):
     return W._mk_layout(numels, buckets), numels
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", list(range(12)) + [57])     # 57: a coefficient of exactly 0.5 on subnormal fp16 values (rounding ties)
 def test_random_layouts_all_modes(seed):
     rng = np.random.default_rng(1000 + seed)
     lay, numels = random_layout(rng)
