@@ -375,8 +375,9 @@ __global__ __launch_bounds__(kBlock) void k_lbs_local(const Params P, const uint
   publish_sums(sums, sum_lo, sum_hi);
 }
 
-// Inclusive running sum over the workgroup of one value per thread (s_scan: kWaves words); all
-// threads call it.  Within a wavefront by shuffles, across the four wavefronts through LDS: two barriers.
+// Inclusive running sum over the workgroup of one value per thread; all threads call it.  Within a wavefront
+// by shuffles, across the four wavefronts through s_scan (kWaves words): one barrier.  The caller leaves s_scan
+// alone until the workgroup has passed another barrier (each use in a trial has words of its own).
 __device__ __forceinline__ uint32_t block_running_sum(uint32_t* s_scan, uint32_t value) {
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   uint32_t x = value;
@@ -389,7 +390,6 @@ __device__ __forceinline__ uint32_t block_running_sum(uint32_t* s_scan, uint32_t
   __syncthreads();
   uint32_t before = 0;
   for (uint32_t w = 0; w < wave; ++w) before += s_scan[w];
-  __syncthreads();  // s_scan may be written again right after
   return x + before;
 }
 
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
                                                         const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                         uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, guide table, the trial's own histogram, (SPREAD) one word per GPU
-  __shared__ uint32_t s_scan[kWaves];
+  __shared__ uint32_t s_scan[2][kWaves];
   __shared__ uint32_t s_base;
   __shared__ Finish s_finish;
   const uint32_t* s_guide = load_tables(s_dyn, P, cum, guide);
@@ -433,7 +433,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
     // running sum over lengths: a thread owns a contiguous piece, the pieces' sums are combined across threads
     uint32_t piece = 0;
     for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
-    uint32_t run = block_running_sum(s_scan, piece) - piece;  // draws with a length below this thread's piece
+    uint32_t run = block_running_sum(s_scan[0], piece) - piece;  // draws with a length below this thread's piece
     uint32_t lo = 0xffffffffu, hi = 0u;
     if (SPREAD) {
       uint32_t whole_turns = 0;
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(kBlock) void k_lbs_global(const Params P, const uin
       __syncthreads();
       uint32_t mine = 0;
       for (uint32_t g = ga; g < gb; ++g) mine += s_gpu[g];
-      uint32_t tokens = block_running_sum(s_scan, mine) - mine + s_base;  // ... of the GPU before this thread's first
+      uint32_t tokens = block_running_sum(s_scan[1], mine) - mine + s_base;  // ... of the GPU before this thread's first
       for (uint32_t g = ga; g < gb; ++g) {
         tokens += s_gpu[g];
         lo = min(lo, tokens), hi = max(hi, tokens);
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) v
                                                      const uint32_t* __restrict__ guide, uint32_t* trial_min,
                                                      uint32_t* trial_max, unsigned long long* sums) {
   extern __shared__ uint32_t s_dyn[];  // histogram, all guide tables, the trial's own histogram, one word per GPU
-  __shared__ uint32_t s_scan[kWaves];
+  __shared__ uint32_t s_scan[2][kWaves];
   __shared__ uint32_t s_base;
   __shared__ FinishAll s_fin;
   __shared__ unsigned long long s_sum[2u * kMethods];  // the workgroup's share of the sums, kept by thread 0
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) v
     {
       uint32_t piece = 0;
       for (uint32_t i = a; i < b; ++i) piece += s_cnt[i];
-      uint32_t run = block_running_sum(s_scan, piece) - piece;
+      uint32_t run = block_running_sum(s_scan[0], piece) - piece;
       uint32_t whole_turns = 0;
       for (uint32_t l = a; l < b; ++l) {
         const uint32_t n = s_cnt[l];
@@ -577,7 +577,7 @@ __global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) v
       __syncthreads();
       uint32_t mine = 0;
       for (uint32_t g = ga; g < gb; ++g) mine += s_gpu[g];
-      uint32_t tokens = block_running_sum(s_scan, mine) - mine + s_base;
+      uint32_t tokens = block_running_sum(s_scan[1], mine) - mine + s_base;
       for (uint32_t g = ga; g < gb; ++g) {
         tokens += s_gpu[g];
         lo[LBS_GLOBAL] = min(lo[LBS_GLOBAL], tokens), hi[LBS_GLOBAL] = max(hi[LBS_GLOBAL], tokens);
