@@ -501,9 +501,9 @@ __global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) v
   __shared__ uint32_t s_scan[2][kWaves];
   __shared__ uint32_t s_base;
   __shared__ FinishAll s_fin;
-  __shared__ unsigned long long s_sum[2u * kMethods];  // the workgroup's share of the sums, kept by thread 0
+  __shared__ unsigned long long s_sum[2u * kMethods];  // the workgroup's share of the sums: thread i keeps sum i
   const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
-  if (tid < 2u * kMethods) s_sum[tid] = 0ull;  // thread 0 first touches them after the first trial's barriers
+  if (tid < 2u * kMethods) s_sum[tid] = 0ull;
   uint32_t* s_whole = s_dyn + P.max_len + 1u;          // guide table of the whole dataset
   uint32_t* s_strata = s_whole + kWholeGuideSize;      // guide tables of the strata
   uint32_t* s_cnt = s_whole + P.guide_words;
@@ -622,21 +622,20 @@ __global__ __launch_bounds__(kBlock, E <= 2 ? 6 : E == 4 ? 4 : E == 8 ? 3 : 2) v
       if (lane == 0) s_fin.lo[buf][q][wave] = lo[q], s_fin.hi[buf][q][wave] = hi[q];
     }
     __syncthreads();  // also: this trial's last reads of s_cnt and s_gpu lie before the next trial's clearing
-    if (tid == 0) {
-#pragma unroll
-      for (uint32_t q = 0; q < kMethods; ++q) {
-        const uint32_t l = min(min(s_fin.lo[buf][q][0], s_fin.lo[buf][q][1]), min(s_fin.lo[buf][q][2], s_fin.lo[buf][q][3]));
-        const uint32_t h = max(max(s_fin.hi[buf][q][0], s_fin.hi[buf][q][1]), max(s_fin.hi[buf][q][2], s_fin.hi[buf][q][3]));
-        if (trial_min) trial_min[(size_t)q * P.n_trials + t] = l;
-        if (trial_max) trial_max[(size_t)q * P.n_trials + t] = h;
-        s_sum[2u * q] += l, s_sum[2u * q + 1u] += h;
+    if (tid < 2u * kMethods) {  // thread 2 q: method q's minimum; thread 2 q + 1: its maximum
+      const uint32_t q = tid >> 1;
+      uint32_t r;
+      if (tid & 1u) {
+        r = max(max(s_fin.hi[buf][q][0], s_fin.hi[buf][q][1]), max(s_fin.hi[buf][q][2], s_fin.hi[buf][q][3]));
+        if (trial_max) trial_max[(size_t)q * P.n_trials + t] = r;
+      } else {
+        r = min(min(s_fin.lo[buf][q][0], s_fin.lo[buf][q][1]), min(s_fin.lo[buf][q][2], s_fin.lo[buf][q][3]));
+        if (trial_min) trial_min[(size_t)q * P.n_trials + t] = r;
       }
+      s_sum[tid] += r;
     }
   }
-  if (tid == 0) {
-#pragma unroll
-    for (uint32_t q = 0; q < 2u * kMethods; ++q) atomicAdd(&sums[q], s_sum[q]);
-  }
+  if (tid < 2u * kMethods) atomicAdd(&sums[tid], s_sum[tid]);
 }
 
 __global__ __launch_bounds__(64) void k_lbs_clear_all(unsigned long long* sums) {
