@@ -211,13 +211,13 @@ def lbs_bench(a, dev):
         cpu = {"value": round(5 * n_cpu * G * b / dt / 1e6, 2), "unit": "M draws/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} trials of each of the five methods, same setting, single thread"}
     # The step is one kernel, k_lbs_all.  Vector instructions it executes, from a rocprofv3 --pmc SQ_INSTS_VALU run of
-    # this command (profiles/lbs_table5_setting_kernel_stats.txt): 4.215e9 wavefront instructions per 100 000 trials at
-    # 1 024 GPUs, i.e. 2 x 1.638e9 draws made (one set from the whole dataset, one stratified) = 82.3 lane-operation
+    # this command (profiles/lbs_table5_setting_kernel_stats.txt): 4.235e9 wavefront instructions per 100 000 trials at
+    # 1 024 GPUs, i.e. 2 x 1.638e9 draws made (one set from the whole dataset, one stratified) = 82.7 lane-operation
     # slots per draw made (64 lanes per instruction).  Peak: a SIMD issues a 64-lane move, add or xor in 2 cycles and
     # a multiply, minimum or median in 4 (measured); the bound taken is every instruction at the faster rate,
     # 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-operations/s, which is also the rate behind the chip's
     # 157.3 TFLOP/s of fp32 vector FMAs.
-    ops_per_draw_made = 82.3
+    ops_per_draw_made = 82.7
     draws_made = 2 * n * G * b
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)

@@ -77,8 +77,8 @@ def test_degenerate_dataset_single_gpu_zero_trials_and_fig3_quota():
 
 @pytest.mark.parametrize("method", [lbs.LBS_NONE, lbs.LBS_STRATIFIED, lbs.LBS_LOCAL_RASTER, lbs.LBS_LOCAL_SNAKE, lbs.LBS_GLOBAL])
 def test_more_trials_than_workgroups_so_that_each_runs_several(method):
-    # a call launches at most 32 workgroups per compute unit; beyond that a workgroup runs trials in turn
-    n = 256 * 32 * 2 + 123
+    # a call launches at most 128 workgroups per compute unit; beyond that a workgroup runs trials in turn
+    n = 256 * 128 * 2 + 123
     check(CUM, ENDS, method, 4, 2 if method != lbs.LBS_LOCAL_SNAKE else 3, 12, [1, 1, 1, 1], seed=31, n=n, first=7)
 
 
@@ -92,7 +92,7 @@ def test_full_size_run_as_benchmarked_sampled_trials_and_sums(method):
         gmin, gmax, g0, g1 = run_gpu(ds, method, 16, 8, G, quota, 2024, n)
     assert g0 == int(gmin.astype(np.uint64).sum()) and g1 == int(gmax.astype(np.uint64).sum())
     rng = np.random.default_rng(77 + method)
-    for t in [0, 1, n - 1, 8191, 8192] + [int(x) for x in rng.integers(0, n, 25)]:
+    for t in [0, 1, n - 1, 32767, 32768] + [int(x) for x in rng.integers(0, n, 25)]:
         omin, omax, _, _ = O.simulate(CUM, ENDS, quota, 16, 8, G, method, 2024, 1, first_trial=t)
         assert (int(gmin[t]), int(gmax[t])) == (int(omin[0]), int(omax[0])), (method, t)
 
@@ -206,7 +206,7 @@ def test_all_methods_in_one_pass_paper_setting_and_other_register_counts():
     check_all(CUM, ENDS, 32, 32, 64, [8, 8, 8, 8], seed=14, n=5)                            # pool of 1024
     check_all(CUM, ENDS, 1, 1, 7, [0, 1, 0, 0], seed=15, n=9)                               # one draw per GPU, one GPU per node
     check_all(CUM, ENDS, 2, 2, 8192, [1, 0, 0, 1], seed=16, n=3)                            # the most GPUs the one pass takes
-    check_all(CUM, ENDS, 4, 2, 12, [1, 1, 1, 1], seed=17, n=256 * 32 + 77, first=5)         # workgroups run several trials
+    check_all(CUM, ENDS, 4, 2, 12, [1, 1, 1, 1], seed=17, n=256 * 128 + 77, first=5)        # workgroups run several trials
 
 
 def test_all_methods_falls_back_to_one_method_at_a_time():
