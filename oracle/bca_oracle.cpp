@@ -419,7 +419,7 @@ int32_t orc_bucket_clip_lamb(uint32_t n_tensors, const uint64_t* tensor_numel, u
   if (coefs_out) std::memcpy(coefs_out, coefs, sizeof(float) * n_buckets);
 
   double** ghat = new double*[n_tensors ? n_tensors : 1];
-  for (uint32_t t = 0; t < n_tensors; ++t) ghat[t] = new double[tensor_numel[t] ? tensor_numel[t] : 1];
+  for (uint32_t t = 0; t < n_tensors; ++t) ghat[t] = new double[tensor_numel[t] ? tensor_numel[t] : 1]();  // zeros where no segment writes
   for (uint32_t b = 0; b < n_buckets; ++b)
     for (uint64_t k = bucket_seg_off[b]; k < bucket_seg_off[b + 1]; ++k) {
       const uint32_t t = seg_tensor[k];
