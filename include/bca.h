@@ -204,9 +204,19 @@ int bucket_clip_apply(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thr
  * launch, for the paper's use of the method: a bucket is clipped as soon as backward
  * has produced it, before its all-reduce (Sec. 4.2, Alg. 1).  Same norms, coefficients
  * and scaled gradients, bit for bit.  norms / coefs (DEVICE [B], entries b0..b1-1
- * written) and status (DEVICE int32, written) may each be NULL. */
+ * written) and status (DEVICE int32, written: BCA_STATUS_NONFINITE, _BAD_THRESHOLD as in
+ * bucket_clip_apply, and BCA_STATUS_TIMEOUT as in bucket_clip_adam) may each be NULL. */
 int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thresholds /*DEVICE [B]*/, float* norms,
                 float* coefs, int32_t* status, void* stream);
+
+/* The per-bucket thresholds Alg. 1 (App. B) compares with: out[b] = c / sqrt(n_buckets) for every b,
+ * evaluated in fp64 and rounded once to fp32.  The algorithm's test and assignment both
+ * divide by sqrt(B); the sentence above it says "divided by B", which is not followed:
+ * only the square root gives sum_b ||G_b||^2 <= c^2, i.e. a clipped whole-gradient norm of
+ * at most c, which is the stated purpose.  out is a HOST array; the compute calls take
+ * thresholds from DEVICE memory, so the caller uploads it.  BCA_ERR_NULL for out == NULL
+ * with n_buckets > 0; BCA_ERR_HPARAM unless c > 0 (Inf allowed: never clips). */
+int bca_alg1_thresholds(double c, uint32_t n_buckets, float* out /*HOST [n_buckets]*/);
 
 /* theta <- ADAM(theta, eta, G) over every tensor of the plan, reading the
  * gradients as stored (Alg. 1, last line).  Adam as published by Kingma & Ba
@@ -215,12 +225,15 @@ int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* threshold
  *   p <- p - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + wd * p ). */
 int adam_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, void* stream);
 
-/* The fused step: norms and clip factors of all buckets, then one sweep that
- * forms ghat = coef_b * g in registers and applies Adam to it.  g is read, not
- * written, unless BCA_WRITE_BACK_GRADS.  norms / coefs (DEVICE [B]) and status
- * (DEVICE int32) may each be NULL.  With BCA_SKIP_STEP_ON_NONFINITE or
- * BCA_CLIP_WHOLE_GRADIENT all norms are computed before any update (no
- * pipelining of bucket groups). */
+/* The fused step: one iteration's loop body of Alg. 1 (App. B) without its all-reduce --
+ * for every bucket the test ||G_b|| >= c_b and the assignment G_b <- c_b G_b / ||G_b||
+ * (clipping-by-norm, Sec. 2.3, per bucket, Sec. 4.2), then theta <- ADAM(theta, eta, G)
+ * on G = [G_1 ... G_B] (the algorithm's last line) -- as norms and clip factors of all
+ * buckets followed by one sweep that forms ghat = coef_b * g in registers and applies
+ * Adam to it.  g is read, not written, unless BCA_WRITE_BACK_GRADS.  norms / coefs
+ * (DEVICE [B]) and status (DEVICE int32, BCA_STATUS_* bits of this call) may each be
+ * NULL.  With BCA_SKIP_STEP_ON_NONFINITE or BCA_CLIP_WHOLE_GRADIENT all norms are
+ * computed before any update (no pipelining of bucket groups). */
 int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
                      uint64_t step, uint32_t flags, float* norms, float* coefs, int32_t* status, void* stream);
 

@@ -31,7 +31,8 @@
 // no fp32 rounding on the oracle's side.
 //
 // Parity pins: every function here is pinned by tests/test_oracle_*.py against
-// closed forms, invariants, brute force and library routines.  The values that
+// closed forms, invariants, brute force and library routines (orc_compare_f32, the
+// acceptance rule of the GPU tests, by tests/test_oracle_compare.py).  The values that
 // propagate from non-finite gradients are "parity unpinned" (NaN != NaN); only
 // the status flag and the skip mode are pinned.
 

@@ -690,6 +690,14 @@ int bca_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream) {
   return BCA_OK;
 }
 
+int bca_alg1_thresholds(double c, uint32_t n_buckets, float* out) {
+  if (n_buckets && !out) return fail(BCA_ERR_NULL, "out is NULL");
+  if (!(c > 0.0)) return fail(BCA_ERR_HPARAM, "the clipping threshold c must be positive");
+  const float each = (float)(c / std::sqrt((double)n_buckets));
+  for (uint32_t b = 0; b < n_buckets; ++b) out[b] = each;
+  return BCA_OK;
+}
+
 int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   if (int rc = check_range(p, b0, b1)) return rc;

@@ -122,7 +122,7 @@ def run_unfused(layout, g, p, m, v, thr, hp, step, offsets=None, split_ranges=Tr
     op, om, ov = f64(p), f64(m), f64(v)
     oracle.adam_step(layout, og, op, om, ov, step=step, decay=decay, **hp_kwargs(hp))
     out = {"p": check_state("p", to_host(dev.p), op), "m": check_state("m", to_host(dev.m), om),
-           "v": check_state("v", to_host(dev.v), ov, strict_rel=(g[0].dtype == np.float32))}
+           "v": check_state("v", to_host(dev.v), ov, strict_rel=True)}
     dev.close()
     return out
 

@@ -38,7 +38,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     L = B.load_library()
     header = open(os.path.join(ROOT, "include", "bca.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(bca_[a-z_]+|bucket_clip_[a-z]+|bucket_clip|adam_step|lamb_step)\s*\(", header))
+    declared = set(re.findall(r"\b(bca_[a-z0-9_]+|bucket_clip_[a-z]+|bucket_clip|adam_step|lamb_step)\s*\(", header))
     assert {"bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
             "bucket_clip_lamb", "bca_plan_set_decay_mask"} <= declared
     assert declared == set(binding.EXPORTS)
@@ -246,9 +246,25 @@ def test_a_device_plan_fails_loudly_without_a_gpu():
     assert e.value.code == -6
 
 
-def test_alg1_threshold_helper():
+def test_alg1_thresholds_come_from_the_library():
+    """Alg. 1 compares every bucket with c / sqrt(B) (not c / B): evaluated by the C export, the binding forwards."""
     thr = B.alg1_thresholds(1.0, 16)
     assert thr.dtype == np.float32 and thr.shape == (16,) and np.all(thr == np.float32(0.25))
+    assert np.all(B.alg1_thresholds(3.0, 9) == np.float32(1.0))
+    thr = B.alg1_thresholds(1.0, 1279)
+    assert np.all(thr == np.float32(1.0 / np.sqrt(np.float64(1279))))
+    assert float(np.sum(thr.astype(np.float64) ** 2)) == pytest.approx(1.0, rel=1e-6)      # sum_b c_b^2 = c^2
+    assert np.all(np.isinf(B.alg1_thresholds(float("inf"), 4)))
+    assert B.alg1_thresholds(1.0, 0).shape == (0,)
+    L = B.load_library()
+    for bad in (0.0, -1.0, float("nan")):
+        with pytest.raises(B.BcaError) as e:
+            B.alg1_thresholds(bad, 4)
+        assert e.value.code == -4
+    assert L.bca_alg1_thresholds(1.0, 4, None) == -1
+    # the oracle's helper, written separately, agrees
+    import oracle
+    assert np.float32(oracle.alg1_threshold(1.0, 1279)) == thr[0]
 
 
 @pytest.mark.parametrize("chunk", [1024, 4096])

@@ -15,7 +15,8 @@ from oracle import build as obuild
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PIN_TESTS = ["tests/test_oracle_half.py", "tests/test_oracle_norm_clip.py", "tests/test_oracle_adam.py",
-             "tests/test_oracle_whole_clip.py", "tests/test_oracle_bf16.py", "tests/test_oracle_lamb.py"]
+             "tests/test_oracle_whole_clip.py", "tests/test_oracle_bf16.py", "tests/test_oracle_lamb.py",
+             "tests/test_oracle_compare.py"]
 
 MUTANTS = [
     ("norm: sum of |x| instead of squares", "s += x * x;", "s += std::fabs(x);"),
@@ -84,6 +85,27 @@ MUTANTS = [
     ("clip+lamb: one coefficient for all buckets", "ghat[t][i] = static_cast<double>(coefs[b]) * load_grad(grads[t], gdt, i);", "ghat[t][i] = static_cast<double>(coefs[0]) * load_grad(grads[t], gdt, i);"),
     ("clip+lamb: write-back always on", "if (write_back && coefs[b] != 1.0f) store_scaled_grad(grads[t], gdt, i, coefs[b]);\n      }\n    }\n  const Adam h_all", "if (coefs[b] != 1.0f) store_scaled_grad(grads[t], gdt, i, coefs[b]);\n      }\n    }\n  const Adam h_all"),
     ("fused: wrong tensor for state", "adam_element(ghat, p[t][i], m[t][i], v[t][i], h, bc1, bc2);", "adam_element(ghat, p[t][i], v[t][i], m[t][i], h, bc1, bc2);"),
+    # the acceptance rule that every GPU parity assertion goes through
+    ("compare: absolute clause joined by 'or'", "ok = (rel <= rel_tol) || (aw < small && err <= abs_tol);",
+     "ok = (rel <= rel_tol) || (aw < small || err <= abs_tol);"),
+    ("compare: 'small' bound ignored", "ok = (rel <= rel_tol) || (aw < small && err <= abs_tol);",
+     "ok = (rel <= rel_tol) || (err <= abs_tol);"),
+    ("compare: absolute clause also at |oracle| == small", "ok = (rel <= rel_tol) || (aw < small && err <= abs_tol);",
+     "ok = (rel <= rel_tol) || (aw <= small && err <= abs_tol);"),
+    ("compare: strict relative bound", "ok = (rel <= rel_tol) || (aw < small && err <= abs_tol);",
+     "ok = (rel < rel_tol) || (aw < small && err <= abs_tol);"),
+    ("compare: strict absolute bound", "ok = (rel <= rel_tol) || (aw < small && err <= abs_tol);",
+     "ok = (rel <= rel_tol) || (aw < small && err < abs_tol);"),
+    ("compare: relative error against the GPU value", "const double rel = aw > 0.0 ? err / aw :", "const double rel = aw > 0.0 ? err / std::fabs(g) :"),
+    ("compare: signs ignored", "const double err = std::fabs(g - w), aw = std::fabs(w);", "const double err = std::fabs(std::fabs(g) - std::fabs(w)), aw = std::fabs(w);"),
+    ("compare: one NaN is enough", "ok = std::isnan(w) && std::isnan(g);", "ok = std::isnan(w) || std::isnan(g);"),
+    ("compare: infinities always pass", "ok = (w == g);", "ok = true;"),
+    ("compare: failures counted once", "      ++bad;\n      if (worst < 0)", "      bad = 1;\n      if (worst < 0)"),
+    ("compare: worst element is the first failure", "if (!ok && err > worst_err) {", "if (!ok && worst_err < 0) {"),
+    ("compare: max_rel_all leaves out values below 'small'", "if (aw > tiny && rel > max_rel_all) max_rel_all = rel;",
+     "if (aw >= small && rel > max_rel_all) max_rel_all = rel;"),
+    ("compare: 'tiny' bound ignored", "if (aw > tiny && rel > max_rel_all) max_rel_all = rel;", "if (rel > max_rel_all) max_rel_all = rel;"),
+    ("compare: zero oracle value has zero relative error", "(err == 0.0 ? 0.0 : INFINITY)", "0.0"),
 ]
 
 
