@@ -53,8 +53,12 @@ typedef struct bca_plan bca_plan; /* opaque */
 /* bits of the device status word written by the clip calls */
 #define BCA_STATUS_NONFINITE 1     /* some bucket's sum of squares is Inf or NaN          */
 #define BCA_STATUS_BAD_THRESHOLD 2 /* some threshold is <= 0 or NaN: that bucket not clipped */
-#define BCA_STATUS_TIMEOUT 4       /* a bounded wait inside the fused step expired; the step is
-                                      incomplete (never seen unless the GPU is wedged)         */
+#define BCA_STATUS_TIMEOUT 4       /* a bounded wait inside a pipelined launch expired; the work it
+                                      held back was carried out by the call's finish kernel: the
+                                      result is complete and the same bits, the call was only slow */
+#define BCA_STATUS_INCOMPLETE 8    /* a work item could not be carried out at all: p, m, v (or g) are
+                                      partly updated.  Cannot happen by construction; reported
+                                      rather than assumed                                       */
 
 /* flags of bucket_clip_adam */
 #define BCA_WRITE_BACK_GRADS 1u       /* also store the scaled gradient into g (what Alg. 1
@@ -120,9 +124,11 @@ typedef struct bca_tuning {
                             each workgroup reserves without using them, which caps the workgroups resident
                             per compute unit (160 KiB each) -- the sweep streams fastest with few
                             wavefronts in flight.  0: default (48 KiB); 1: none; at most 65536       */
-  uint32_t spin_limit;   /* fused calls: polls of a bucket's ready word after which a waiting work item gives
-                            up and BCA_STATUS_TIMEOUT is reported; 0: default (2^18, about a second).  Small
-                            values exist for tests of that path: every kernel still ends normally        */
+  uint32_t spin_limit;   /* pipelined calls (bucket_clip_adam, bucket_clip_lamb, bucket_clip): polls of a bucket's
+                            ready word after which a waiting work item gives up, is handed to the call's finish
+                            kernel and BCA_STATUS_TIMEOUT is reported; 0: default (2^18, about a second).  Small
+                            values exist for tests of that path: every kernel still ends normally and the
+                            result is the same                                                            */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */
@@ -262,7 +268,8 @@ int bucket_clip_lamb(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, con
  * frees the events).  Calls with BCA_SKIP_STEP_ON_NONFINITE or BCA_CLIP_WHOLE_GRADIENT
  * are not recorded.  bca_plan_profile_read waits for the recorded events and
  * returns the summed duration of each kernel in milliseconds in ms[0..2] and the
- * number of calls summed in *n_calls, then starts a new series. */
+ * number of calls summed in *n_calls, then starts a new series.  The single pipelined
+ * launch (the default) reports its step kernel in ms[2] and its finish kernel in ms[0]. */
 int bca_plan_profile(bca_plan* plan, uint32_t max_calls);
 int bca_plan_profile_read(bca_plan* plan, double* ms /*HOST [3]*/, uint32_t* n_calls /*HOST*/);
 

@@ -18,7 +18,7 @@ BCA_GRAD_F32, BCA_GRAD_F16, BCA_GRAD_BF16 = 0, 1, 2
 BCA_STATUS_NONFINITE, BCA_STATUS_BAD_THRESHOLD = 1, 2
 BCA_WRITE_BACK_GRADS, BCA_SKIP_STEP_ON_NONFINITE, BCA_CLIP_WHOLE_GRADIENT = 1, 2, 4
 BCA_TUNE_MULTI_LAUNCH, BCA_TUNE_STAGE_TABLE_LDS, BCA_TUNE_TICKETS = 1, 2, 4
-BCA_STATUS_TIMEOUT = 4
+BCA_STATUS_TIMEOUT, BCA_STATUS_INCOMPLETE = 4, 8
 BCA_TABLE_NORM, BCA_TABLE_APPLY, BCA_TABLE_LAMB = 0, 1, 2
 
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
@@ -274,7 +274,8 @@ class Plan:
         _check(self._L.bca_plan_profile(self._h, max_calls))
 
     def profile_read(self):
-        """(ms_sqnorm, ms_finalize, ms_adam) summed over n_calls, and n_calls."""
+        """(ms_sqnorm, ms_finalize, ms_adam) summed over n_calls, and n_calls; with the single pipelined launch
+        (ms_finish_kernel, 0, ms_step_kernel)."""
         ms = (C.c_double * 3)()
         n = C.c_uint32()
         _check(self._L.bca_plan_profile_read(self._h, ms, C.byref(n)))

@@ -238,7 +238,8 @@ void free_device(bca_plan* p) {
   if (p->d_arrived) (void)hipFree(p->d_arrived);
   if (p->d_ready) (void)hipFree(p->d_ready);
   if (p->d_ctl) (void)hipFree(p->d_ctl);
-  p->d_work = nullptr, p->d_arrived = nullptr, p->d_ready = nullptr, p->d_ctl = nullptr;
+  if (p->d_skipped) (void)hipFree(p->d_skipped);
+  p->d_work = nullptr, p->d_arrived = nullptr, p->d_ready = nullptr, p->d_ctl = nullptr, p->d_skipped = nullptr;
   if (p->d_partials) (void)hipFree(p->d_partials);
   if (p->d_norms) (void)hipFree(p->d_norms);
   if (p->d_bucket_sq) (void)hipFree(p->d_bucket_sq);
@@ -300,6 +301,7 @@ StepState step_state(const bca_plan* p) {
   ss.norm_tab = p->norm_tab.d_chunks, ss.apply_tab = p->apply_tab.d_chunks;
   ss.norm_bucket_off = p->norm_tab.d_bucket_off;
   ss.partials = p->d_partials, ss.arrived = p->d_arrived, ss.ready = p->d_ready, ss.ctl = p->d_ctl;
+  ss.skipped = p->d_skipped, ss.skipped_cap = (uint32_t)std::max<size_t>(p->apply_tab.chunks.size(), 1);
   ss.apply_to_lamb = p->d_apply_to_lamb, ss.lamb_sums = p->d_lamb_sums;
   ss.spin_limit = p->spin_limit;
   return ss;
@@ -474,6 +476,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
     const size_t nb = n_buckets;
     const size_t nl = std::max<size_t>(p->lamb_tab.chunks.size(), 1), nt = std::max<size_t>(n_tensors, 1);
     const std::vector<uint32_t> a2l = apply_to_lamb_map(p);
+    const uint32_t first_epoch = 1;  // ready words start at zero: epoch 0 is never current
     if ((e = alloc_table(&p->norm_tab, n_buckets)) != hipSuccess ||
         (e = alloc_table(&p->apply_tab, n_buckets)) != hipSuccess ||
         (e = alloc_table(&p->lamb_tab, n_buckets)) != hipSuccess ||
@@ -495,6 +498,9 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
         (e = hipMemset(p->d_ready, 0, nb * sizeof(unsigned long long))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_ctl, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMemset(p->d_ctl, 0, kCtlWords * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMemcpy(p->d_ctl + kCtlEpoch, &first_epoch, sizeof first_epoch, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMalloc((void**)&p->d_skipped, std::max<size_t>(p->apply_tab.chunks.size(), 1) * sizeof(uint32_t))) !=
+            hipSuccess ||
         (e = hipMalloc((void**)&p->d_partials, np * sizeof(double))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_norms, (nb + 1) * sizeof(float))) != hipSuccess ||
         (e = hipMalloc((void**)&p->d_bucket_sq, nb * sizeof(double))) != hipSuccess ||
@@ -672,8 +678,9 @@ int bca_plan_profile_read(bca_plan* p, double* ms, uint32_t* n_calls) {
     for (size_t k = 0; k + 1 < per_call && e == hipSuccess; ++k) {
       float t = 0.f;
       e = hipEventElapsedTime(&t, ev[k], ev[k + 1]);
-      // multi-launch: squared norm, finalize, Adam in turn; single launch: prepare, then the step kernel
-      ms[per_call == 3 ? (k == 0 ? 0 : 2) : k % 3] += t;
+      // multi-launch: squared norm, finalize, Adam in turn; single launch: the step kernel (ms[2]), then the
+      // finish kernel (ms[0])
+      ms[per_call == 3 ? (k == 0 ? 2 : 0) : k % 3] += t;
     }
     if (e != hipSuccess) return fail_hip(e, "reading profile events");
   }
@@ -799,10 +806,10 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     ev = &p->prof_events[(size_t)p->prof_calls++ * per_call];
 
   if (!multi && !skip) {
-    // One launch for the whole step (plus the tiny reset kernel).
+    // One launch for the whole step (plus the small finish kernel behind it).
     const StepState ss = step_state(p);
     if (ev) (void)hipEventRecord(ev[0], s);
-    hipError_t e = launch_step(p->grad_dtype, ss, p->n_buckets, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cf,
+    hipError_t e = launch_step(p->grad_dtype, ss, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cf,
                                st, (flags & BCA_WRITE_BACK_GRADS) != 0, k, p->unroll_apply,
                                (p->tune_flags & BCA_TUNE_TICKETS) != 0, false, ev ? ev[1] : nullptr, s);
     if (e != hipSuccess) return fail_hip(e, "launching the fused step kernel");
@@ -865,7 +872,7 @@ static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     if (!(p->tune_flags & BCA_TUNE_MULTI_LAUNCH)) {
       // squared norms, coefficients and LAMB's first sweep as one pipelined launch (the fused Adam step's
       // work list and waiting scheme; the first sweep's second read of the gradients is served from cache)
-      e = launch_step(p->grad_dtype, step_state(p), p->n_buckets, p->d_work, (uint32_t)p->work.size(), thresholds, nm, cw,
+      e = launch_step(p->grad_dtype, step_state(p), p->d_work, (uint32_t)p->work.size(), thresholds, nm, cw,
                       st, (flags & BCA_WRITE_BACK_GRADS) != 0, k, 1, false, true, nullptr, s);
       if (e != hipSuccess) return fail_hip(e, "launching the fused clip + LAMB moments kernel");
     } else {

@@ -86,10 +86,22 @@ struct Launch {
                     // how many workgroups a compute unit holds at once
 };
 
-// Device-side state of the single-launch fused step (k_prepare / k_step).
+// Device-side state of the pipelined launches (k_step / k_clip, each followed by its finish kernel).
 // Control words, each in its own 128-byte line: eight ticket counters (one per XCD) at
-// kCtlTicket + 32 y, the epoch, the abort flag.
-enum : uint32_t { kCtlTicket = 0, kCtlEpoch = 256, kCtlAbort = 288, kCtlWords = 320 };
+// kCtlTicket + 32 y; the epoch (number of the current call, never 0); the abort flag; the number
+// of work items whose wait expired (their indices are in StepState::skipped); the status bits
+// collected during the call; the arrival counter of the finish kernel's workgroups.  The finish
+// kernel of a call leaves all of them ready for the next call.
+enum : uint32_t {
+  kCtlTicket = 0,
+  kCtlEpoch = 256,
+  kCtlAbort = 288,
+  kCtlSkipped = 320,
+  kCtlStatus = 352,
+  kCtlFinish = 384,
+  kCtlWords = 416
+};
+constexpr uint32_t kFinishGrid = 32;  // workgroups of the finish kernels
 constexpr uint32_t kItemNorm = 0u, kItemAdam = 1u, kItemEmpty = 2u;  // work item kinds, in bits 30..31 of an item
 struct StepState {
   const Chunk* norm_tab;
@@ -98,9 +110,11 @@ struct StepState {
   double* partials;                 // kWaves per norm chunk
   uint32_t* arrived;                // [B] squared-norm workgroups done per bucket
   unsigned long long* ready;        // [B] (epoch << 32) | bits of the bucket's coefficient
-  uint32_t* ctl;                    // [kCtlWords] ticket counter, epoch
+  uint32_t* ctl;                    // [kCtlWords] see kCtl*
+  uint32_t* skipped;                // [chunks of the apply table] apply-table indices of items whose wait expired
   const uint32_t* apply_to_lamb;    // LAMB: place of every apply-table chunk in the tensor-major table
   double* lamb_sums;                // LAMB: two sums per chunk, in tensor-major order
+  uint32_t skipped_cap;             // entries of `skipped`
   uint32_t spin_limit;              // polls of a ready word before a waiting item gives up
 };
 
@@ -126,14 +140,13 @@ hipError_t launch_scale(int gdt, const Chunk* table, uint32_t c0, uint32_t n, co
 hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, const float* coefs, bool write_back,
                        const int32_t* skip_status, const AdamK& k, const Launch& L, hipStream_t stream);
 
-// The whole fused step: k_prepare, then one k_step workgroup per work item.  `between`
+// The whole fused step: one k_step workgroup per work item, then the finish kernel.  `between`
 // (may be null) is recorded between the two kernels.
-hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
-                       const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
-                       const AdamK& k, uint32_t unroll, bool tickets, bool lamb, hipEvent_t between,
-                       hipStream_t stream);
+hipError_t launch_step(int gdt, const StepState& st, const uint32_t* work, uint32_t n_work, const float* thresholds,
+                       float* norms, float* coefs, int32_t* status, bool write_back, const AdamK& k, uint32_t unroll,
+                       bool tickets, bool lamb, hipEvent_t between, hipStream_t stream);
 
-// Clipping of buckets [b0, b1) in one launch (k_prepare_range, then k_clip): cn0 / n_norm
+// Clipping of buckets [b0, b1) in one launch (k_clip, then its finish kernel): cn0 / n_norm
 // and ca0 / n_apply are the range's chunks in the norm and the apply table.
 hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
                        uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
@@ -190,6 +203,7 @@ struct bca_plan {
   uint32_t* d_arrived = nullptr;
   unsigned long long* d_ready = nullptr;
   uint32_t* d_ctl = nullptr;
+  uint32_t* d_skipped = nullptr;
   // device memory owned by the plan
   double* d_partials = nullptr;
   float* d_norms = nullptr;        // n_buckets + 1 (the last one: whole-gradient norm)

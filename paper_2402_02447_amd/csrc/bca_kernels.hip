@@ -758,34 +758,41 @@ __global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict_
 // precede its Adam items in the list and never wait themselves.
 //
 // Which workgroup takes which item:
-//  * default: item = workgroup index.  gfx950 starts the workgroups of a grid in
-//    index order within each XCD, so everything an Adam item waits for has been
-//    started before it.
+//  * default: item = workgroup index.  The hardware has been seen to start the
+//    workgroups of a grid in index order within each XCD, so that everything an
+//    Adam item waits for has been started before it; that is what makes the
+//    pipeline fast, but nothing below depends on it for its result.
 //  * TICKETS: eight atomic counters, one per XCD; item 8 t + y is the t-th item
 //    of list y.  A workgroup draws from its own XCD's list and moves to the next
 //    list when that one is used up.  Each list is thus started strictly in order
-//    by running workgroups, whatever the dispatcher does.  Why no wait can last:
-//    take the waiting Adam item of the earliest group k and a squared-norm item I
-//    of its bucket that has not been taken, in list y.  XCD y cannot be full of
-//    waiters drawn from list y, because those would lie before I in list y and so
-//    belong to groups before k; nor of waiters drawn from other lists, because a
-//    workgroup only leaves its own list once it is used up, and then I was taken.
-//    So XCD y has a free slot or a running non-waiter, starts another workgroup,
-//    and list y advances to I.
-// The wait is bounded all the same: after StepState::spin_limit polls the item is skipped,
-// an abort word makes every other waiter give up at its next look, and
-// BCA_STATUS_TIMEOUT is reported, so the grid always drains.
+//    by running workgroups, whatever the dispatcher does.
+//
+// Every wait is bounded: after StepState::spin_limit polls the item gives up, files
+// its index in the skipped list, raises the abort word (every other waiter then
+// gives up at its next look) and BCA_STATUS_TIMEOUT, and its workgroup ends, which
+// frees the slot for whatever it was waiting for.  Squared-norm items never wait, so
+// by the end of the launch every bucket's coefficient exists, and the finish kernel
+// that follows every such launch on the stream carries out the skipped items with
+// the same code.  The call's result is therefore complete and bit-identical whatever
+// the order in which workgroups were started; an expired wait only costs time.
+//
+// Per-call state needs no kernel in front of the launch: the last squared-norm item of a
+// bucket zeroes that bucket's arrival counter, and the finish kernel hands the collected
+// status bits to the caller, clears the abort word, the skipped count and the tickets and
+// moves the epoch on, so that the state is ready for the next call on the plan.
 
-// Resets the per-call state: takes a new epoch, clears the ticket, the arrival
-// counters and the caller's status word (k_step only ORs into it).
-__global__ __launch_bounds__(kBlock) void k_prepare(StepState st, uint32_t n_buckets, int32_t* status) {
-  for (uint32_t b = threadIdx.x; b < n_buckets; b += kBlock) st.arrived[b] = 0u;
-  if (threadIdx.x == 0) {
-    for (uint32_t y = 0; y < 8u; ++y) st.ctl[kCtlTicket + 32u * y] = 0u;
-    st.ctl[kCtlAbort] = 0u;
-    st.ctl[kCtlEpoch] = st.ctl[kCtlEpoch] + 1u;
-    *status = 0;
-  }
+// Waits until this wavefront's outstanding vector-memory operations have completed (stores
+// included: gfx9-family stores are counted by vmcnt until they are acknowledged).
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ uint32_t ctl_load(const uint32_t* w) {
+  return __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ctl_store(uint32_t* w, uint32_t x) {
+  __hip_atomic_store(w, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ctl_or(uint32_t* w, uint32_t bits) {
+  (void)__hip_atomic_fetch_or(w, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Shared memory of one k_step / k_clip workgroup.
@@ -798,8 +805,9 @@ struct StepShared {
 };
 
 // Waits (bounded) for bucket b's ready word of this epoch.  Returns true with the
-// bucket's coefficient in sh.coef, or false after reporting BCA_STATUS_TIMEOUT.
-__device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b, uint32_t epoch, int32_t* status,
+// bucket's coefficient in sh.coef; false when the wait expired, after filing `self`
+// (the item's index in the apply table) for the finish kernel.
+__device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b, uint32_t epoch, uint32_t self,
                                                 StepShared& sh) {
   if (threadIdx.x == 0) {
     // ready word: (epoch << 32) | bits of the coefficient
@@ -809,16 +817,20 @@ __device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b,
       r = __hip_atomic_load(&st.ready[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if ((uint32_t)(r >> 32) == epoch || ++polls > st.spin_limit) break;
       // once one wait has expired every other waiter gives up at its next look
-      if ((polls & 63u) == 0 && __hip_atomic_load(&st.ctl[kCtlAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
-        break;
+      if ((polls & 63u) == 0 && ctl_load(&st.ctl[kCtlAbort]) != 0u) break;
       __builtin_amdgcn_s_sleep(8);
     }
     const bool ok = (uint32_t)(r >> 32) == epoch;
     sh.flag = ok ? 1u : 0u;
     sh.coef = __uint_as_float((uint32_t)r);
     if (!ok) {
-      __hip_atomic_store(&st.ctl[kCtlAbort], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      atomicOr(status, BCA_STATUS_TIMEOUT);
+      ctl_store(&st.ctl[kCtlAbort], 1u);
+      ctl_or(&st.ctl[kCtlStatus], BCA_STATUS_TIMEOUT);
+      // every item is filed at most once, so the list cannot overflow unless an earlier call on the plan was
+      // cut short between its two launches; then the item is reported lost rather than written out of bounds
+      const uint32_t slot = atomicAdd(&st.ctl[kCtlSkipped], 1u);
+      if (slot < st.skipped_cap) st.skipped[slot] = self;  // read by the finish kernel, after this launch has ended
+      else ctl_or(&st.ctl[kCtlStatus], BCA_STATUS_INCOMPLETE);
     }
   }
   __syncthreads();
@@ -829,10 +841,24 @@ __device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b,
 // stand-in for a bucket without elements (kItemEmpty, idx = bucket).  The last
 // workgroup of a bucket to get here adds the bucket's partials in the fixed
 // order of k_finalize, writes norm and coefficient and publishes the ready word.
+//
+// Why the last arriver sees every partial.  A partial is written by an agent-scope
+// atomic store, which on this target is a write-through store that is acknowledged
+// once it has reached the level at which the whole device is coherent; the storing
+// wavefront then waits for that acknowledgement (vmcnt(0)) *before* the workgroup
+// barrier, so when thread 0 counts the workgroup's arrival (after the barrier) all
+// four partials of the chunk are visible to any agent-scope load.  Read-modify-write
+// operations on arrived[b] are totally ordered; the workgroup whose increment makes the
+// count complete therefore runs after every other arrival, hence after every partial
+// of the bucket became visible, and its own loads of the partials (agent scope: they
+// do not hit lines a per-XCD L2 may still hold from an earlier call) are issued only
+// after its increment has returned.  A workgroup-scope release fence would not do: on
+// this target it does not wait for vector stores, so the arrival could be counted
+// while a partial is still on its way.
 template <int GDT>
 __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, uint32_t idx, uint32_t epoch,
                                           const float* __restrict__ thresholds, float* __restrict__ norms,
-                                          float* __restrict__ coefs, int32_t* status, StepShared& sh) {
+                                          float* __restrict__ coefs, StepShared& sh) {
   const uint32_t tid = threadIdx.x;
   uint32_t b = idx;
   if (kind == kItemNorm) {
@@ -842,18 +868,18 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
     if ((tid & 63u) == 0)
       __hip_atomic_store(&st.partials[(uint64_t)idx * kWaves + (tid >> 6)], ws, __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
-    // The partial was stored write-through at device scope; once the store has
-    // completed (the workgroup-scope fence waits for it) it is visible to every
-    // device-scope load, so the arrival may be counted.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+    wait_vmem();  // the partial has been acknowledged ...
+    __syncthreads();  // ... by every wavefront of the workgroup
     if (tid == 0) {
       const uint32_t total = st.norm_bucket_off[b + 1] - st.norm_bucket_off[b];
       const uint32_t old = atomicAdd(&st.arrived[b], 1u);
-      sh.flag = (old + 1u == total) ? 1u : 0u;
+      const bool last = (old + 1u == total);
+      // nobody else touches the counter again in this call: leave it at zero for the next one
+      if (last) ctl_store(&st.arrived[b], 0u);
+      sh.flag = last ? 1u : 0u;
     }
     __syncthreads();
-    if (!sh.flag) return;  // the last to arrive goes on; its loads below are device-scope and bypass L2
+    if (!sh.flag) return;
   }
   const uint64_t lo = (uint64_t)st.norm_bucket_off[b] * kWaves, hi = (uint64_t)st.norm_bucket_off[b + 1] * kWaves;
   double s = 0.0;
@@ -869,19 +895,33 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
     const float coef = clip_coef(norm, thresholds[b], bst);
     norms[b] = norm;
     coefs[b] = coef;
-    if (bst) atomicOr(status, bst);
+    if (bst) ctl_or(&st.ctl[kCtlStatus], (uint32_t)bst);
+    // The coefficient travels inside the ready word, so a waiter needs nothing else that this item wrote.
     const unsigned long long word = ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(coef);
     __hip_atomic_store(&st.ready[b], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
-// LAMB: the items that would apply Adam run LAMB's first sweep instead (moments and the
-// chunk's two sums, filed under the chunk's place in the tensor-major order); the trust
-// ratio and the parameter update follow as launches of their own.
+// What the items that wait for a coefficient do with it.
+constexpr int kModeAdam = 0, kModeLamb = 1, kModeScale = 2;
+
+template <int GDT, bool WB, uint32_t U, int MODE>
+__device__ __forceinline__ void apply_item(const StepState& st, const Entry& en, uint32_t idx, float coef,
+                                           const AdamK& k, StepShared& sh) {
+  if constexpr (MODE == kModeLamb)
+    // LAMB's first sweep in place of Adam: moments and the chunk's two sums, filed under the chunk's place in
+    // the tensor-major order; the trust ratio and the parameter update follow as launches of their own.
+    lamb_moments_chunk<GDT, true, WB, false>(en, coef, k, sh.pp, sh.uu, st.lamb_sums + (uint64_t)st.apply_to_lamb[idx] * 2u);
+  else if constexpr (MODE == kModeScale) {
+    if (coef != 1.f) scale_chunk<GDT, U, false>(en, coef);
+  } else
+    adam_chunk<GDT, true, WB, U, false>(en, coef, k);
+}
+
 template <int GDT, bool WB, uint32_t U, bool TICKETS, bool LAMB>
 __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* __restrict__ work, uint32_t n_work,
                                                   const float* __restrict__ thresholds, float* __restrict__ norms,
-                                                  float* __restrict__ coefs, int32_t* status, const AdamK ka) {
+                                                  float* __restrict__ coefs, const AdamK ka) {
   __shared__ StepShared sh;
   const AdamK k = resolve(ka);
   uint32_t ticket;
@@ -909,20 +949,15 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
     ticket = blockIdx.x;
   }
   if (ticket >= n_work) return;
-  const uint32_t epoch = st.ctl[kCtlEpoch];  // written by k_prepare, constant during this launch
+  const uint32_t epoch = st.ctl[kCtlEpoch];  // left by the previous call's finish kernel, constant during this launch
   const uint32_t item = work[ticket];
   const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
   if (kind == kItemAdam) {
     const Entry en = read_entry(&st.apply_tab[idx]);
-    if (wait_for_bucket(st, en.bucket, epoch, status, sh)) {
-      if constexpr (LAMB)
-        lamb_moments_chunk<GDT, true, WB, false>(en, sh.coef, k, sh.pp, sh.uu,
-                                                 st.lamb_sums + (uint64_t)st.apply_to_lamb[idx] * 2u);
-      else
-        adam_chunk<GDT, true, WB, U, false>(en, sh.coef, k);
-    }
+    if (wait_for_bucket(st, en.bucket, epoch, idx, sh))
+      apply_item<GDT, WB, U, LAMB ? kModeLamb : kModeAdam>(st, en, idx, sh.coef, k, sh);
   } else {
-    norm_item<GDT>(st, kind, idx, epoch, thresholds, norms, coefs, status, sh);
+    norm_item<GDT>(st, kind, idx, epoch, thresholds, norms, coefs, sh);
   }
 }
 
@@ -932,46 +967,76 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
 // which wait for their bucket's coefficient exactly as the Adam items of k_step
 // do; buckets that are not clipped are not touched.  Norms, coefficients and
 // scaled gradients are those of k_sqnorm + k_finalize + k_coefs + k_scale bit
-// for bit.  Buckets without elements are dealt with by k_prepare_range.
+// for bit.  Buckets without elements are dealt with by the finish kernel.
 template <int GDT, uint32_t U>
 __global__ __launch_bounds__(kBlock) void k_clip(StepState st, uint32_t cn0, uint32_t n_norm, uint32_t ca0,
                                                   uint32_t n_apply, const float* __restrict__ thresholds,
-                                                  float* __restrict__ norms, float* __restrict__ coefs,
-                                                  int32_t* status) {
+                                                  float* __restrict__ norms, float* __restrict__ coefs) {
   __shared__ StepShared sh;
   const uint32_t w = blockIdx.x;
   const uint32_t epoch = st.ctl[kCtlEpoch];
   if (w < n_norm) {
-    norm_item<GDT>(st, kItemNorm, cn0 + w, epoch, thresholds, norms, coefs, status, sh);
+    norm_item<GDT>(st, kItemNorm, cn0 + w, epoch, thresholds, norms, coefs, sh);
   } else if (w - n_norm < n_apply) {
-    const Entry en = read_entry(&st.apply_tab[ca0 + (w - n_norm)]);
-    if (wait_for_bucket(st, en.bucket, epoch, status, sh) && sh.coef != 1.f) scale_chunk<GDT, U, false>(en, sh.coef);
+    const uint32_t idx = ca0 + (w - n_norm);
+    const Entry en = read_entry(&st.apply_tab[idx]);
+    if (wait_for_bucket(st, en.bucket, epoch, idx, sh)) apply_item<GDT, false, U, kModeScale>(st, en, idx, sh.coef, AdamK{}, sh);
   }
 }
 
-// Per-call reset for k_clip: new epoch, arrival counters of the range, status
-// word; norm 0 and the coefficient of buckets that have no elements.
-__global__ __launch_bounds__(kBlock) void k_prepare_range(StepState st, uint32_t b0, uint32_t b1,
-                                                           const float* __restrict__ thresholds,
-                                                           float* __restrict__ norms, float* __restrict__ coefs,
-                                                           int32_t* status) {
-  __shared__ int32_t s_st;
-  if (threadIdx.x == 0) s_st = 0;
-  __syncthreads();
-  int32_t bst = 0;
-  for (uint32_t b = b0 + threadIdx.x; b < b1; b += kBlock) {
-    st.arrived[b] = 0u;
-    if (st.norm_bucket_off[b] == st.norm_bucket_off[b + 1]) {
-      norms[b] = 0.f;
-      coefs[b] = clip_coef(0.f, thresholds[b], bst);
+// Follows every k_step / k_clip launch on the stream.  (1) Carries out the items whose
+// wait expired (none, as a rule), with the coefficient their bucket's ready word holds
+// by now.  (2) k_clip only (b0 < b1): norm 0 and the coefficient of buckets without
+// elements.  (3) The last of its workgroups to finish hands the status bits collected
+// during the call to the caller and resets the per-call state, epoch included.
+template <int GDT, bool WB, uint32_t U, int MODE>
+__global__ __launch_bounds__(kBlock) void k_finish(StepState st, uint32_t b0, uint32_t b1,
+                                                    const float* __restrict__ thresholds, float* __restrict__ norms,
+                                                    float* __restrict__ coefs, int32_t* status, const AdamK ka) {
+  __shared__ StepShared sh;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t epoch = ctl_load(&st.ctl[kCtlEpoch]);
+  const uint32_t n_skipped = min(ctl_load(&st.ctl[kCtlSkipped]), st.skipped_cap);
+  uint32_t bits = 0;
+  if (n_skipped != 0) {
+    const AdamK k = resolve(ka);
+    for (uint32_t i = blockIdx.x; i < n_skipped; i += gridDim.x) {
+      const uint32_t idx = st.skipped[i];
+      const Entry en = read_entry(&st.apply_tab[idx]);
+      const unsigned long long r = __hip_atomic_load(&st.ready[en.bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((uint32_t)(r >> 32) != epoch) {  // cannot happen: squared-norm items never wait
+        bits |= BCA_STATUS_INCOMPLETE;
+        continue;
+      }
+      apply_item<GDT, WB, U, MODE>(st, en, idx, __uint_as_float((uint32_t)r), k, sh);
+      __syncthreads();  // LAMB: sh.pp / sh.uu are reused by the next item
     }
   }
-  if (bst) atomicOr(&s_st, bst);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    st.ctl[kCtlAbort] = 0u;
-    st.ctl[kCtlEpoch] = st.ctl[kCtlEpoch] + 1u;
-    *status = s_st;
+  if (blockIdx.x == 0) {
+    int32_t bst = 0;
+    for (uint32_t b = b0 + tid; b < b1; b += kBlock) {
+      if (st.norm_bucket_off[b] == st.norm_bucket_off[b + 1]) {
+        norms[b] = 0.f;
+        coefs[b] = clip_coef(0.f, thresholds[b], bst);
+      }
+    }
+    bits |= (uint32_t)bst;
+  }
+  if (bits) ctl_or(&st.ctl[kCtlStatus], bits);
+  wait_vmem();      // this wavefront's status bits have landed ...
+  __syncthreads();  // ... and every wavefront's, before the workgroup is counted
+  if (tid == 0) {
+    const uint32_t old = atomicAdd(&st.ctl[kCtlFinish], 1u);
+    if (old + 1u == gridDim.x) {  // the last workgroup: nobody reads the per-call state after this
+      const uint32_t all = ctl_load(&st.ctl[kCtlStatus]);
+      if (status != nullptr) *status = (int32_t)all;
+      ctl_store(&st.ctl[kCtlStatus], 0u);
+      ctl_store(&st.ctl[kCtlSkipped], 0u);
+      ctl_store(&st.ctl[kCtlAbort], 0u);
+      ctl_store(&st.ctl[kCtlFinish], 0u);
+      for (uint32_t y = 0; y < 8u; ++y) ctl_store(&st.ctl[kCtlTicket + 32u * y], 0u);
+      ctl_store(&st.ctl[kCtlEpoch], epoch + 1u == 0u ? 1u : epoch + 1u);
+    }
   }
 }
 
@@ -1040,49 +1105,64 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t 
 hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
                        uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
                        int32_t* status, uint32_t unroll, hipStream_t stream) {
-  hipLaunchKernelGGL(k_prepare_range, dim3(1), dim3(kBlock), 0, stream, st, b0, b1, thresholds, norms, coefs, status);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || n_norm + n_apply == 0) return e;
-  pick_unroll(unroll, [&](auto uu) {
-    constexpr uint32_t U = decltype(uu)::value;
-    pick_gdt(gdt, [&](auto gd) {
-      constexpr int GDT = decltype(gd)::value;
-      hipLaunchKernelGGL((k_clip<GDT, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm, ca0,
-                         n_apply, thresholds, norms, coefs, status);
+  if (n_norm + n_apply != 0) {
+    pick_unroll(unroll, [&](auto uu) {
+      constexpr uint32_t U = decltype(uu)::value;
+      pick_gdt(gdt, [&](auto gd) {
+        constexpr int GDT = decltype(gd)::value;
+        hipLaunchKernelGGL((k_clip<GDT, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm, ca0,
+                           n_apply, thresholds, norms, coefs);
+      });
     });
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  pick_gdt(gdt, [&](auto gd) {
+    constexpr int GDT = decltype(gd)::value;
+    hipLaunchKernelGGL((k_finish<GDT, false, 1, kModeScale>), dim3(kFinishGrid), dim3(kBlock), 0, stream, st, b0, b1,
+                       thresholds, norms, coefs, status, AdamK{});
   });
   return hipGetLastError();
 }
 
-hipError_t launch_step(int gdt, const StepState& st, uint32_t n_buckets, const uint32_t* work, uint32_t n_work,
-                       const float* thresholds, float* norms, float* coefs, int32_t* status, bool write_back,
-                       const AdamK& k, uint32_t unroll, bool tickets, bool lamb, hipEvent_t between,
-                       hipStream_t stream) {
-  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(kBlock), 0, stream, st, n_buckets, status);
-  hipError_t e = hipGetLastError();
-  if (between != nullptr) (void)hipEventRecord(between, stream);
-  if (e != hipSuccess || n_work == 0) return e;
-  if (lamb) {  // one variant per gradient type and write-back setting: items by workgroup index, no unrolling
-    pick_gdt(gdt, [&](auto gd) {
-      constexpr int GDT = decltype(gd)::value;
-      if (write_back)
-        hipLaunchKernelGGL((k_step<GDT, true, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
-                           thresholds, norms, coefs, status, k);
-      else
-        hipLaunchKernelGGL((k_step<GDT, false, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
-                           thresholds, norms, coefs, status, k);
-    });
-    return hipGetLastError();
-  }
-  pick_unroll(unroll, [&](auto uu) {
-    constexpr uint32_t U = decltype(uu)::value;
-    pick2(tickets, write_back, [&](auto tk, auto wb) {
-      constexpr bool TK = decltype(tk)::value, WB = decltype(wb)::value;
+hipError_t launch_step(int gdt, const StepState& st, const uint32_t* work, uint32_t n_work, const float* thresholds,
+                       float* norms, float* coefs, int32_t* status, bool write_back, const AdamK& k, uint32_t unroll,
+                       bool tickets, bool lamb, hipEvent_t between, hipStream_t stream) {
+  if (n_work != 0) {
+    if (lamb) {  // one variant per gradient type and write-back setting: items by workgroup index, no unrolling
       pick_gdt(gdt, [&](auto gd) {
         constexpr int GDT = decltype(gd)::value;
-        hipLaunchKernelGGL((k_step<GDT, WB, U, TK, false>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
-                           thresholds, norms, coefs, status, k);
+        if (write_back)
+          hipLaunchKernelGGL((k_step<GDT, true, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                             thresholds, norms, coefs, k);
+        else
+          hipLaunchKernelGGL((k_step<GDT, false, 1, false, true>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                             thresholds, norms, coefs, k);
       });
+    } else {
+      pick_unroll(unroll, [&](auto uu) {
+        constexpr uint32_t U = decltype(uu)::value;
+        pick2(tickets, write_back, [&](auto tk, auto wb) {
+          constexpr bool TK = decltype(tk)::value, WB = decltype(wb)::value;
+          pick_gdt(gdt, [&](auto gd) {
+            constexpr int GDT = decltype(gd)::value;
+            hipLaunchKernelGGL((k_step<GDT, WB, U, TK, false>), dim3(n_work), dim3(kBlock), 0, stream, st, work, n_work,
+                               thresholds, norms, coefs, k);
+          });
+        });
+      });
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (between != nullptr) (void)hipEventRecord(between, stream);
+  // the finish kernel: skipped items (same arithmetic whatever the unrolling, so one variant), status, next epoch
+  pick2(lamb, write_back, [&](auto lm, auto wb) {
+    constexpr bool LM = decltype(lm)::value, WB = decltype(wb)::value;
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      hipLaunchKernelGGL((k_finish<GDT, WB, 1, LM ? kModeLamb : kModeAdam>), dim3(kFinishGrid), dim3(kBlock), 0, stream,
+                         st, 0u, 0u, thresholds, norms, coefs, status, k);
     });
   });
   return hipGetLastError();

@@ -643,23 +643,61 @@ def test_hyper_parameter_extremes(hp, step):
 # ------------------------------------------------------------------ the bounded wait of the fused calls
 
 
-def test_expired_wait_is_reported_every_kernel_ends_and_later_calls_are_unaffected():
-    """With a spin limit of one poll, the Adam items that start while their bucket's squared norm is still
-    being read give up at once: the call returns, the kernels end, the status word carries the time-out bit.
-    The same tensors then go through a plan with the default limit and match the oracle."""
-    numels = [3_000_000, 1_500_000]
-    lay = W.layout_flat_split(numels, 4_500_000)                     # one bucket: every Adam item waits for one norm
+@pytest.mark.parametrize("gdtype", ["f32", "f16"])
+def test_expired_wait_costs_time_only(gdtype):
+    """With a spin limit of one poll, the items that start while their bucket's squared norm is still being read
+    give up at once and are handed to the call's finish kernel.  The status word carries the time-out bit and
+    nothing else; p, m, v (and g) hold exactly the bits a plan with the default limit produces, and match the
+    oracle; the per-call state is left in order, so a second call on the same plan behaves the same way."""
+    numels = [3_000_000, 1_500_000, 12_345]
+    lay = W.layout_flat_split(numels, 4_500_000)                     # one large bucket: its Adam items wait for one norm
     g = W.normal_tensors(numels, 41, "g", 1e-3, threads=1)
+    if gdtype == "f16":
+        g = [x.astype(np.float16) for x in g]
     p, m, v = (W.normal_tensors(numels, 41, "p", 0.02, threads=1), W.normal_tensors(numels, 41, "m", 3e-3, threads=1),
                W.warm_second_moment(numels, 41, threads=1))
     hp = W.Hyper()
-    thr = np.asarray([0.5 * oracle.bucket_norms(lay, g)[0]], np.float32)
-    d = Device(lay, g, p, m, v, spin_limit=1)
-    d.plan.bucket_clip_adam(d.thresholds(thr), hyper(hp), 5, 0, d.norms, d.coefs, d.status)
-    d.sync()
-    assert int(d.status.item()) & B.BCA_STATUS_TIMEOUT
-    d.plan.bucket_clip(0, 1, d.thresholds(thr), d.norms, d.coefs, d.status)     # the clip-only call waits the same way
-    d.sync()
-    assert int(d.status.item()) & B.BCA_STATUS_TIMEOUT
-    d.close()
-    run_fused(lay, g, p, m, v, thr, hp, 5)
+    thr = (0.5 * oracle.bucket_norms(lay, g)).astype(np.float32)
+    for flags in (0, B.BCA_WRITE_BACK_GRADS):
+        ref = Device(lay, g, p, m, v)
+        d = Device(lay, g, p, m, v, spin_limit=1)
+        og = [x.copy() for x in g]
+        op, om, ov = f64(p), f64(m), f64(v)
+        for step in (5, 6):
+            ref.plan.bucket_clip_adam(ref.thresholds(thr), hyper(hp), step, flags, ref.norms, ref.coefs, ref.status)
+            d.plan.bucket_clip_adam(d.thresholds(thr), hyper(hp), step, flags, d.norms, d.coefs, d.status)
+            d.sync()
+            assert int(ref.status.item()) == 0
+            assert int(d.status.item()) == B.BCA_STATUS_TIMEOUT
+            assert np.array_equal(d.norms.cpu().numpy(), ref.norms.cpu().numpy())
+            assert np.array_equal(d.coefs.cpu().numpy(), ref.coefs.cpu().numpy())
+            for name, a, b in (("p", d.p, ref.p), ("m", d.m, ref.m), ("v", d.v, ref.v), ("g", d.g, ref.g)):
+                assert bits_equal(to_host(a), to_host(b)), f"{name} after step {step}, flags {flags}"
+            if gdtype == "f32" or flags == 0:     # (stored fp16 gradients feed the next step: compared bit for bit above)
+                oracle.bucket_clip_adam(lay, og, op, om, ov, thr, step=step, write_back=bool(flags), **hp_kwargs(hp))
+                check_state("p", to_host(d.p), op), check_state("m", to_host(d.m), om)
+                check_state("v", to_host(d.v), ov, strict_rel=True)
+        # the clip-only call waits the same way; its skipped scale items are carried out as well
+        thr2 = (0.5 * thr).astype(np.float32)
+        ref.plan.bucket_clip_norms(0, lay.n_buckets, ref.norms)
+        ref.plan.bucket_clip_apply(0, lay.n_buckets, ref.thresholds(thr2), ref.norms, ref.coefs, ref.status)
+        d.plan.bucket_clip(0, lay.n_buckets, d.thresholds(thr2), d.norms, d.coefs, d.status)
+        d.sync()
+        assert int(d.status.item()) == B.BCA_STATUS_TIMEOUT and int(ref.status.item()) == 0
+        assert np.array_equal(d.norms.cpu().numpy(), ref.norms.cpu().numpy())
+        assert np.array_equal(d.coefs.cpu().numpy(), ref.coefs.cpu().numpy())
+        assert bits_equal(to_host(d.g), to_host(ref.g))
+        assert not bits_equal(to_host(d.g), g)
+        # and LAMB behind the clip (its first sweep is what waits)
+        ref.plan.bucket_clip_lamb(ref.thresholds(thr2), hyper(hp), 7, flags, ref.norms, ref.coefs, ref.trust, ref.status)
+        d.plan.bucket_clip_lamb(d.thresholds(thr2), hyper(hp), 7, flags, d.norms, d.coefs, d.trust, d.status)
+        d.sync()
+        assert int(d.status.item()) == B.BCA_STATUS_TIMEOUT and int(ref.status.item()) == 0
+        assert np.array_equal(d.trust.cpu().numpy(), ref.trust.cpu().numpy())
+        for name, a, b in (("p", d.p, ref.p), ("m", d.m, ref.m), ("v", d.v, ref.v), ("g", d.g, ref.g)):
+            assert bits_equal(to_host(a), to_host(b)), f"{name} after LAMB, flags {flags}"
+        # a plan whose waits do not expire reports a clean status again after all that
+        ref.plan.bucket_clip_adam(ref.thresholds(thr), hyper(hp), 8, 0, ref.norms, ref.coefs, ref.status)
+        ref.sync()
+        assert int(ref.status.item()) == 0
+        d.close(), ref.close()
