@@ -24,7 +24,7 @@ BCA_TABLE_NORM, BCA_TABLE_APPLY, BCA_TABLE_LAMB = 0, 1, 2
 _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4: "BCA_ERR_HPARAM",
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
-EXPORTS = ["bca_alg1_thresholds", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
+EXPORTS = ["bca_alg1_thresholds", "bucket_clip_flat", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
            "bca_plan_num_groups", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
            "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error",
@@ -126,6 +126,7 @@ def load_library():
     L.bca_plan_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]
     L.bca_copy_bytes.argtypes = [vp, vp, u64, vp]
     L.bca_alg1_thresholds.argtypes = [C.c_double, u32, C.POINTER(C.c_float)]
+    L.bucket_clip_flat.argtypes = [vp, u64, i32, vp, vp, vp, vp, vp]
     L.bca_last_error.restype = C.c_char_p
     L.bca_version.restype = i32
     for name in EXPORTS:
@@ -165,6 +166,12 @@ def alg1_thresholds(c: float, n_buckets: int) -> np.ndarray:
     out = np.zeros(n_buckets, dtype=np.float32)
     _check(load_library().bca_alg1_thresholds(float(c), int(n_buckets), out.ctypes.data_as(C.POINTER(C.c_float))))
     return out
+
+
+def bucket_clip_flat(g, n: int, grad_dtype: int, threshold, norm=None, coef=None, status=None, stream=None) -> None:
+    """bucket_clip_flat: clip one contiguous bucket in place; no plan, no allocation (see bca.h)."""
+    _check(load_library().bucket_clip_flat(_ptr(g), int(n), grad_dtype, _ptr(threshold), _ptr(norm), _ptr(coef),
+                                           _ptr(status), _stream(stream)))
 
 
 class Plan:

@@ -765,6 +765,28 @@ int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, 
   return BCA_OK;
 }
 
+int bucket_clip_flat(void* g, uint64_t n, int grad_dtype, const float* threshold, float* norm, float* coef,
+                     int32_t* status, void* stream) {
+  if (grad_dtype != BCA_GRAD_F32 && grad_dtype != BCA_GRAD_F16 && grad_dtype != BCA_GRAD_BF16)
+    return fail(BCA_ERR_DTYPE, "unknown gradient type");
+  if (n > kFlatMaxElems) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "bucket_clip_flat handles at most %llu elements per call (got %llu)",
+             (unsigned long long)kFlatMaxElems, (unsigned long long)n);
+    return fail(BCA_ERR_RANGE, buf);
+  }
+  if (n && !g) return fail(BCA_ERR_NULL, "g is NULL");
+  if (!threshold) return fail(BCA_ERR_NULL, "threshold is NULL");
+  if ((uintptr_t)g % grad_bytes(grad_dtype)) return fail(BCA_ERR_ALIGN, "g is not aligned to its element size");
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (device < 0 || device >= kFlatMaxDevices) return fail(BCA_ERR_RANGE, "device index beyond what bucket_clip_flat keeps scratch for");
+  e = launch_clip_flat(device, grad_dtype, g, n, threshold, norm, coef, status, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(e, "bucket_clip_flat");
+  return BCA_OK;
+}
+
 int adam_step(bca_plan* p, const bca_adam* hp, uint64_t step, void* stream) {
   if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
   AdamK k;

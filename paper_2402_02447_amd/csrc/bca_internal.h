@@ -153,6 +153,14 @@ hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, u
                        int32_t* status, uint32_t unroll, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 
+// bucket_clip_flat: one contiguous bucket of n <= kFlatMaxElems elements at g, clipped in place with partial
+// sums in the library's fixed device array.  `device` is the current device, below kFlatMaxDevices.
+constexpr uint64_t kFlatMaxElems = 1ull << 28;
+constexpr uint32_t kFlatChunkNorm = 16384;
+constexpr int kFlatMaxDevices = 64;
+hipError_t launch_clip_flat(int device, int gdt, void* g, uint64_t n, const float* threshold, float* norm, float* coef,
+                            int32_t* status, hipStream_t stream);
+
 // LAMB (tensor-major table `table` of n chunks; tensor_off[t] = first chunk of tensor t).
 // Stage 1: moments, per-chunk sums of p^2 and update^2 (2 doubles per chunk in `sums`);
 // coefs == nullptr: gradients as stored.  Trust: per tensor, ratio and step scale.

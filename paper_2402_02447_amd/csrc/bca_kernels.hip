@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "bca_internal.h"
@@ -1040,6 +1041,64 @@ __global__ __launch_bounds__(kBlock) void k_finish(StepState st, uint32_t b0, ui
   }
 }
 
+// ---- clipping one contiguous bucket without a plan and without allocating ---------------
+//
+// For callers that cannot allocate (HIP graph capture, tight loops): the bucket is a
+// pointer and a length, chunk bounds are computed from the chunk index instead of read
+// from a table, and the partial sums live in a fixed array of this library's device
+// image.  Three plain launches (squared norms, finalize, scale) with the device functions
+// of the plan-based path, so norm, coefficient and scaled gradients are those of
+// bucket_clip on a one-tensor, one-bucket plan whose squared-norm chunk is kFlatChunkNorm.
+
+constexpr uint32_t kFlatHeaderBytes = 256;  // coefficient of the current call (one float), padding
+constexpr size_t kFlatScratchBytes = kFlatHeaderBytes + (size_t)(kFlatMaxElems / kFlatChunkNorm) * kWaves * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kFlatScratchBytes];
+
+__device__ __forceinline__ Entry flat_entry(uint64_t g, uint64_t n, uint32_t chunk_elems, uint32_t gsize, uint32_t i) {
+  const uint64_t first = (uint64_t)i * chunk_elems;
+  Entry e;
+  e.g = g + first * gsize, e.p = 0, e.m = 0, e.v = 0;
+  e.len = (uint32_t)(n - first < chunk_elems ? n - first : chunk_elems);
+  e.bucket = 0, e.tensor = 0, e.flags = 0;
+  return e;
+}
+
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void k_flat_sqnorm(uint64_t g, uint64_t n, double* __restrict__ partials) {
+  const Entry en = flat_entry(g, n, kFlatChunkNorm, sizeof(typename Grad<GDT>::elem), blockIdx.x);
+  const double ws = sqnorm_chunk<GDT, false>(en);  // cacheable loads: the scale pass reads the bucket again at once
+  if ((threadIdx.x & 63u) == 0) partials[(uint64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = ws;
+}
+
+// One workgroup; the summation order of k_finalize.  Writes (not ORs) the status word.
+__global__ __launch_bounds__(kBlock) void k_flat_finalize(const double* __restrict__ partials, uint32_t n_chunks,
+                                                           const float* __restrict__ threshold, float* norm_out,
+                                                           float* coef_out, int32_t* status, float* coef_scratch) {
+  __shared__ double s_w[kWaves];
+  double s = 0.0;
+  for (uint64_t i = threadIdx.x; i < (uint64_t)n_chunks * kWaves; i += kBlock) s += partials[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+    const float norm = (float)sqrt(tot);
+    int32_t st = 0;
+    const float coef = clip_coef(norm, *threshold, st);
+    *coef_scratch = coef;
+    if (norm_out != nullptr) *norm_out = norm;
+    if (coef_out != nullptr) *coef_out = coef;
+    if (status != nullptr) *status = st;
+  }
+}
+
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void k_flat_scale(uint64_t g, uint64_t n, const float* __restrict__ coef_scratch) {
+  const float coef = *coef_scratch;
+  if (coef == 1.f) return;  // an unclipped bucket is not touched
+  scale_chunk<GDT, 1, false>(flat_entry(g, n, kDefaultChunkApply, sizeof(typename Grad<GDT>::elem), blockIdx.x), coef);
+}
+
 // Plain device-to-device copy (16-byte pieces, then single bytes).  It exists so
 // that hardware counters can be calibrated against a kernel whose HBM traffic is
 // known exactly: nbytes read, nbytes written.
@@ -1262,6 +1321,49 @@ hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uin
   if (n_tensors == 0) return hipSuccess;
   hipLaunchKernelGGL(k_lamb_trust, dim3(n_tensors), dim3(kTrustBlock), 0, stream, sums, tensor_off, k, trust, scale);
   return hipGetLastError();
+}
+
+// Device address of `scratch` on each device, looked up once per device with that device current
+// (every device holds its own copy of the array at its own address).  Host code never uses the
+// array's name for anything else: as an expression it is a host-side stand-in, not a device address.
+static void* g_flat_scratch[kFlatMaxDevices];
+static hipError_t g_flat_scratch_err[kFlatMaxDevices];
+static std::once_flag g_flat_scratch_once[kFlatMaxDevices];
+
+hipError_t launch_clip_flat(int device, int gdt, void* g, uint64_t n, const float* threshold, float* norm, float* coef,
+                            int32_t* status, hipStream_t stream) {
+  std::call_once(g_flat_scratch_once[device], [device] {
+    void* ptr = nullptr;
+    g_flat_scratch_err[device] = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    g_flat_scratch[device] = g_flat_scratch_err[device] == hipSuccess ? ptr : nullptr;
+  });
+  if (g_flat_scratch_err[device] != hipSuccess) return g_flat_scratch_err[device];
+  unsigned char* base = static_cast<unsigned char*>(g_flat_scratch[device]);
+  if (base == nullptr) return hipErrorInvalidSymbol;
+  float* coef_scratch = reinterpret_cast<float*>(base);
+  double* partials = reinterpret_cast<double*>(base + kFlatHeaderBytes);
+  const uint32_t n_norm = (uint32_t)((n + kFlatChunkNorm - 1) / kFlatChunkNorm);
+  const uint32_t n_apply = (uint32_t)((n + kDefaultChunkApply - 1) / kDefaultChunkApply);
+  const uint64_t ga = (uint64_t)(uintptr_t)g;
+  hipError_t e = hipSuccess;
+  // Nothing in the scratch array has to start at zero: every partial that the finalize kernel reads and the
+  // coefficient that the scale kernel reads are written earlier in this same call.
+  if (n_norm != 0) {
+    pick_gdt(gdt, [&](auto gd) {
+      hipLaunchKernelGGL((k_flat_sqnorm<decltype(gd)::value>), dim3(n_norm), dim3(kBlock), 0, stream, ga, n, partials);
+    });
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_flat_finalize, dim3(1), dim3(kBlock), 0, stream, partials, n_norm, threshold, norm, coef, status,
+                     coef_scratch);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (n_apply != 0) {
+    pick_gdt(gdt, [&](auto gd) {
+      hipLaunchKernelGGL((k_flat_scale<decltype(gd)::value>), dim3(n_apply), dim3(kBlock), 0, stream, ga, n, coef_scratch);
+    });
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 hipError_t launch_lamb_update(const Chunk* table, uint32_t n, const float* scale, const AdamK& k, hipStream_t stream) {

@@ -1,0 +1,163 @@
+"""bucket_clip_flat, the entry point that allocates nothing, against bucket_clip (GPU, through the C ABI).
+
+The existing entry point runs on a one-tensor, one-bucket plan whose squared-norm chunk is the flat call's
+(16 384 elements): norm, coefficient, status and every stored gradient must then agree bit for bit, which is
+stricter than the tolerances that hold against the oracle.  Calls come in pairs, the second on a smaller
+input, so that anything a call wrongly inherits from the fixed scratch array of the call before shows up."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2402_02447_amd as B
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def host_grads(n, seed, gdt):
+    g = np.random.default_rng(seed).normal(0.0, 1e-3, n).astype(np.float32)
+    if gdt == B.BCA_GRAD_F16:
+        return g.astype(np.float16)
+    if gdt == B.BCA_GRAD_BF16:
+        return W.float32_to_bf16_bits(g)
+    return g
+
+
+def host_norm(h):
+    x = W.bf16_bits_to_float32(h) if h.dtype == np.uint16 else h
+    return float(np.sqrt(np.sum(x.astype(np.float64) ** 2)))
+
+
+def to_dev(h, offset):
+    t = torch.from_numpy(h.view(np.int16) if h.dtype == np.uint16 else h)
+    buf = torch.empty(h.shape[0] + offset + 8, dtype=t.dtype, device="cuda")
+    view = buf[offset:offset + h.shape[0]]
+    view.copy_(t)
+    return buf, view
+
+
+def plan_clip(h, gdt, offset, thr):
+    """bucket_clip on a plan that holds the array as its only tensor and only bucket."""
+    n = h.shape[0]
+    _, g = to_dev(h, offset)
+    lay = W.layout_one_tensor_per_bucket([n])
+    dummy = [torch.zeros(max(n, 1), dtype=torch.float32, device="cuda")]
+    plan = B.Plan.from_layout(lay, gdt, device=0, chunk_norm=16384)
+    plan.bind([g], dummy, dummy, dummy)
+    norm = torch.full((1,), -1.0, device="cuda")
+    coef = torch.full((1,), -1.0, device="cuda")
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    plan.bucket_clip(0, 1, thr, norm, coef, status)
+    torch.cuda.synchronize()
+    out = (g.cpu().numpy().copy(), norm.item(), coef.item(), int(status.item()))
+    plan.close()
+    return out
+
+
+def flat_clip(h, gdt, offset, thr, stream=None):
+    buf, g = to_dev(h, offset)
+    guard_before = buf[:offset].clone()
+    guard_after = buf[offset + h.shape[0]:].clone()
+    norm = torch.full((1,), -1.0, device="cuda")
+    coef = torch.full((1,), -1.0, device="cuda")
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.bucket_clip_flat(g, h.shape[0], gdt, thr, norm, coef, status, stream)
+    torch.cuda.synchronize()
+    assert torch.equal(buf[:offset], guard_before) and torch.equal(buf[offset + h.shape[0]:], guard_after)
+    return g.cpu().numpy().copy(), norm.item(), coef.item(), int(status.item())
+
+
+def same(a, b):
+    ga, na, ca, sa = a
+    gb, nb, cb, sb = b
+    return (np.array_equal(ga.view(np.uint8), gb.view(np.uint8)) and np.float32(na).tobytes() == np.float32(nb).tobytes()
+            and np.float32(ca).tobytes() == np.float32(cb).tobytes() and sa == sb)
+
+
+@pytest.mark.parametrize("gdt", [B.BCA_GRAD_F32, B.BCA_GRAD_F16, B.BCA_GRAD_BF16])
+def test_two_calls_in_a_row_the_second_smaller_match_bucket_clip_bit_for_bit(gdt):
+    # several chunks and a ragged tail, then a smaller input that uses a strict subset of the scratch array;
+    # thresholds at half the norm (clips) or four times the norm (does not)
+    for (n1, n2), offset in (((1_000_003, 70_001), 0), ((3 * 16384 + 5, 16384), 3), ((200_000, 1), 1), ((12_345, 0), 0)):
+        for clip in (True, False):
+            results = []
+            for k, n in enumerate((n1, n2)):
+                h = host_grads(n, 100 + k, gdt)
+                c = (0.5 if clip else 4.0) * host_norm(h) if n else 1.0
+                thr = torch.tensor([c], dtype=torch.float32, device="cuda")
+                flat = flat_clip(h, gdt, offset, thr)
+                ref = plan_clip(h, gdt, offset, thr)
+                assert same(flat, ref), (gdt, n, offset, clip, flat[1:], ref[1:])
+                results.append(flat)
+                if n:
+                    assert (flat[2] < 1.0) == clip
+                    changed = not np.array_equal(flat[0].view(np.uint8), h.view(np.uint8))
+                    assert changed == clip
+                else:
+                    assert flat[1] == 0.0 and flat[2] == 1.0
+            assert results[0][1] != results[1][1]
+
+
+def test_back_to_back_on_a_stream_without_synchronising_in_between():
+    """Two calls enqueued one behind the other (the second smaller) before anything is waited for."""
+    gdt = B.BCA_GRAD_F32
+    h1, h2 = host_grads(600_000, 7, gdt), host_grads(33_000, 8, gdt)
+    s = torch.cuda.Stream()
+    thr1 = torch.tensor([0.3], dtype=torch.float32, device="cuda")
+    thr2 = torch.tensor([0.05], dtype=torch.float32, device="cuda")
+    _, g1 = to_dev(h1, 0)
+    _, g2 = to_dev(h2, 0)
+    out = torch.full((6,), -1.0, device="cuda")
+    st = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    B.bucket_clip_flat(g1, h1.shape[0], gdt, thr1, out[0:1], out[1:2], st[0:1], s)
+    B.bucket_clip_flat(g2, h2.shape[0], gdt, thr2, out[2:3], out[3:4], st[1:2], s)
+    s.synchronize()
+    r1 = plan_clip(h1, gdt, 0, thr1)
+    r2 = plan_clip(h2, gdt, 0, thr2)
+    assert same((g1.cpu().numpy(), out[0].item(), out[1].item(), int(st[0])), r1)
+    assert same((g2.cpu().numpy(), out[2].item(), out[3].item(), int(st[1])), r2)
+
+
+def test_status_bits_and_optional_outputs():
+    gdt = B.BCA_GRAD_F32
+    h = host_grads(50_000, 3, gdt)
+    bad = torch.tensor([-1.0], dtype=torch.float32, device="cuda")
+    flat, ref = flat_clip(h, gdt, 0, bad), plan_clip(h, gdt, 0, bad)
+    assert same(flat, ref) and flat[3] == B.BCA_STATUS_BAD_THRESHOLD and flat[2] == 1.0
+    h[17] = np.inf
+    thr = torch.tensor([1.0], dtype=torch.float32, device="cuda")
+    _, g = to_dev(h, 0)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.bucket_clip_flat(g, h.shape[0], gdt, thr, None, None, status)       # norm and coef not wanted
+    torch.cuda.synchronize()
+    assert int(status.item()) & B.BCA_STATUS_NONFINITE
+
+
+def test_sizes_beyond_the_limit_and_bad_arguments_are_refused_before_anything_is_enqueued():
+    L = B.load_library()
+    thr = torch.tensor([1.0], dtype=torch.float32, device="cuda")
+    g = torch.zeros(16, device="cuda")
+    for n, gdt, gp, tp, code in (((1 << 28) + 1, 0, g.data_ptr(), thr.data_ptr(), -3),
+                                 (16, 7, g.data_ptr(), thr.data_ptr(), -7),
+                                 (16, 0, None, thr.data_ptr(), -1),
+                                 (16, 0, g.data_ptr(), None, -1),
+                                 (16, 0, g.data_ptr() + 2, thr.data_ptr(), -8)):
+        rc = L.bucket_clip_flat(gp, n, gdt, tp, None, None, None, None)
+        assert rc == code, (n, gdt, rc, L.bca_last_error())
+    torch.cuda.synchronize()
+    assert bool((g == 0).all())
+
+
+def test_largest_size_runs():
+    """2^28 fp16 elements (512 MiB): the whole scratch array is in use; the norm of a constant bucket is known."""
+    n = 1 << 28
+    g = torch.full((n,), 2.0 ** -10, dtype=torch.float16, device="cuda")
+    thr = torch.tensor([4.0], dtype=torch.float32, device="cuda")
+    out = torch.full((2,), -1.0, device="cuda")
+    st = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.bucket_clip_flat(g, n, B.BCA_GRAD_F16, thr, out[0:1], out[1:2], st)
+    torch.cuda.synchronize()
+    assert out[0].item() == 16.0 and out[1].item() == 0.25 and int(st.item()) == 0      # 2^-10 * sqrt(2^28) = 16
+    assert bool((g[:: 4099] == 2.0 ** -12).all()) and g[-1].item() == 2.0 ** -12
