@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5], help="benchmark configuration: 2 BERT-Base 25 MiB, 3 BERT-Large 50 MiB, 4 fp16 1 MiB, 5 4 MiB")
-    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms", "whole_clip_adam", "per_bucket", "lbs"],
+    ap.add_argument("--op", default="clip_adam", choices=["clip_adam", "adam", "clip_lamb", "lamb", "norms", "whole_clip_adam", "per_bucket", "lbs", "issue_rate"],
                     help="what one step is: the fused bucket_clip_adam (headline, default), adam_step alone, "
                          "bucket_clip_lamb, lamb_step, bucket_clip_norms alone, whole-gradient clipping + Adam, the paper's "
                          "order (bucket_clip bucket by bucket, then adam_step), or (lbs) the load-balancing "
@@ -167,6 +167,35 @@ def other_ops(a, w, plan, g, p, m, v, dev):
     }))
 
 
+def issue_rate_bench(a, dev):
+    """Vector issue rates of the instruction kinds the load-balancing simulation is made of (lbs_issue_rate_probe):
+    the evidence for the "alu" peak that k_lbs_all is priced on.  One JSON line."""
+    import torch
+
+    from paper_2402_02447_amd import lbs
+    grid, iters = 256 * 8 * 4, 2000                      # 8 workgroups per compute unit resident, 4 rounds of them
+    out = torch.zeros(grid * 256, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    rates = {}
+    for kind, (what, n_instr) in lbs.PROBE_KINDS.items():
+        lbs.issue_rate_probe(kind, grid, iters, out, stream)
+        ts = []
+        for _ in range(max(3, a.steps)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            lbs.issue_rate_probe(kind, grid, iters, out, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = sorted(ts)[len(ts) // 2]
+        lane_ops = grid * 256 * iters * 8 * n_instr
+        rates[what] = {"ms": round(ms, 3), "T_lane_ops_per_s": round(lane_ops / (ms * 1e-3) / 1e12, 1)}
+    peak = 256 * 4 * 32 * 2.4e9 / 1e12
+    print(json.dumps({"metric": "vector issue rate per instruction kind (lane-operations per second)", "unit": "T lane-ops/s",
+                      "n_gpus": 1, "config": {"workload": f"{grid} workgroups x 256 threads x {iters} rounds x 8 chains per lane"},
+                      "peak_taken": round(peak, 1), "rates": rates}))
+
+
 def lbs_bench(a, dev):
     """Load-balancing simulation (Sec. 5.2, Table 5) at the paper's setting: local batch 16, nodes of 8 GPUs,
     --lbs-gpus GPUs, --lbs-trials trials per method.  One JSON line: simulated sequence draws per second over
@@ -272,6 +301,9 @@ def main():
     dev = torch.device("cuda:0")
     if a.op == "lbs":
         lbs_bench(a, dev)
+        return
+    if a.op == "issue_rate":
+        issue_rate_bench(a, dev)
         return
 
     w = W.CONFIGS[a.config]()

@@ -94,6 +94,20 @@ int lbs_simulate(const lbs_dataset* ds, const lbs_run* run /*HOST*/, uint32_t* t
 int lbs_simulate_all(const lbs_dataset* ds, const lbs_run* run /*HOST*/, uint32_t* trial_min /*DEVICE or NULL*/,
                      uint32_t* trial_max /*DEVICE or NULL*/, uint64_t* sums /*DEVICE [5][2]*/, void* stream);
 
+/* Measurement only (not part of the method): runs `iters` rounds of eight independent register chains per lane
+ * of one instruction kind in n_workgroups workgroups of 256 threads, so that a caller who times it gets the rate
+ * at which this GPU issues that kind -- the evidence behind the "alu" roofline peak the simulation is priced on.
+ * Per round and chain: XOR_ADD, MUL_HI_ADD, DPP_ADD and BPERMUTE_ADD issue two instructions, the others one.
+ * out: DEVICE [n_workgroups * 256] (one word per thread, written so that the arithmetic is kept). */
+#define LBS_PROBE_XOR_ADD 0      /* v_xor_b32 + v_add_u32                  */
+#define LBS_PROBE_MUL_LO 1       /* v_mul_lo_u32 (+ add)                   */
+#define LBS_PROBE_MUL_HI_ADD 2   /* v_mul_hi_u32 + v_add_u32               */
+#define LBS_PROBE_MED3 3         /* v_med3_u32                             */
+#define LBS_PROBE_DPP_ADD 4      /* v_mov_b32 with a DPP quad permutation + v_add_u32 */
+#define LBS_PROBE_BPERMUTE_ADD 5 /* ds_bpermute_b32 + v_add_u32            */
+#define LBS_PROBE_FMA_F32 6      /* v_fma_f32                              */
+int lbs_issue_rate_probe(int kind, uint32_t n_workgroups, uint32_t iters, uint32_t* out /*DEVICE*/, void* stream);
+
 const char* lbs_last_error(void);
 
 #ifdef __cplusplus

@@ -666,6 +666,34 @@ void fill_guide(uint32_t* out, uint32_t bits, const std::vector<uint32_t>& cum, 
   }
 }
 
+// Measurement only: how many lane-operations per second the vector units issue for the instruction kinds the
+// simulation is made of.  Pure register arithmetic on eight independent chains per lane (enough to cover every
+// instruction's latency), one store per thread at the end so that nothing is optimised away.
+template <int KIND>
+__global__ __launch_bounds__(256) void k_issue_probe(uint32_t* out, uint32_t iters, uint32_t seed) {
+  uint32_t a[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = seed * (i + 1) + threadIdx.x;
+  const uint32_t c = seed | 1u;
+  for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (KIND == LBS_PROBE_XOR_ADD) a[i] = (a[i] ^ c) + 0x9E3779B9u;
+      if (KIND == LBS_PROBE_MUL_LO) a[i] = a[i] * 0x85EBCA6Bu + 1u;
+      if (KIND == LBS_PROBE_MUL_HI_ADD) a[i] = __umulhi(a[i], c) + a[i];
+      if (KIND == LBS_PROBE_MED3) a[i] = max(min(a[i], c), min(max(a[i], c), it));
+      if (KIND == LBS_PROBE_DPP_ADD)
+        a[i] = (uint32_t)__builtin_amdgcn_update_dpp((int)a[i], (int)a[i], 0xB1, 0xf, 0xf, false) + 1u;
+      if (KIND == LBS_PROBE_BPERMUTE_ADD) a[i] = (uint32_t)__shfl_xor((int)a[i], 16, 64) + 1u;
+      if (KIND == LBS_PROBE_FMA_F32) a[i] = __float_as_uint(__fmaf_rn(__uint_as_float(a[i]), 1.0001f, 0.5f));
+    }
+  }
+  uint32_t r = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r ^= a[i];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+
 }  // namespace
 }  // namespace lbs
 
@@ -674,6 +702,26 @@ using namespace lbs;
 extern "C" {
 
 const char* lbs_last_error(void) { return g_error.c_str(); }
+
+int lbs_issue_rate_probe(int kind, uint32_t n_workgroups, uint32_t iters, uint32_t* out, void* stream) {
+  if (!out) return fail(LBS_ERR_NULL, "out is NULL");
+  if (n_workgroups == 0 || n_workgroups > (1u << 20)) return fail(LBS_ERR_ARG, "n_workgroups must lie in [1, 2^20]");
+  void (*kernel)(uint32_t*, uint32_t, uint32_t) = nullptr;
+  switch (kind) {
+    case LBS_PROBE_XOR_ADD: kernel = k_issue_probe<LBS_PROBE_XOR_ADD>; break;
+    case LBS_PROBE_MUL_LO: kernel = k_issue_probe<LBS_PROBE_MUL_LO>; break;
+    case LBS_PROBE_MUL_HI_ADD: kernel = k_issue_probe<LBS_PROBE_MUL_HI_ADD>; break;
+    case LBS_PROBE_MED3: kernel = k_issue_probe<LBS_PROBE_MED3>; break;
+    case LBS_PROBE_DPP_ADD: kernel = k_issue_probe<LBS_PROBE_DPP_ADD>; break;
+    case LBS_PROBE_BPERMUTE_ADD: kernel = k_issue_probe<LBS_PROBE_BPERMUTE_ADD>; break;
+    case LBS_PROBE_FMA_F32: kernel = k_issue_probe<LBS_PROBE_FMA_F32>; break;
+    default: return fail(LBS_ERR_ARG, "unknown probe kind");
+  }
+  hipLaunchKernelGGL(kernel, dim3(n_workgroups), dim3(256), 0, (hipStream_t)stream, out, iters, 12345u);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LBS_ERR_HIP, std::string("launching the probe: ") + hipGetErrorString(e));
+  return 0;
+}
 
 static int dataset_create(lbs_dataset** out, int device, uint32_t max_len, const uint32_t* cum, uint32_t n_strata,
                           const uint32_t* stratum_end) {

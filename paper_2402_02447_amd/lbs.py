@@ -14,7 +14,11 @@ LBS_NONE, LBS_STRATIFIED, LBS_LOCAL_RASTER, LBS_LOCAL_SNAKE, LBS_GLOBAL = 0, 1, 
 LBS_MAX_LEN, LBS_MAX_STRATA, LBS_MAX_LOCAL_BATCH, LBS_MAX_NODE_POOL = 1024, 8, 64, 1024
 _ERR = {-1: "LBS_ERR_NULL", -2: "LBS_ERR_ARG", -3: "LBS_ERR_LIMIT", -4: "LBS_ERR_HIP", -5: "LBS_ERR_HOST"}
 
-EXPORTS = ["lbs_dataset_create", "lbs_dataset_destroy", "lbs_simulate", "lbs_simulate_all", "lbs_last_error"]
+EXPORTS = ["lbs_dataset_create", "lbs_dataset_destroy", "lbs_simulate", "lbs_simulate_all", "lbs_issue_rate_probe",
+           "lbs_last_error"]
+PROBE_KINDS = {0: ("v_xor_b32 + v_add_u32", 2), 1: ("v_mul_lo_u32 (+ add)", 1), 2: ("v_mul_hi_u32 + v_add_u32", 2),
+               3: ("v_med3_u32", 1), 4: ("DPP v_mov_b32 + v_add_u32", 2), 5: ("ds_bpermute_b32 + v_add_u32", 2),
+               6: ("v_fma_f32", 1)}       # kind -> (instructions, how many of them per round and chain)
 
 
 class LbsError(RuntimeError):
@@ -42,6 +46,7 @@ def _lib():
         L.lbs_dataset_destroy.restype = None
         L.lbs_simulate.argtypes = [vp, C.POINTER(_Run), vp, vp, vp, vp]
         L.lbs_simulate_all.argtypes = [vp, C.POINTER(_Run), vp, vp, vp, vp]
+        L.lbs_issue_rate_probe.argtypes = [C.c_int, u32, u32, vp, vp]
         L.lbs_last_error.restype = C.c_char_p
         for name in EXPORTS:
             getattr(L, name)
@@ -52,6 +57,11 @@ def _lib():
 def _check(rc: int) -> None:
     if rc != 0:
         raise LbsError(rc, _lib().lbs_last_error().decode())
+
+
+def issue_rate_probe(kind: int, n_workgroups: int, iters: int, out, stream=None) -> None:
+    """lbs_issue_rate_probe: enqueue the register-arithmetic probe of one instruction kind (measurement only)."""
+    _check(_lib().lbs_issue_rate_probe(kind, n_workgroups, iters, _ptr(out), _stream(stream)))
 
 
 class Dataset:
