@@ -58,6 +58,7 @@ def parse():
     ap.add_argument("--decay-mask", action="store_true", help="exempt biases and LayerNorm tensors from weight decay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-norm", type=int, default=0)
+    ap.add_argument("--norm-item-chunks", type=int, default=0, help="fused step: squared-norm chunks per work item (0: automatic)")
     ap.add_argument("--chunk-apply", type=int, default=0)
     ap.add_argument("--unroll-apply", type=int, default=0)
     ap.add_argument("--group-mib", type=int, default=0)
@@ -345,7 +346,8 @@ def main():
     plan = B.Plan.from_layout(lay, gdt, device=0, chunk_norm=a.chunk_norm,
                               chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
                               unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20,
-                              adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10)
+                              adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10,
+                              norm_item_chunks=a.norm_item_chunks)
     plan.bind(g, p, m, v)
     if a.decay_mask:
         H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)

@@ -110,8 +110,8 @@ typedef struct bca_adam_device {
 #define BCA_TUNE_STAGE_TABLE_LDS 2u /* multi-launch kernels: persistent workgroups stage chunk-table
                                        slices in LDS                                                 */
 typedef struct bca_tuning {
-  uint32_t chunk_norm;   /* largest chunk of the squared-norm pass, elements, multiple of 1024;
-                            0: chosen from the bucket sizes (16 Ki .. 64 Ki)                     */
+  uint32_t chunk_norm;   /* largest chunk of the squared-norm pass (one set of partial sums each), elements,
+                            multiple of 1024; 0: 16 Ki, what a workgroup fetches in one go                 */
   uint32_t chunk_apply;  /* largest chunk of the scale / Adam passes, elements, multiple of 1024 */
   uint32_t grid_norm;    /* workgroups of the squared-norm kernel (0: one per chunk)            */
   uint32_t grid_apply;   /* workgroups of the scale / Adam kernels (0: one per chunk)           */
@@ -124,11 +124,14 @@ typedef struct bca_tuning {
                             each workgroup reserves without using them, which caps the workgroups resident
                             per compute unit (160 KiB each) -- the sweep streams fastest with few
                             wavefronts in flight.  0: default (48 KiB); 1: none; at most 65536       */
-  uint32_t spin_limit;   /* pipelined calls (bucket_clip_adam, bucket_clip_lamb, bucket_clip): polls of a bucket's
+  uint32_t spin_limit;   /* pipelined calls (bucket_clip_adam, bucket_clip_lamb): polls of a bucket's
                             ready word after which a waiting work item gives up, is handed to the call's finish
                             kernel and BCA_STATUS_TIMEOUT is reported; 0: default (2^18, about a second).  Small
                             values exist for tests of that path: every kernel still ends normally and the
                             result is the same                                                            */
+  uint32_t norm_item_chunks; /* fused calls: consecutive squared-norm chunks one work item reads, 1 .. 4;
+                            0: chosen from the bucket sizes so that an item reads 16 Ki .. 64 Ki elements
+                            (1 when chunk_norm is given)                                               */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */
@@ -180,6 +183,7 @@ void bca_plan_destroy(bca_plan* plan);
  * order for LAMB. */
 uint32_t bca_plan_num_buckets(const bca_plan* plan);
 uint32_t bca_plan_num_groups(const bca_plan* plan);
+uint32_t bca_plan_norm_item_chunks(const bca_plan* plan); /* squared-norm chunks per work item of the fused step */
 uint32_t bca_plan_num_chunks(const bca_plan* plan, int table);
 /* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
 int bca_plan_chunk_info(const bca_plan* plan, int table, uint32_t i, uint32_t* tensor, uint64_t* begin,
@@ -206,12 +210,14 @@ int bucket_clip_apply(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thr
                       const float* norms /*DEVICE [B]*/, float* coefs /*DEVICE [B] or NULL*/,
                       int32_t* status /*DEVICE or NULL*/, void* stream);
 
-/* bucket_clip_norms followed by bucket_clip_apply on buckets [b0, b1) as one pipelined
- * launch, for the paper's use of the method: a bucket is clipped as soon as backward
- * has produced it, before its all-reduce (Sec. 4.2, Alg. 1).  Same norms, coefficients
- * and scaled gradients, bit for bit.  norms / coefs (DEVICE [B], entries b0..b1-1
+/* bucket_clip_norms followed by bucket_clip_apply on buckets [b0, b1) in one call, for the
+ * paper's use of the method: a bucket is clipped as soon as backward has produced it,
+ * before its all-reduce (Sec. 4.2, Alg. 1).  Same norms, coefficients and scaled
+ * gradients, bit for bit.  Two launches: the squared-norm partials, then a kernel whose
+ * workgroups each derive their bucket's coefficient from the partials and scale a chunk;
+ * no workgroup waits for another.  norms / coefs (DEVICE [B], entries b0..b1-1
  * written) and status (DEVICE int32, written: BCA_STATUS_NONFINITE, _BAD_THRESHOLD as in
- * bucket_clip_apply, and BCA_STATUS_TIMEOUT as in bucket_clip_adam) may each be NULL. */
+ * bucket_clip_apply) may each be NULL. */
 int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* thresholds /*DEVICE [B]*/, float* norms,
                 float* coefs, int32_t* status, void* stream);
 
@@ -220,14 +226,14 @@ int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* threshold
  * grad_dtype at g (DEVICE) is clipped in place against *threshold (DEVICE, one float): norm and
  * factor as in bucket_clip_apply, written to *norm / *coef / *status (DEVICE, each may be NULL;
  * status is written, not ORed).  The call allocates nothing and calls no allocating routine: its
- * partial sums live in a fixed array of 512.25 KiB inside the library's device image (every GPU
+ * partial sums live in a fixed array of 512 KiB inside the library's device image (every GPU
  * the library runs on holds that array until the process ends), looked up once per device at the
  * first call made with that device current.  Limit: n <= 2^28 elements, else BCA_ERR_RANGE and
  * nothing is enqueued.  g must be on the device that is current at the call.  All calls on one
  * GPU share the array: calls that overlap in time on one GPU (different streams) race; calls in
  * stream order are fine, each call writes what it later reads and needs nothing cleared.
  * Results equal bucket_clip's on a one-tensor, one-bucket plan with chunk_norm = 16384, bit for
- * bit.  Only enqueues (three kernels). */
+ * bit.  Only enqueues (two kernels). */
 int bucket_clip_flat(void* g /*DEVICE*/, uint64_t n, int grad_dtype, const float* threshold /*DEVICE*/,
                      float* norm /*DEVICE or NULL*/, float* coef /*DEVICE or NULL*/,
                      int32_t* status /*DEVICE or NULL*/, void* stream);

@@ -25,7 +25,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
 EXPORTS = ["bca_alg1_thresholds", "bucket_clip_flat", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
-           "bca_plan_num_groups", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
+           "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
            "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error",
            "bca_version"]
@@ -49,7 +49,8 @@ class _Adam(C.Structure):
 class _Tuning(C.Structure):
     _fields_ = [("chunk_norm", C.c_uint32), ("chunk_apply", C.c_uint32), ("grid_norm", C.c_uint32),
                 ("grid_apply", C.c_uint32), ("unroll_apply", C.c_uint32), ("flags", C.c_uint32),
-                ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("spin_limit", C.c_uint32)]
+                ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("spin_limit", C.c_uint32),
+                ("norm_item_chunks", C.c_uint32)]
 
 
 @dataclass
@@ -111,6 +112,8 @@ def load_library():
     L.bca_plan_num_buckets.restype = u32
     L.bca_plan_num_groups.argtypes = [vp]
     L.bca_plan_num_groups.restype = u32
+    L.bca_plan_norm_item_chunks.argtypes = [vp]
+    L.bca_plan_norm_item_chunks.restype = u32
     L.bca_plan_num_chunks.argtypes = [vp, i32]
     L.bca_plan_num_chunks.restype = u32
     L.bca_plan_chunk_info.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
@@ -181,7 +184,7 @@ class Plan:
                  seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
                  chunk_norm: int = 0, chunk_apply: int = 0, grid_norm: int = 0, grid_apply: int = 0,
                  unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0, adam_lds_reserve: int = 0,
-                 spin_limit: int = 0):
+                 spin_limit: int = 0, norm_item_chunks: int = 0):
         L = load_library()
         self._L = L
         self._h = C.c_void_p()
@@ -192,7 +195,7 @@ class Plan:
         for i in range(n_seg):
             segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
         tune = _Tuning(chunk_norm, chunk_apply, grid_norm, grid_apply, unroll_apply, tune_flags, group_bytes,
-                       adam_lds_reserve, spin_limit)
+                       adam_lds_reserve, spin_limit, norm_item_chunks)
         _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
                                  len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
                                  C.byref(tune)))
@@ -233,6 +236,10 @@ class Plan:
     @property
     def n_groups(self) -> int:
         return int(self._L.bca_plan_num_groups(self._h))
+
+    @property
+    def norm_item_chunks(self) -> int:
+        return int(self._L.bca_plan_norm_item_chunks(self._h))
 
     def n_chunks(self, table: int = BCA_TABLE_APPLY) -> int:
         return int(self._L.bca_plan_num_chunks(self._h, table))

@@ -181,17 +181,17 @@ void build_groups(bca_plan* p, uint64_t group_bytes, const uint64_t* seg_off, co
   p->groups.emplace_back(first, p->n_buckets);
 }
 
-// Squared-norm chunk size when the caller names none: the largest power of two in
-// [16 Ki, 64 Ki] that still gives an average bucket group 160 chunks or more.  Fewer, larger
-// chunks mean fewer partial sums and arrivals; but a group's squared-norm items are all
-// that keeps its Adam items from waiting, and below ~200 of them (256 CUs) they finish
-// late (measured: 64 Ki best for 50 MiB buckets, 32 Ki for 25 MiB and 4 MiB ones).
-uint32_t default_chunk_norm(const bca_plan* p, const uint64_t* seg_off, const bca_segment* segs) {
+// Elements a squared-norm item of the fused step reads when the caller does not say: the largest power of
+// two in [16 Ki, 64 Ki] that still gives an average bucket group 160 items or more.  Fewer, larger items
+// mean fewer workgroups and arrivals; but a group's squared-norm items are all that keeps its Adam items
+// from waiting, and below ~200 of them (256 CUs) they finish late (measured: 64 Ki best for 50 MiB
+// buckets, 32 Ki for 25 MiB and 4 MiB ones).
+uint32_t default_norm_item_elems(const bca_plan* p, const uint64_t* seg_off, const bca_segment* segs) {
   uint64_t total = 0;
   for (uint64_t s = 0; s < seg_off[p->n_buckets]; ++s) total += segs[s].len;
   const uint64_t per_group = total / std::max<size_t>(p->groups.size(), 1);
-  uint32_t c = kDefaultChunkNorm;
-  while (c > kMinAutoChunkNorm && per_group / c < 160) c >>= 1;
+  uint32_t c = kMaxNormItemElems;
+  while (c > kMinNormItemElems && per_group / c < 160) c >>= 1;
   return c;
 }
 
@@ -203,10 +203,15 @@ void build_work(bca_plan* p) {
   p->work.clear();
   const Table& TN = p->norm_tab;
   const Table& TA = p->apply_tab;
+  const uint32_t span = std::min(std::max(p->norm_item_chunks, 1u), kMaxNormItemChunks);
   auto push_norm = [&](const std::pair<uint32_t, uint32_t>& g) {
     for (uint32_t b = g.first; b < g.second; ++b) {
       if (TN.bucket_off[b] == TN.bucket_off[b + 1]) p->work.push_back((kItemEmpty << 30) | b);
-      for (uint32_t c = TN.bucket_off[b]; c < TN.bucket_off[b + 1]; ++c) p->work.push_back((kItemNorm << 30) | c);
+      // an item is up to `span` consecutive chunks of one bucket: first chunk in bits 0..27, count - 1 in bits 28..29
+      for (uint32_t c = TN.bucket_off[b]; c < TN.bucket_off[b + 1]; c += span) {
+        const uint32_t cnt = std::min(span, TN.bucket_off[b + 1] - c);
+        p->work.push_back((kItemNorm << 30) | ((cnt - 1u) << 28) | c);
+      }
     }
   };
   auto push_adam = [&](const std::pair<uint32_t, uint32_t>& g) {
@@ -376,6 +381,15 @@ int enqueue_hyper(const bca_plan* p, hipStream_t stream) {
   return e == hipSuccess ? BCA_OK : fail_hip(e, "launching the hyper-parameter kernel");
 }
 
+// Workgroups of a stand-alone squared-norm launch over n chunks: the plan's grid_norm if the caller set one, else
+// as many as the fused step would use items for them (a workgroup then reads several 16 Ki chunks, which streams
+// better than one workgroup per chunk once there are thousands of chunks).
+uint32_t norm_grid(const bca_plan* p, uint32_t n_chunks) {
+  if (p->grid_norm) return p->grid_norm;
+  const uint32_t span = std::max(p->norm_item_chunks, 1u);
+  return (n_chunks + span - 1) / span;
+}
+
 // requested == 0: one workgroup per chunk.
 Launch make_launch(const bca_plan* p, uint32_t requested, uint32_t n_chunks, bool g_keep) {
   const uint32_t g = requested ? std::min(requested, n_chunks) : n_chunks;
@@ -425,6 +439,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
     if (tuning->flags & ~(BCA_TUNE_MULTI_LAUNCH | BCA_TUNE_STAGE_TABLE_LDS | BCA_TUNE_TICKETS))
       return fail(BCA_ERR_RANGE, "unknown tuning flag bits");
     if (tuning->adam_lds_reserve > 65536) return fail(BCA_ERR_RANGE, "adam_lds_reserve must be at most 65536");
+    if (tuning->norm_item_chunks > kMaxNormItemChunks) return fail(BCA_ERR_RANGE, "norm_item_chunks must be at most 4");
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
@@ -451,8 +466,17 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
   p->decay.assign(n_tensors, 1);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
-  if (chunk_norm == 0) chunk_norm = default_chunk_norm(p, bucket_seg_off, segments);
+  if (tuning && tuning->norm_item_chunks) {
+    p->norm_item_chunks = tuning->norm_item_chunks;
+  } else if (chunk_norm == 0) {
+    p->norm_item_chunks = default_norm_item_elems(p, bucket_seg_off, segments) / kDefaultChunkNorm;
+  } else {
+    p->norm_item_chunks = 1;  // a caller who names the chunk gets one chunk per item unless told otherwise
+  }
+  if (chunk_norm == 0) chunk_norm = kDefaultChunkNorm;
   build_table(&p->norm_tab, chunk_norm, n_buckets, bucket_seg_off, segments);
+  if (p->norm_tab.chunks.size() >= (1ull << 28))
+    return fail(BCA_ERR_RANGE, "too many squared-norm chunks; raise chunk_norm");
   build_table(&p->apply_tab, chunk_apply, n_buckets, bucket_seg_off, segments);
   build_tensor_table(&p->lamb_tab, &p->tensor_off, chunk_apply, n_tensors, n_buckets, bucket_seg_off, segments);
   build_work(p);
@@ -614,6 +638,8 @@ uint32_t bca_plan_num_chunks(const bca_plan* p, int which) {
 
 uint32_t bca_plan_num_groups(const bca_plan* p) { return p ? (uint32_t)p->groups.size() : 0; }
 
+uint32_t bca_plan_norm_item_chunks(const bca_plan* p) { return p ? p->norm_item_chunks : 0; }
+
 int bca_plan_chunk_info(const bca_plan* p, int which, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
                         uint32_t* bucket) {
   const Table* t = pick_table(p, which);
@@ -718,7 +744,7 @@ int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void*
   // Called per bucket as buckets become ready, bucket_clip_apply follows shortly:
   // keep the gradients cacheable.
   hipError_t e = launch_sqnorm(p->grad_dtype, T.d_chunks, c0, n, p->d_partials, nullptr,
-                               make_launch(p, p->grid_norm, n, true), s);
+                               make_launch(p, norm_grid(p, n), n, true), s);
   if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
   e = launch_finalize(p->d_partials, T.d_bucket_off, b0, b1, nullptr, norms, nullptr, nullptr, nullptr, s);
   if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
@@ -753,15 +779,32 @@ int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, 
   if (int rc = check_ready(p)) return rc;
   if (b0 == b1) return BCA_OK;
   DeviceGuard g(p->device);
-  const StepState ss = step_state(p);
+  hipStream_t s = (hipStream_t)stream;
   const Table& TN = p->norm_tab;
-  const Table& TA = p->apply_tab;
   const uint32_t cn0 = TN.bucket_off[b0], nn = TN.bucket_off[b1] - cn0;
+  float* nm = norms ? norms : p->d_norms;
+  float* cf = coefs ? coefs : p->d_coefs;
+  int32_t* st = status ? status : p->d_status;
+  uint32_t most = 0;  // chunks of the range's largest bucket
+  for (uint32_t b = b0; b < b1; ++b) most = std::max(most, TN.bucket_off[b + 1] - TN.bucket_off[b]);
+  // First launch: the squared-norm partials of the range's chunks (one workgroup per chunk: a single bucket has
+  // few of them); it also clears the status word.
+  hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, cn0, nn, p->d_partials, st, make_launch(p, 0, nn, true), s);
+  if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
+  if (most <= kMaxChunksForInlineFinalize && !(p->tune_flags & BCA_TUNE_MULTI_LAUNCH)) {
+    // Second launch: one workgroup per chunk derives the bucket's coefficient from the partials and scales the chunk.
+    e = launch_clip_scale(p->grad_dtype, TN.d_chunks, cn0, nn, TN.d_bucket_off, b0, b1, p->d_partials, thresholds, nm, cf,
+                          st, s);
+    if (e != hipSuccess) return fail_hip(e, "launching the clip kernel");
+    return BCA_OK;
+  }
+  // Very large buckets: the finalize and scale kernels of bucket_clip_norms / bucket_clip_apply instead.
+  e = launch_finalize(p->d_partials, TN.d_bucket_off, b0, b1, thresholds, nm, cf, st, nullptr, s);
+  if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
+  const Table& TA = p->apply_tab;
   const uint32_t ca0 = TA.bucket_off[b0], na = TA.bucket_off[b1] - ca0;
-  hipError_t e = launch_clip(p->grad_dtype, ss, b0, b1, cn0, nn, ca0, na, thresholds, norms ? norms : p->d_norms,
-                             coefs ? coefs : p->d_coefs, status ? status : p->d_status, p->unroll_apply,
-                             (hipStream_t)stream);
-  if (e != hipSuccess) return fail_hip(e, "launching the clip kernel");
+  e = launch_scale(p->grad_dtype, TA.d_chunks, ca0, na, cf, make_launch(p, p->grid_apply, na, true), s);
+  if (e != hipSuccess) return fail_hip(e, "launching the scale kernel");
   return BCA_OK;
 }
 
@@ -857,7 +900,7 @@ int bucket_clip_adam(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     const uint32_t ca0 = TA.bucket_off[b0], na = TA.bucket_off[b1] - ca0;
     // the first squared-norm launch of a call also clears the status word
     hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, cn0, nn, p->d_partials, first ? st : nullptr,
-                                 make_launch(p, p->grid_norm, nn, keep), s);
+                                 make_launch(p, norm_grid(p, nn), nn, keep), s);
     if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
     if (ev) (void)hipEventRecord(*ev++, s);
     e = launch_finalize(p->d_partials, TN.d_bucket_off, b0, b1, whole ? nullptr : thresholds, nm, cf, st,
@@ -900,7 +943,7 @@ static int lamb_impl(bca_plan* p, const float* thresholds, const bca_adam* hp, u
     } else {
       const Table& TN = p->norm_tab;
       const uint32_t nn = (uint32_t)TN.chunks.size();
-      e = launch_sqnorm(p->grad_dtype, TN.d_chunks, 0, nn, p->d_partials, st, make_launch(p, 0, nn, false), s);
+      e = launch_sqnorm(p->grad_dtype, TN.d_chunks, 0, nn, p->d_partials, st, make_launch(p, norm_grid(p, nn), nn, false), s);
       if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
       e = launch_finalize(p->d_partials, TN.d_bucket_off, 0, p->n_buckets, thresholds, nm, cw, st, nullptr, s);
       if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");

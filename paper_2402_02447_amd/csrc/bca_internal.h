@@ -62,8 +62,17 @@ struct AdamK {
 constexpr uint32_t kBlock = 256;          // threads per workgroup (4 wavefronts)
 constexpr uint32_t kWaves = kBlock / 64;  // wavefronts per workgroup
 constexpr uint32_t kSlice = 64;           // chunk-table entries staged in LDS at a time
-constexpr uint32_t kDefaultChunkNorm = 65536;  // upper end of the automatic choice
-constexpr uint32_t kMinAutoChunkNorm = 16384;  // lower end
+// Squared-norm chunk: partial sums are filed per 16 Ki elements (four doubles each).  That is what one
+// workgroup fetches in one go (16 or 8 128-bit loads per lane), which is what a single bucket needs to be read
+// fast; the fused step hands out 1, 2 or 4 consecutive chunks per work item, so that an item reads
+// 16 Ki .. 64 Ki elements.
+constexpr uint32_t kDefaultChunkNorm = 16384;
+constexpr uint32_t kSmallNormGrid = 2048;       // squared-norm launches of at most this many workgroups fetch 16 pieces per lane at a time
+// bucket_clip derives the coefficient in every workgroup from the bucket's partial sums; beyond this many chunks in
+// one bucket (64 MiB of fp32) that costs more than a finalize launch of its own
+constexpr uint32_t kMaxChunksForInlineFinalize = 1024;
+constexpr uint32_t kMaxNormItemChunks = 4;
+constexpr uint32_t kMinNormItemElems = 16384, kMaxNormItemElems = 65536;
 constexpr uint32_t kDefaultChunkApply = 1024;
 // Buckets are pipelined in groups of about this many elements (at least one bucket):
 // large enough that a group's norms are done before its Adam items start, small enough
@@ -86,23 +95,22 @@ struct Launch {
                     // how many workgroups a compute unit holds at once
 };
 
-// Device-side state of the pipelined launches (k_step / k_clip, each followed by its finish kernel).
+// Device-side state of the pipelined launch (k_step, followed by its finish kernel).
 // Control words, each in its own 128-byte line: eight ticket counters (one per XCD) at
 // kCtlTicket + 32 y; the epoch (number of the current call, never 0); the abort flag; the number
 // of work items whose wait expired (their indices are in StepState::skipped); the status bits
-// collected during the call; the arrival counter of the finish kernel's workgroups.  The finish
-// kernel of a call leaves all of them ready for the next call.
+// collected during the call.  The finish kernel of a call leaves all of them ready for the next call.
 enum : uint32_t {
   kCtlTicket = 0,
   kCtlEpoch = 256,
   kCtlAbort = 288,
   kCtlSkipped = 320,
   kCtlStatus = 352,
-  kCtlFinish = 384,
-  kCtlWords = 416
+  kCtlWords = 384
 };
-constexpr uint32_t kFinishGrid = 32;  // workgroups of the finish kernels
-constexpr uint32_t kItemNorm = 0u, kItemAdam = 1u, kItemEmpty = 2u;  // work item kinds, in bits 30..31 of an item
+// Work items of k_step: kind in bits 30..31; kItemAdam: apply-table chunk in bits 0..29; kItemNorm: first
+// norm-table chunk in bits 0..27 and the number of consecutive chunks minus one in bits 28..29; kItemEmpty: bucket.
+constexpr uint32_t kItemNorm = 0u, kItemAdam = 1u, kItemEmpty = 2u;
 struct StepState {
   const Chunk* norm_tab;
   const Chunk* apply_tab;
@@ -146,11 +154,11 @@ hipError_t launch_step(int gdt, const StepState& st, const uint32_t* work, uint3
                        float* norms, float* coefs, int32_t* status, bool write_back, const AdamK& k, uint32_t unroll,
                        bool tickets, bool lamb, hipEvent_t between, hipStream_t stream);
 
-// Clipping of buckets [b0, b1) in one launch (k_clip, then its finish kernel): cn0 / n_norm
-// and ca0 / n_apply are the range's chunks in the norm and the apply table.
-hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
-                       uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
-                       int32_t* status, uint32_t unroll, hipStream_t stream);
+// Second launch of bucket_clip (after launch_sqnorm with a status word, which clears it):
+// per squared-norm chunk, the bucket's norm and coefficient from the partial sums, then the chunk scaled.
+hipError_t launch_clip_scale(int gdt, const Chunk* norm_tab, uint32_t cn0, uint32_t n, const uint32_t* bucket_chunk_off,
+                             uint32_t b0, uint32_t b1, const double* partials, const float* thresholds, float* norms,
+                             float* coefs, int32_t* status, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 
 // bucket_clip_flat: one contiguous bucket of n <= kFlatMaxElems elements at g, clipped in place with partial
@@ -185,6 +193,7 @@ struct bca_plan {
   uint32_t grid_norm = 0, grid_apply = 0;  // 0: one workgroup per chunk
   uint32_t unroll_apply = 1;
   uint32_t adam_lds_reserve = 0;  // bytes; see bca_tuning::adam_lds_reserve
+  uint32_t norm_item_chunks = 1;  // consecutive norm-table chunks per squared-norm item of the fused step
   uint32_t spin_limit = 0;        // see bca_tuning::spin_limit (default already applied)
   const bca_adam_device* hyper_dev = nullptr;  // hyper-parameters in device memory, when set
   bca::AdamK* d_adamk = nullptr;  // the constants derived from them by k_hyper

@@ -46,15 +46,30 @@ typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 // NT = non-temporal: data that is touched once per launch is loaded and stored
 // with the streaming hint, which raises HBM throughput on gfx950 and keeps such
 // lines from displacing reusable ones in L2 / Infinity Cache.
+//
+// Tensor addresses come out of the chunk table as integers, so the compiler cannot tell that they are global
+// memory and would emit flat accesses; those may complete out of order, which forces a full wait
+// (vmcnt(0) lgkmcnt(0)) before the first use of any of them and leaves only two or three of a batch of
+// loads in flight.  Every access to tensor memory therefore goes through a pointer that is explicitly in the
+// global address space: global_load / global_store, counted waits, all loads of a batch in flight.
+// loads_issued(): nothing is scheduled across this point, so a batch of loads written before it is issued as a
+// whole before the first instruction that uses one of them (left to itself the scheduler interleaves loads and
+// uses in pairs, which leaves two loads in flight where eight or sixteen were meant).
+__device__ __forceinline__ void loads_issued() { __builtin_amdgcn_sched_barrier(0); }
+#define BCA_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ BCA_GLOBAL T* as_global(T* p) {
+  return (BCA_GLOBAL T*)p;
+}
 template <bool NT, typename T>
 __device__ __forceinline__ T ldv(const T* p) {
-  if constexpr (NT) return __builtin_nontemporal_load(p);
-  else return *p;
+  if constexpr (NT) return __builtin_nontemporal_load(as_global(p));
+  else return *as_global(p);
 }
 template <bool NT, typename T>
 __device__ __forceinline__ void stv(T* p, T x) {
-  if constexpr (NT) __builtin_nontemporal_store(x, p);
-  else *p = x;
+  if constexpr (NT) __builtin_nontemporal_store(x, as_global(p));
+  else *as_global(p) = x;
 }
 
 // ---- chunk table access -----------------------------------------------------------
@@ -122,6 +137,11 @@ struct Grad<BCA_GRAD_F32> {
   static __device__ __forceinline__ void widen(const wide& x, float (&f)[VE]) {
     f[0] = x.x, f[1] = x.y, f[2] = x.z, f[3] = x.w;
   }
+  static __device__ __forceinline__ wide narrow(const float (&f)[VE]) {
+    wide x;
+    x.x = f[0], x.y = f[1], x.z = f[2], x.w = f[3];
+    return x;
+  }
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
     return ldv<NT>(reinterpret_cast<const f32x4*>(base) + vec);
@@ -131,10 +151,10 @@ struct Grad<BCA_GRAD_F32> {
     stv<NT>(reinterpret_cast<f32x4*>(base) + vec, x);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
-    return reinterpret_cast<const float*>(base)[i];
+    return as_global(reinterpret_cast<const float*>(base))[i];
   }
   static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
-    reinterpret_cast<float*>(base)[i] = x;
+    as_global(reinterpret_cast<float*>(base))[i] = x;
   }
 };
 
@@ -155,6 +175,12 @@ struct Grad<BCA_GRAD_F16> {
     asm volatile("" : "+v"(x));
     return x;
   }
+  static __device__ __forceinline__ wide narrow(const float (&f)[VE]) {  // the rounding of store4 / store1
+    wide x;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) x[q] = (_Float16)settled(f[q]);
+    return x;
+  }
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
     const f16x4 h = ldv<NT>(reinterpret_cast<const f16x4*>(base) + vec);
@@ -169,10 +195,10 @@ struct Grad<BCA_GRAD_F16> {
     stv<NT>(reinterpret_cast<f16x4*>(base) + vec, h);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
-    return (float)reinterpret_cast<const _Float16*>(base)[i];
+    return (float)as_global(reinterpret_cast<const _Float16*>(base))[i];
   }
   static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
-    reinterpret_cast<_Float16*>(base)[i] = (_Float16)settled(x);
+    as_global(reinterpret_cast<_Float16*>(base))[i] = (_Float16)settled(x);
   }
 };
 
@@ -196,6 +222,12 @@ struct Grad<BCA_GRAD_BF16> {
 #pragma unroll
     for (int q = 0; q < 8; ++q) f[q] = bf16_to_f32(x[q]);
   }
+  static __device__ __forceinline__ wide narrow(const float (&f)[VE]) {
+    wide x;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) x[q] = f32_to_bf16(f[q]);
+    return x;
+  }
   template <bool NT>
   static __device__ __forceinline__ f32x4 load4(const void* base, uint32_t vec) {
     const u16x4 h = ldv<NT>(reinterpret_cast<const u16x4*>(base) + vec);
@@ -210,10 +242,10 @@ struct Grad<BCA_GRAD_BF16> {
     stv<NT>(reinterpret_cast<u16x4*>(base) + vec, h);
   }
   static __device__ __forceinline__ float load1(const void* base, uint32_t i) {
-    return bf16_to_f32(reinterpret_cast<const unsigned short*>(base)[i]);
+    return bf16_to_f32(as_global(reinterpret_cast<const unsigned short*>(base))[i]);
   }
   static __device__ __forceinline__ void store1(void* base, uint32_t i, float x) {
-    reinterpret_cast<unsigned short*>(base)[i] = f32_to_bf16(x);
+    as_global(reinterpret_cast<unsigned short*>(base))[i] = f32_to_bf16(x);
   }
 };
 
@@ -242,16 +274,30 @@ __device__ __forceinline__ double wave_sum(double x) {
 
 // ---- squared-norm partials ------------------------------------------------------
 
+// Adds the squares of one 128-bit piece to the lane's four fp32 accumulators: element q of the piece goes to
+// accumulator q mod 4, in element order.  Every squared-norm path goes through this one function, so that a
+// chunk's partial sums do not depend on which kernel computed them.
+template <int GDT>
+__device__ __forceinline__ void add_squares(const typename Grad<GDT>::wide& x, float& a0, float& a1, float& a2, float& a3) {
+  constexpr uint32_t VE = Grad<GDT>::VE;
+  float f[VE];
+  Grad<GDT>::widen(x, f);
+#pragma unroll
+  for (uint32_t q = 0; q < VE; q += 4) {
+    a0 = __fmaf_rn(f[q], f[q], a0), a1 = __fmaf_rn(f[q + 1], f[q + 1], a1);
+    a2 = __fmaf_rn(f[q + 2], f[q + 2], a2), a3 = __fmaf_rn(f[q + 3], f[q + 3], a3);
+  }
+}
+
 // Sum of g^2 over the part of a chunk this wavefront reads, in fp64 (same value
 // in every lane).  Per lane the squares are accumulated in fp32 (four independent
 // accumulators, at most chunk_elems/1024 terms each), then the lanes are combined
 // in fp64 by butterfly shuffles.  Wavefronts never wait for each other.
-template <int GDT, bool NT>
+template <int GDT, bool NT, uint32_t U = 8>  // U: 128-bit loads in flight per lane (the result does not depend on it)
 __device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
   typedef Grad<GDT> G;
   constexpr uint32_t gsize = sizeof(typename G::elem);
   constexpr uint32_t VE = G::VE;  // elements per 128-bit load: 4 (fp32) or 8 (fp16, bf16)
-  constexpr uint32_t U = 8;       // loads in flight per lane
   const uint32_t tid = threadIdx.x;
   const uint64_t ga = en.g;
   const uint32_t len = en.len;
@@ -264,29 +310,25 @@ __device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
 
   typedef typename G::wide wide;
   const wide* gw = reinterpret_cast<const wide*>(gv);
-  auto add_squares = [&](const wide& x) {
-    float f[VE];
-    G::widen(x, f);
-#pragma unroll
-    for (uint32_t q = 0; q < VE; q += 4) {
-      a0 = __fmaf_rn(f[q], f[q], a0), a1 = __fmaf_rn(f[q + 1], f[q + 1], a1);
-      a2 = __fmaf_rn(f[q + 2], f[q + 2], a2), a3 = __fmaf_rn(f[q + 3], f[q + 3], a3);
-    }
-  };
+  // Lane t adds pieces t, t + 256, t + 512, ... in that order.  They are fetched U at a time; a slot past the end
+  // of the chunk holds zeros, whose squares leave the (non-negative) accumulators as they are.
   for (uint32_t base = 0; base < nvec; base += kBlock * U) {
     const uint32_t j0 = base + tid;
+    wide x[U];
     if (base + kBlock * U <= nvec) {
-      wide x[U];
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) x[u] = ldv<NT>(gw + j0 + u * kBlock);
-#pragma unroll
-      for (uint32_t u = 0; u < U; ++u) add_squares(x[u]);
     } else {
+#pragma unroll
       for (uint32_t u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * kBlock;
-        if (j < nvec) add_squares(ldv<NT>(gw + j));
+        x[u] = wide{};
+        if (j < nvec) x[u] = ldv<NT>(gw + j);
       }
     }
+    loads_issued();
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) add_squares<GDT>(x[u], a0, a1, a2, a3);
   }
   // head and tail elements one by one (fewer than VE each unless the chunk is unaligned throughout)
   for (uint32_t i = tid; i < head; i += kBlock) {
@@ -303,13 +345,13 @@ __device__ __forceinline__ double sqnorm_chunk(const Entry& en) {
 
 // kWaves partials (fp64) per chunk, one per wavefront.  The finalize pass adds a
 // bucket's partials in a fixed order.
-template <int GDT, bool NT, bool STAGED>
+template <int GDT, bool NT, bool STAGED, uint32_t U>
 __global__ __launch_bounds__(kBlock) void k_sqnorm(const Chunk* __restrict__ table, uint32_t c0, uint32_t n,
                                                     double* __restrict__ partials, int32_t* status) {
   const uint32_t tid = threadIdx.x;
   if (status != nullptr && blockIdx.x == 0 && tid == 0) *status = 0;  // finalize ORs into it later on this stream
   for_each_chunk<STAGED>(table, c0, n, [&](const Entry& en, uint32_t ci) {
-    const double ws = sqnorm_chunk<GDT, NT>(en);
+    const double ws = sqnorm_chunk<GDT, NT, U>(en);
     if ((tid & 63u) == 0) partials[(uint64_t)ci * kWaves + (tid >> 6)] = ws;
   });
 }
@@ -421,6 +463,7 @@ __device__ __forceinline__ void scale_chunk(const Entry& en, float coef) {
       f32x4 x[U];
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) x[u] = G::template load4<NT>(gv, j0 + u * kBlock);
+      loads_issued();
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) G::template store4<NT>(gv, j0 + u * kBlock, x[u] * coef);
     } else {
@@ -539,6 +582,7 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
       for (uint32_t u = 0; u < U; ++u) m[u] = ldv<NT>(mv + j0 + u * kBlock);
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) v[u] = ldv<NT>(vv + j0 + u * kBlock);
+      loads_issued();
 #pragma unroll
       for (uint32_t u = 0; u < U; ++u) {
         if constexpr (FUSED) g[u] = g[u] * coef;
@@ -562,9 +606,9 @@ __device__ __forceinline__ void adam_chunk(const Entry& en, float coef, const Ad
   }
   // head and tail, element-wise
   void* gbase = reinterpret_cast<void*>(ga);
-  float* p1 = reinterpret_cast<float*>(pa);
-  float* m1 = reinterpret_cast<float*>(ma);
-  float* v1 = reinterpret_cast<float*>(va);
+  BCA_GLOBAL float* p1 = as_global(reinterpret_cast<float*>(pa));
+  BCA_GLOBAL float* m1 = as_global(reinterpret_cast<float*>(ma));
+  BCA_GLOBAL float* v1 = as_global(reinterpret_cast<float*>(va));
   for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
     const uint32_t i = r < head ? r : tail0 + (r - head);
     float g = G::load1(gbase, i), p = p1[i], m = m1[i], v = v1[i];
@@ -646,9 +690,9 @@ __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, 
     if (wb) G::template store4<GNT>(gv, j, g);
   }
   void* gbase = reinterpret_cast<void*>(en.g);
-  const float* p1 = reinterpret_cast<const float*>(en.p);
-  float* m1 = reinterpret_cast<float*>(en.m);
-  float* v1 = reinterpret_cast<float*>(en.v);
+  const BCA_GLOBAL float* p1 = as_global(reinterpret_cast<const float*>(en.p));
+  BCA_GLOBAL float* m1 = as_global(reinterpret_cast<float*>(en.m));
+  BCA_GLOBAL float* v1 = as_global(reinterpret_cast<float*>(en.v));
   for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
     const uint32_t i = r < head ? r : tail0 + (r - head);
     float g = G::load1(gbase, i), m = m1[i], v = v1[i];
@@ -733,9 +777,9 @@ __global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict_
       for (int i = 0; i < 4; ++i) p[i] = __fmaf_rn(sc, adam_direction(p[i], m[i], v[i], k, wd), p[i]);
       stv<true>(pv + j, p);
     }
-    float* p1 = reinterpret_cast<float*>(en.p);
-    const float* m1 = reinterpret_cast<const float*>(en.m);
-    const float* v1 = reinterpret_cast<const float*>(en.v);
+    BCA_GLOBAL float* p1 = as_global(reinterpret_cast<float*>(en.p));
+    const BCA_GLOBAL float* m1 = as_global(reinterpret_cast<const float*>(en.m));
+    const BCA_GLOBAL float* v1 = as_global(reinterpret_cast<const float*>(en.v));
     for (uint32_t r = tid; r < head + (len - tail0); r += kBlock) {
       const uint32_t i = r < head ? r : tail0 + (r - head);
       p1[i] = __fmaf_rn(sc, adam_direction(p1[i], m1[i], v1[i], k, wd), p1[i]);
@@ -856,25 +900,20 @@ __device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b,
 // after its increment has returned.  A workgroup-scope release fence would not do: on
 // this target it does not wait for vector stores, so the arrival could be counted
 // while a partial is still on its way.
-template <int GDT>
-__device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, uint32_t idx, uint32_t epoch,
-                                          const float* __restrict__ thresholds, float* __restrict__ norms,
-                                          float* __restrict__ coefs, StepShared& sh) {
+// The tail of every squared-norm item.  `stored` chunks' partials of bucket b have just been written by this
+// workgroup (0: a bucket without elements, nothing to count): waits for them, counts the arrival, and if
+// this workgroup completes the bucket, finalizes it and publishes the ready word.
+__device__ __forceinline__ void norm_arrive(const StepState& st, uint32_t b, uint32_t stored, uint32_t epoch,
+                                            const float* __restrict__ thresholds, float* __restrict__ norms,
+                                            float* __restrict__ coefs, StepShared& sh) {
   const uint32_t tid = threadIdx.x;
-  uint32_t b = idx;
-  if (kind == kItemNorm) {
-    const Entry en = read_entry(&st.norm_tab[idx]);
-    b = en.bucket;
-    const double ws = sqnorm_chunk<GDT, false>(en);
-    if ((tid & 63u) == 0)
-      __hip_atomic_store(&st.partials[(uint64_t)idx * kWaves + (tid >> 6)], ws, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-    wait_vmem();  // the partial has been acknowledged ...
-    __syncthreads();  // ... by every wavefront of the workgroup
+  if (stored != 0) {
+    wait_vmem();      // the partials have been acknowledged ...
+    __syncthreads();  // ... for every wavefront of the workgroup
     if (tid == 0) {
       const uint32_t total = st.norm_bucket_off[b + 1] - st.norm_bucket_off[b];
-      const uint32_t old = atomicAdd(&st.arrived[b], 1u);
-      const bool last = (old + 1u == total);
+      const uint32_t old = atomicAdd(&st.arrived[b], stored);
+      const bool last = (old + stored == total);
       // nobody else touches the counter again in this call: leave it at zero for the next one
       if (last) ctl_store(&st.arrived[b], 0u);
       sh.flag = last ? 1u : 0u;
@@ -882,10 +921,22 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
     __syncthreads();
     if (!sh.flag) return;
   }
+  // k_finalize's order: thread t adds partials lo + t, lo + t + 256, ... one after the other.  The loads are issued
+  // eight at a time before the first addition (this workgroup is the one everybody else is waiting for, and an
+  // agent-scope load that misses every cache takes a microsecond or two); a slot past the end adds +0.0, which
+  // leaves a sum of squares as it is.
   const uint64_t lo = (uint64_t)st.norm_bucket_off[b] * kWaves, hi = (uint64_t)st.norm_bucket_off[b + 1] * kWaves;
   double s = 0.0;
-  for (uint64_t i = lo + tid; i < hi; i += kBlock)
-    s += __hip_atomic_load(&st.partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (uint64_t i = lo + tid; i < hi; i += 8u * kBlock) {
+    double part[8];
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) {
+      const uint64_t j = i + (uint64_t)q * kBlock;
+      part[q] = j < hi ? __hip_atomic_load(&st.partials[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) s += part[q];
+  }
   s = wave_sum(s);
   if ((tid & 63u) == 0) sh.w[tid >> 6] = s;
   __syncthreads();
@@ -903,8 +954,34 @@ __device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, ui
   }
 }
 
+__device__ __forceinline__ void store_partial(const StepState& st, uint32_t chunk, double ws) {
+  if ((threadIdx.x & 63u) == 0)
+    __hip_atomic_store(&st.partials[(uint64_t)chunk * kWaves + (threadIdx.x >> 6)], ws, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A squared-norm item of k_step: `count` consecutive chunks of the norm table (all of one bucket), first
+// chunk idx; or (kItemEmpty) the stand-in for bucket idx, which has no elements.  A chunk's partials are the
+// same whichever item it was part of.
+template <int GDT>
+__device__ __forceinline__ void norm_item(const StepState& st, uint32_t kind, uint32_t idx, uint32_t count,
+                                          uint32_t epoch, const float* __restrict__ thresholds,
+                                          float* __restrict__ norms, float* __restrict__ coefs, StepShared& sh) {
+  if (kind != kItemNorm) {
+    norm_arrive(st, idx, 0u, epoch, thresholds, norms, coefs, sh);
+    return;
+  }
+  uint32_t b = 0;
+  for (uint32_t c = idx; c < idx + count; ++c) {
+    const Entry en = read_entry(&st.norm_tab[c]);
+    b = en.bucket;
+    store_partial(st, c, sqnorm_chunk<GDT, false>(en));
+  }
+  norm_arrive(st, b, count, epoch, thresholds, norms, coefs, sh);
+}
+
 // What the items that wait for a coefficient do with it.
-constexpr int kModeAdam = 0, kModeLamb = 1, kModeScale = 2;
+constexpr int kModeAdam = 0, kModeLamb = 1;
 
 template <int GDT, bool WB, uint32_t U, int MODE>
 __device__ __forceinline__ void apply_item(const StepState& st, const Entry& en, uint32_t idx, float coef,
@@ -913,9 +990,7 @@ __device__ __forceinline__ void apply_item(const StepState& st, const Entry& en,
     // LAMB's first sweep in place of Adam: moments and the chunk's two sums, filed under the chunk's place in
     // the tensor-major order; the trust ratio and the parameter update follow as launches of their own.
     lamb_moments_chunk<GDT, true, WB, false>(en, coef, k, sh.pp, sh.uu, st.lamb_sums + (uint64_t)st.apply_to_lamb[idx] * 2u);
-  else if constexpr (MODE == kModeScale) {
-    if (coef != 1.f) scale_chunk<GDT, U, false>(en, coef);
-  } else
+  else
     adam_chunk<GDT, true, WB, U, false>(en, coef, k);
 }
 
@@ -952,56 +1027,130 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
   if (ticket >= n_work) return;
   const uint32_t epoch = st.ctl[kCtlEpoch];  // left by the previous call's finish kernel, constant during this launch
   const uint32_t item = work[ticket];
-  const uint32_t kind = item >> 30, idx = item & 0x3fffffffu;
+  const uint32_t kind = item >> 30;
   if (kind == kItemAdam) {
+    const uint32_t idx = item & 0x3fffffffu;
     const Entry en = read_entry(&st.apply_tab[idx]);
     if (wait_for_bucket(st, en.bucket, epoch, idx, sh))
       apply_item<GDT, WB, U, LAMB ? kModeLamb : kModeAdam>(st, en, idx, sh.coef, k, sh);
   } else {
-    norm_item<GDT>(st, kind, idx, epoch, thresholds, norms, coefs, sh);
+    // squared-norm items carry their chunk count (1 .. 4) in bits 28..29
+    norm_item<GDT>(st, kind, item & 0x0fffffffu, ((item >> 28) & 3u) + 1u, epoch, thresholds, norms, coefs, sh);
   }
 }
 
-// Clipping of a bucket range in one launch (the paper's per-bucket use: a bucket
-// is clipped the moment backward has produced it).  Workgroups 0 .. n_norm-1 take
-// the range's squared-norm chunks, the following n_apply ones its scale chunks,
-// which wait for their bucket's coefficient exactly as the Adam items of k_step
-// do; buckets that are not clipped are not touched.  Norms, coefficients and
-// scaled gradients are those of k_sqnorm + k_finalize + k_coefs + k_scale bit
-// for bit.  Buckets without elements are dealt with by the finish kernel.
-template <int GDT, uint32_t U>
-__global__ __launch_bounds__(kBlock) void k_clip(StepState st, uint32_t cn0, uint32_t n_norm, uint32_t ca0,
-                                                  uint32_t n_apply, const float* __restrict__ thresholds,
-                                                  float* __restrict__ norms, float* __restrict__ coefs) {
-  __shared__ StepShared sh;
-  const uint32_t w = blockIdx.x;
-  const uint32_t epoch = st.ctl[kCtlEpoch];
-  if (w < n_norm) {
-    norm_item<GDT>(st, kItemNorm, cn0 + w, epoch, thresholds, norms, coefs, sh);
-  } else if (w - n_norm < n_apply) {
-    const uint32_t idx = ca0 + (w - n_norm);
-    const Entry en = read_entry(&st.apply_tab[idx]);
-    if (wait_for_bucket(st, en.bucket, epoch, idx, sh)) apply_item<GDT, false, U, kModeScale>(st, en, idx, sh.coef, AdamK{}, sh);
+// The sum of partials[lo .. hi) in k_finalize's order (thread t adds lo + t, lo + t + 256, ... one after the
+// other, lanes by butterfly, wavefronts in index order), computed by the whole workgroup; loads are issued eight
+// at a time before the first addition, a slot past the end adding +0.0.  Valid in thread 0.
+__device__ __forceinline__ double sum_partials(const double* __restrict__ partials, uint64_t lo, uint64_t hi, double* s_w) {
+  const uint32_t tid = threadIdx.x;
+  double s = 0.0;
+  for (uint64_t i = lo + tid; i < hi; i += 8u * kBlock) {
+    double part[8];
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) {
+      const uint64_t j = i + (uint64_t)q * kBlock;
+      part[q] = j < hi ? partials[j] : 0.0;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) s += part[q];
+  }
+  s = wave_sum(s);
+  if ((tid & 63u) == 0) s_w[tid >> 6] = s;
+  __syncthreads();
+  return ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+}
+
+// g <- coef * g over one chunk of the squared-norm cut.  A full, 16-byte aligned chunk of kDefaultChunkNorm
+// elements is fetched whole (every load in flight before the first store); anything else goes through scale_chunk.
+// Element by element the stored value is the same either way.
+template <int GDT>
+__device__ __forceinline__ void scale_norm_chunk(const Entry& en, float coef) {
+  typedef Grad<GDT> G;
+  typedef typename G::wide wide;
+  constexpr uint32_t R = kDefaultChunkNorm / (G::VE * kBlock);  // 128-bit pieces per lane: 16 (fp32) or 8 (16-bit types)
+  if (en.len == kDefaultChunkNorm && (en.g & 15u) == 0) {
+    wide* gw = reinterpret_cast<wide*>(en.g);
+    const uint32_t tid = threadIdx.x;
+    wide x[R];
+#pragma unroll
+    for (uint32_t u = 0; u < R; ++u) x[u] = ldv<false>(gw + tid + u * kBlock);
+    loads_issued();
+#pragma unroll
+    for (uint32_t u = 0; u < R; ++u) {
+      float f[G::VE];
+      G::widen(x[u], f);
+#pragma unroll
+      for (uint32_t q = 0; q < G::VE; ++q) f[q] = f[q] * coef;
+      stv<false>(gw + tid + u * kBlock, G::narrow(f));
+    }
+  } else {
+    scale_chunk<GDT, 4, false>(en, coef);
   }
 }
 
-// Follows every k_step / k_clip launch on the stream.  (1) Carries out the items whose
-// wait expired (none, as a rule), with the coefficient their bucket's ready word holds
-// by now.  (2) k_clip only (b0 < b1): norm 0 and the coefficient of buckets without
-// elements.  (3) The last of its workgroups to finish hands the status bits collected
-// during the call to the caller and resets the per-call state, epoch included.
+// The second of bucket_clip's two launches (the first is k_sqnorm over the range's chunks): one workgroup per
+// squared-norm chunk.  Every workgroup adds up its bucket's partial sums itself, in k_finalize's order, so all of
+// them arrive at the same norm and coefficient without exchanging anything (the partials of a 50 MiB bucket
+// are 25 KB, read from L2 by every workgroup), and then scales its chunk; the workgroup of a bucket's first
+// chunk also writes the bucket's norm and coefficient and ORs its status bits.  No workgroup waits for another.
+// Workgroup 0 deals with the range's buckets that have no elements.
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void k_clip_scale(const Chunk* __restrict__ norm_tab, uint32_t cn0, uint32_t n,
+                                                        const uint32_t* __restrict__ bucket_chunk_off, uint32_t b0,
+                                                        uint32_t b1, const double* __restrict__ partials,
+                                                        const float* __restrict__ thresholds, float* __restrict__ norms,
+                                                        float* __restrict__ coefs, int32_t* status) {
+  __shared__ double s_w[kWaves];
+  __shared__ float s_coef;
+  const uint32_t tid = threadIdx.x;
+  if (blockIdx.x == 0) {
+    int32_t bst = 0;
+    for (uint32_t b = b0 + tid; b < b1; b += kBlock) {
+      if (bucket_chunk_off[b] == bucket_chunk_off[b + 1]) {
+        norms[b] = 0.f;
+        coefs[b] = clip_coef(0.f, thresholds[b], bst);
+      }
+    }
+    if (bst != 0 && status != nullptr) atomicOr(status, bst);
+  }
+  if (blockIdx.x >= n) return;
+  const uint32_t idx = cn0 + blockIdx.x;
+  const Entry en = read_entry(&norm_tab[idx]);
+  const uint32_t b = en.bucket;
+  const double tot = sum_partials(partials, (uint64_t)bucket_chunk_off[b] * kWaves, (uint64_t)bucket_chunk_off[b + 1] * kWaves, s_w);
+  if (tid == 0) {
+    const float norm = (float)sqrt(tot);
+    int32_t bst = 0;
+    const float coef = clip_coef(norm, thresholds[b], bst);
+    s_coef = coef;
+    if (idx == bucket_chunk_off[b]) {
+      norms[b] = norm;
+      coefs[b] = coef;
+      if (bst != 0 && status != nullptr) atomicOr(status, bst);
+    }
+  }
+  __syncthreads();
+  const float coef = s_coef;
+  if (coef != 1.f) scale_norm_chunk<GDT>(en, coef);
+}
+
+// Follows every k_step launch on the stream; ONE workgroup, so that it costs a launch and one round trip to
+// memory when there is nothing to do.  (1) Carries out the items whose wait expired (none, as a rule; one after
+// the other if there are any -- an expired wait has cost about a second already), with the coefficient their
+// bucket's ready word holds by now.  (2) Hands the status bits collected during the call to the caller and
+// resets the per-call state, epoch included.
 template <int GDT, bool WB, uint32_t U, int MODE>
-__global__ __launch_bounds__(kBlock) void k_finish(StepState st, uint32_t b0, uint32_t b1,
-                                                    const float* __restrict__ thresholds, float* __restrict__ norms,
-                                                    float* __restrict__ coefs, int32_t* status, const AdamK ka) {
+__global__ __launch_bounds__(kBlock) void k_finish(StepState st, int32_t* status, const AdamK ka) {
   __shared__ StepShared sh;
   const uint32_t tid = threadIdx.x;
   const uint32_t epoch = ctl_load(&st.ctl[kCtlEpoch]);
   const uint32_t n_skipped = min(ctl_load(&st.ctl[kCtlSkipped]), st.skipped_cap);
+  const uint32_t collected = ctl_load(&st.ctl[kCtlStatus]);  // complete: the launch that ORed into it has ended
   uint32_t bits = 0;
   if (n_skipped != 0) {
     const AdamK k = resolve(ka);
-    for (uint32_t i = blockIdx.x; i < n_skipped; i += gridDim.x) {
+    for (uint32_t i = 0; i < n_skipped; ++i) {
       const uint32_t idx = st.skipped[i];
       const Entry en = read_entry(&st.apply_tab[idx]);
       const unsigned long long r = __hip_atomic_load(&st.ready[en.bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1013,31 +1162,13 @@ __global__ __launch_bounds__(kBlock) void k_finish(StepState st, uint32_t b0, ui
       __syncthreads();  // LAMB: sh.pp / sh.uu are reused by the next item
     }
   }
-  if (blockIdx.x == 0) {
-    int32_t bst = 0;
-    for (uint32_t b = b0 + tid; b < b1; b += kBlock) {
-      if (st.norm_bucket_off[b] == st.norm_bucket_off[b + 1]) {
-        norms[b] = 0.f;
-        coefs[b] = clip_coef(0.f, thresholds[b], bst);
-      }
-    }
-    bits |= (uint32_t)bst;
-  }
-  if (bits) ctl_or(&st.ctl[kCtlStatus], bits);
-  wait_vmem();      // this wavefront's status bits have landed ...
-  __syncthreads();  // ... and every wavefront's, before the workgroup is counted
   if (tid == 0) {
-    const uint32_t old = atomicAdd(&st.ctl[kCtlFinish], 1u);
-    if (old + 1u == gridDim.x) {  // the last workgroup: nobody reads the per-call state after this
-      const uint32_t all = ctl_load(&st.ctl[kCtlStatus]);
-      if (status != nullptr) *status = (int32_t)all;
-      ctl_store(&st.ctl[kCtlStatus], 0u);
-      ctl_store(&st.ctl[kCtlSkipped], 0u);
-      ctl_store(&st.ctl[kCtlAbort], 0u);
-      ctl_store(&st.ctl[kCtlFinish], 0u);
-      for (uint32_t y = 0; y < 8u; ++y) ctl_store(&st.ctl[kCtlTicket + 32u * y], 0u);
-      ctl_store(&st.ctl[kCtlEpoch], epoch + 1u == 0u ? 1u : epoch + 1u);
-    }
+    if (status != nullptr) *status = (int32_t)(collected | bits);
+    ctl_store(&st.ctl[kCtlStatus], 0u);
+    ctl_store(&st.ctl[kCtlSkipped], 0u);
+    ctl_store(&st.ctl[kCtlAbort], 0u);
+    for (uint32_t y = 0; y < 8u; ++y) ctl_store(&st.ctl[kCtlTicket + 32u * y], 0u);
+    ctl_store(&st.ctl[kCtlEpoch], epoch + 1u == 0u ? 1u : epoch + 1u);
   }
 }
 
@@ -1046,12 +1177,11 @@ __global__ __launch_bounds__(kBlock) void k_finish(StepState st, uint32_t b0, ui
 // For callers that cannot allocate (HIP graph capture, tight loops): the bucket is a
 // pointer and a length, chunk bounds are computed from the chunk index instead of read
 // from a table, and the partial sums live in a fixed array of this library's device
-// image.  Three plain launches (squared norms, finalize, scale) with the device functions
+// image.  Two plain launches (squared norms; coefficient and scale) with the device functions
 // of the plan-based path, so norm, coefficient and scaled gradients are those of
 // bucket_clip on a one-tensor, one-bucket plan whose squared-norm chunk is kFlatChunkNorm.
 
-constexpr uint32_t kFlatHeaderBytes = 256;  // coefficient of the current call (one float), padding
-constexpr size_t kFlatScratchBytes = kFlatHeaderBytes + (size_t)(kFlatMaxElems / kFlatChunkNorm) * kWaves * sizeof(double);
+constexpr size_t kFlatScratchBytes = (size_t)(kFlatMaxElems / kFlatChunkNorm) * kWaves * sizeof(double);
 static __device__ __align__(256) unsigned char scratch[kFlatScratchBytes];
 
 __device__ __forceinline__ Entry flat_entry(uint64_t g, uint64_t n, uint32_t chunk_elems, uint32_t gsize, uint32_t i) {
@@ -1066,37 +1196,36 @@ __device__ __forceinline__ Entry flat_entry(uint64_t g, uint64_t n, uint32_t chu
 template <int GDT>
 __global__ __launch_bounds__(kBlock) void k_flat_sqnorm(uint64_t g, uint64_t n, double* __restrict__ partials) {
   const Entry en = flat_entry(g, n, kFlatChunkNorm, sizeof(typename Grad<GDT>::elem), blockIdx.x);
-  const double ws = sqnorm_chunk<GDT, false>(en);  // cacheable loads: the scale pass reads the bucket again at once
+  const double ws = sqnorm_chunk<GDT, false, 16>(en);  // cacheable loads: the scale pass reads the bucket again at once
   if ((threadIdx.x & 63u) == 0) partials[(uint64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = ws;
 }
 
-// One workgroup; the summation order of k_finalize.  Writes (not ORs) the status word.
-__global__ __launch_bounds__(kBlock) void k_flat_finalize(const double* __restrict__ partials, uint32_t n_chunks,
-                                                           const float* __restrict__ threshold, float* norm_out,
-                                                           float* coef_out, int32_t* status, float* coef_scratch) {
+// One workgroup per chunk of the squared-norm cut (one workgroup for an empty bucket): norm and coefficient
+// from the partial sums as in k_clip_scale, then the chunk scaled.  Workgroup 0 writes the outputs; the status word
+// is written, not ORed.
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void k_flat_scale(uint64_t g, uint64_t n, uint32_t n_chunks,
+                                                        const double* __restrict__ partials,
+                                                        const float* __restrict__ threshold, float* norm_out,
+                                                        float* coef_out, int32_t* status) {
   __shared__ double s_w[kWaves];
-  double s = 0.0;
-  for (uint64_t i = threadIdx.x; i < (uint64_t)n_chunks * kWaves; i += kBlock) s += partials[i];
-  s = wave_sum(s);
-  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = s;
-  __syncthreads();
+  __shared__ float s_coef;
+  const double tot = sum_partials(partials, 0, (uint64_t)n_chunks * kWaves, s_w);
   if (threadIdx.x == 0) {
-    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
     const float norm = (float)sqrt(tot);
     int32_t st = 0;
     const float coef = clip_coef(norm, *threshold, st);
-    *coef_scratch = coef;
-    if (norm_out != nullptr) *norm_out = norm;
-    if (coef_out != nullptr) *coef_out = coef;
-    if (status != nullptr) *status = st;
+    s_coef = coef;
+    if (blockIdx.x == 0) {
+      if (norm_out != nullptr) *norm_out = norm;
+      if (coef_out != nullptr) *coef_out = coef;
+      if (status != nullptr) *status = st;
+    }
   }
-}
-
-template <int GDT>
-__global__ __launch_bounds__(kBlock) void k_flat_scale(uint64_t g, uint64_t n, const float* __restrict__ coef_scratch) {
-  const float coef = *coef_scratch;
-  if (coef == 1.f) return;  // an unclipped bucket is not touched
-  scale_chunk<GDT, 1, false>(flat_entry(g, n, kDefaultChunkApply, sizeof(typename Grad<GDT>::elem), blockIdx.x), coef);
+  __syncthreads();
+  const float coef = s_coef;
+  if (coef == 1.f || blockIdx.x >= n_chunks) return;  // an unclipped bucket is not touched
+  scale_norm_chunk<GDT>(flat_entry(g, n, kFlatChunkNorm, sizeof(typename Grad<GDT>::elem), blockIdx.x), coef);
 }
 
 // Plain device-to-device copy (16-byte pieces, then single bytes).  It exists so
@@ -1146,8 +1275,13 @@ hipError_t launch_sqnorm(int gdt, const Chunk* table, uint32_t c0, uint32_t n, d
     constexpr bool NT = decltype(nt)::value, ST = decltype(st)::value;
     pick_gdt(gdt, [&](auto gd) {
       constexpr int GDT = decltype(gd)::value;
-      hipLaunchKernelGGL((k_sqnorm<GDT, NT, ST>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, partials,
-                         status);
+      // a launch that does not fill the GPU (one bucket) keeps a whole 16 Ki chunk in flight per workgroup
+      if (L.grid <= kSmallNormGrid)
+        hipLaunchKernelGGL((k_sqnorm<GDT, NT, ST, 16>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, partials,
+                           status);
+      else
+        hipLaunchKernelGGL((k_sqnorm<GDT, NT, ST, 8>), dim3(L.grid), dim3(kBlock), 0, stream, table, c0, n, partials,
+                           status);
     });
   });
   return hipGetLastError();
@@ -1161,25 +1295,12 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t 
   return hipGetLastError();
 }
 
-hipError_t launch_clip(int gdt, const StepState& st, uint32_t b0, uint32_t b1, uint32_t cn0, uint32_t n_norm,
-                       uint32_t ca0, uint32_t n_apply, const float* thresholds, float* norms, float* coefs,
-                       int32_t* status, uint32_t unroll, hipStream_t stream) {
-  if (n_norm + n_apply != 0) {
-    pick_unroll(unroll, [&](auto uu) {
-      constexpr uint32_t U = decltype(uu)::value;
-      pick_gdt(gdt, [&](auto gd) {
-        constexpr int GDT = decltype(gd)::value;
-        hipLaunchKernelGGL((k_clip<GDT, U>), dim3(n_norm + n_apply), dim3(kBlock), 0, stream, st, cn0, n_norm, ca0,
-                           n_apply, thresholds, norms, coefs);
-      });
-    });
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
+hipError_t launch_clip_scale(int gdt, const Chunk* norm_tab, uint32_t cn0, uint32_t n, const uint32_t* bucket_chunk_off,
+                             uint32_t b0, uint32_t b1, const double* partials, const float* thresholds, float* norms,
+                             float* coefs, int32_t* status, hipStream_t stream) {
   pick_gdt(gdt, [&](auto gd) {
-    constexpr int GDT = decltype(gd)::value;
-    hipLaunchKernelGGL((k_finish<GDT, false, 1, kModeScale>), dim3(kFinishGrid), dim3(kBlock), 0, stream, st, b0, b1,
-                       thresholds, norms, coefs, status, AdamK{});
+    hipLaunchKernelGGL((k_clip_scale<decltype(gd)::value>), dim3(std::max(n, 1u)), dim3(kBlock), 0, stream, norm_tab, cn0, n,
+                       bucket_chunk_off, b0, b1, partials, thresholds, norms, coefs, status);
   });
   return hipGetLastError();
 }
@@ -1220,8 +1341,8 @@ hipError_t launch_step(int gdt, const StepState& st, const uint32_t* work, uint3
     constexpr bool LM = decltype(lm)::value, WB = decltype(wb)::value;
     pick_gdt(gdt, [&](auto gd) {
       constexpr int GDT = decltype(gd)::value;
-      hipLaunchKernelGGL((k_finish<GDT, WB, 1, LM ? kModeLamb : kModeAdam>), dim3(kFinishGrid), dim3(kBlock), 0, stream,
-                         st, 0u, 0u, thresholds, norms, coefs, status, k);
+      hipLaunchKernelGGL((k_finish<GDT, WB, 1, LM ? kModeLamb : kModeAdam>), dim3(1), dim3(kBlock), 0, stream, st, status,
+                         k);
     });
   });
   return hipGetLastError();
@@ -1340,30 +1461,23 @@ hipError_t launch_clip_flat(int device, int gdt, void* g, uint64_t n, const floa
   if (g_flat_scratch_err[device] != hipSuccess) return g_flat_scratch_err[device];
   unsigned char* base = static_cast<unsigned char*>(g_flat_scratch[device]);
   if (base == nullptr) return hipErrorInvalidSymbol;
-  float* coef_scratch = reinterpret_cast<float*>(base);
-  double* partials = reinterpret_cast<double*>(base + kFlatHeaderBytes);
+  double* partials = reinterpret_cast<double*>(base);
   const uint32_t n_norm = (uint32_t)((n + kFlatChunkNorm - 1) / kFlatChunkNorm);
-  const uint32_t n_apply = (uint32_t)((n + kDefaultChunkApply - 1) / kDefaultChunkApply);
   const uint64_t ga = (uint64_t)(uintptr_t)g;
   hipError_t e = hipSuccess;
-  // Nothing in the scratch array has to start at zero: every partial that the finalize kernel reads and the
-  // coefficient that the scale kernel reads are written earlier in this same call.
+  // Nothing in the scratch array has to start at zero: every partial that the second kernel reads is written
+  // by the first kernel of this same call.
   if (n_norm != 0) {
     pick_gdt(gdt, [&](auto gd) {
       hipLaunchKernelGGL((k_flat_sqnorm<decltype(gd)::value>), dim3(n_norm), dim3(kBlock), 0, stream, ga, n, partials);
     });
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k_flat_finalize, dim3(1), dim3(kBlock), 0, stream, partials, n_norm, threshold, norm, coef, status,
-                     coef_scratch);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (n_apply != 0) {
-    pick_gdt(gdt, [&](auto gd) {
-      hipLaunchKernelGGL((k_flat_scale<decltype(gd)::value>), dim3(n_apply), dim3(kBlock), 0, stream, ga, n, coef_scratch);
-    });
-    e = hipGetLastError();
-  }
-  return e;
+  pick_gdt(gdt, [&](auto gd) {
+    hipLaunchKernelGGL((k_flat_scale<decltype(gd)::value>), dim3(std::max(n_norm, 1u)), dim3(kBlock), 0, stream, ga, n, n_norm,
+                       partials, threshold, norm, coef, status);
+  });
+  return hipGetLastError();
 }
 
 hipError_t launch_lamb_update(const Chunk* table, uint32_t n, const float* scale, const AdamK& k, hipStream_t stream) {

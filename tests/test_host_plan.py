@@ -31,7 +31,7 @@ def test_binding_constants_equal_the_headers():
         errs = {int(v): k for k, v in defines.items() if "_ERR_" in k}
         assert errs == table, (header, errs, table)
     # struct layouts the C side and ctypes must agree on (C99 layout rules: natural alignment)
-    assert C.sizeof(binding._Segment) == 24 and C.sizeof(binding._Tuning) == 40 and C.sizeof(lbs._Run) == 72
+    assert C.sizeof(binding._Segment) == 24 and C.sizeof(binding._Tuning) == 48 and C.sizeof(lbs._Run) == 72
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -93,17 +93,25 @@ def test_chunk_table_partitions_the_layout(chunk, table):
 
 def test_chunk_counts_and_groups_of_the_bert_large_configs():
     N = 335_141_888
-    # default cuts: 1 024 elements for the read-write passes; for the norm pass the largest power of two in
-    # [16 Ki, 64 Ki] that leaves an average bucket group at least 160 chunks: 64 Ki for 50 MiB buckets (one per
-    # group), 32 Ki for 1 MiB buckets (32 per group of 8 Mi elements)
-    for make, cn in ((W.config_bert_large, 65536), (W.config_bert_large_fp16, 32768)):
+    # default cuts: 1 024 elements for the read-write passes, 16 Ki for the squared-norm pass (one set of partial
+    # sums per chunk).  A squared-norm work item of the fused step reads the largest power of two in [16 Ki, 64 Ki]
+    # elements that leaves an average bucket group at least 160 items: 4 chunks for 50 MiB buckets (one per group),
+    # 2 for 1 MiB buckets (32 per group of 8 Mi elements), 2 for BERT-Base's 25 MiB ones
+    for make, per_item in ((W.config_bert_large, 4), (W.config_bert_large_fp16, 2)):
         w = make()
         p = host_plan(w.layout)
-        assert -(-N // cn) <= p.n_chunks(B.BCA_TABLE_NORM) <= -(-N // cn) + 2 * w.layout.n_segments
-        assert max(p.chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(0, p.n_chunks(B.BCA_TABLE_NORM), 7)) == cn
+        assert -(-N // 16384) <= p.n_chunks(B.BCA_TABLE_NORM) <= -(-N // 16384) + 2 * w.layout.n_segments
+        assert max(p.chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(0, p.n_chunks(B.BCA_TABLE_NORM), 7)) == 16384
+        assert p.norm_item_chunks == per_item
         assert -(-N // 1024) <= p.n_chunks(B.BCA_TABLE_APPLY) <= -(-N // 1024) + 2 * w.layout.n_segments
-    assert max(host_plan(W.config_bert_base().layout).chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(100)) == 32768
+    assert host_plan(W.config_bert_base().layout).norm_item_chunks == 2
+    assert max(host_plan(W.config_bert_base().layout).chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(100)) == 16384
     assert max(host_plan(W.config_tiny().layout).chunk_info(i, B.BCA_TABLE_NORM)[2] for i in range(3)) == 12345
+    assert host_plan(W.config_tiny().layout).norm_item_chunks == 1
+    assert host_plan(W.config_bert_base().layout, chunk_norm=32768).norm_item_chunks == 1       # a named chunk: one per item
+    assert host_plan(W.config_bert_base().layout, chunk_norm=8192, norm_item_chunks=3).norm_item_chunks == 3
+    with pytest.raises(B.BcaError):
+        host_plan(W.config_tiny().layout, norm_item_chunks=5)
     assert host_plan(W.config_bert_base().layout, chunk_norm=4096).n_chunks(B.BCA_TABLE_NORM) > 109_482_240 // 4096
     w = W.config_bert_large()
     assert host_plan(w.layout).n_groups == 26                          # default 8 Mi elements: one 50 MiB bucket per group
