@@ -59,6 +59,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-norm", type=int, default=0)
     ap.add_argument("--norm-item-chunks", type=int, default=0, help="fused step: squared-norm chunks per work item (0: automatic)")
+    ap.add_argument("--norm-lead", type=int, default=0, help="fused step: bucket groups the squared-norm items run ahead (0: default)")
     ap.add_argument("--chunk-apply", type=int, default=0)
     ap.add_argument("--unroll-apply", type=int, default=0)
     ap.add_argument("--group-mib", type=int, default=0)
@@ -347,7 +348,7 @@ def main():
                               chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
                               unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20,
                               adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10,
-                              norm_item_chunks=a.norm_item_chunks)
+                              norm_item_chunks=a.norm_item_chunks, norm_lead=a.norm_lead)
     plan.bind(g, p, m, v)
     if a.decay_mask:
         H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)
@@ -396,6 +397,7 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
     (ms_norm, ms_fin, ms_adam), n_prof = plan.profile_read()
     plan.profile(0)
+    n_waited, n_polls = plan.wait_stats()        # over warm-up and timed steps
     assert n_prof == a.steps
     ms_norm, ms_fin, ms_adam = ms_norm / n_prof, ms_fin / n_prof, ms_adam / n_prof
     st = int(status.item())
@@ -454,6 +456,8 @@ def main():
         "step_GBps_hbm_bytes": round(hbm_per_elt * N / (ms_per_step * 1e-3) / 1e9, 1),
         "step_frac_of_peak_hbm_bytes": round(hbm_per_elt * N / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "plain_copy_frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
+        "items_that_waited_per_step": round(n_waited / (a.warmup + a.steps), 1),
+        "polls_per_waiting_item": round(n_polls / max(n_waited, 1), 1),
         "elements": N, "buckets": lay.n_buckets, "chunks_norm": plan.n_chunks(B.BCA_TABLE_NORM),
         "chunks_apply": plan.n_chunks(B.BCA_TABLE_APPLY), "groups": plan.n_groups, "buckets_clipped": n_clipped,
         "status": st,

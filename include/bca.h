@@ -132,6 +132,8 @@ typedef struct bca_tuning {
   uint32_t norm_item_chunks; /* fused calls: consecutive squared-norm chunks one work item reads, 1 .. 4;
                             0: chosen from the bucket sizes so that an item reads 16 Ki .. 64 Ki elements
                             (1 when chunk_norm is given)                                               */
+  uint32_t norm_lead;    /* fused calls: bucket groups by which the squared-norm items run ahead of the Adam
+                            items in the work list (their gradients must stay cached that long); 0: default */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */
@@ -295,6 +297,12 @@ int bucket_clip_lamb(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, con
  * launch (the default) reports its step kernel in ms[2] and its finish kernel in ms[0]. */
 int bca_plan_profile(bca_plan* plan, uint32_t max_calls);
 int bca_plan_profile_read(bca_plan* plan, double* ms /*HOST [3]*/, uint32_t* n_calls /*HOST*/);
+
+/* Waiting inside the pipelined launches since the plan was created or this was last called: out[0] = work items
+ * that found their bucket's coefficient not yet published at their first look, out[1] = polls they made in all
+ * (a poll takes about a third of a microsecond; 2^18 of them is the default bound).  Synchronises the device,
+ * then clears the two counters.  Measurement only. */
+int bca_plan_wait_stats(bca_plan* plan, uint64_t* out /*HOST [2]*/);
 
 /* Plain copy of nbytes from src to dst (both DEVICE, 16-byte aligned, not
  * overlapping) on the current device.  Not part of the method: a kernel with

@@ -27,7 +27,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
 EXPORTS = ["bca_alg1_thresholds", "bucket_clip_flat", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
            "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
-           "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_copy_bytes", "bca_last_error",
+           "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_plan_wait_stats", "bca_copy_bytes", "bca_last_error",
            "bca_version"]
 
 
@@ -50,7 +50,7 @@ class _Tuning(C.Structure):
     _fields_ = [("chunk_norm", C.c_uint32), ("chunk_apply", C.c_uint32), ("grid_norm", C.c_uint32),
                 ("grid_apply", C.c_uint32), ("unroll_apply", C.c_uint32), ("flags", C.c_uint32),
                 ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("spin_limit", C.c_uint32),
-                ("norm_item_chunks", C.c_uint32)]
+                ("norm_item_chunks", C.c_uint32), ("norm_lead", C.c_uint32)]
 
 
 @dataclass
@@ -128,6 +128,7 @@ def load_library():
     L.bca_plan_profile.argtypes = [vp, u32]
     L.bca_plan_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]
     L.bca_copy_bytes.argtypes = [vp, vp, u64, vp]
+    L.bca_plan_wait_stats.argtypes = [vp, C.POINTER(u64)]
     L.bca_alg1_thresholds.argtypes = [C.c_double, u32, C.POINTER(C.c_float)]
     L.bucket_clip_flat.argtypes = [vp, u64, i32, vp, vp, vp, vp, vp]
     L.bca_last_error.restype = C.c_char_p
@@ -184,7 +185,7 @@ class Plan:
                  seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
                  chunk_norm: int = 0, chunk_apply: int = 0, grid_norm: int = 0, grid_apply: int = 0,
                  unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0, adam_lds_reserve: int = 0,
-                 spin_limit: int = 0, norm_item_chunks: int = 0):
+                 spin_limit: int = 0, norm_item_chunks: int = 0, norm_lead: int = 0):
         L = load_library()
         self._L = L
         self._h = C.c_void_p()
@@ -195,7 +196,7 @@ class Plan:
         for i in range(n_seg):
             segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
         tune = _Tuning(chunk_norm, chunk_apply, grid_norm, grid_apply, unroll_apply, tune_flags, group_bytes,
-                       adam_lds_reserve, spin_limit, norm_item_chunks)
+                       adam_lds_reserve, spin_limit, norm_item_chunks, norm_lead)
         _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
                                  len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
                                  C.byref(tune)))
@@ -294,6 +295,12 @@ class Plan:
         n = C.c_uint32()
         _check(self._L.bca_plan_profile_read(self._h, ms, C.byref(n)))
         return (ms[0], ms[1], ms[2]), int(n.value)
+
+    def wait_stats(self):
+        """(items that had to wait for their bucket's coefficient, polls they made) since the last call; synchronises."""
+        out = (C.c_uint64 * 2)()
+        _check(self._L.bca_plan_wait_stats(self._h, out))
+        return int(out[0]), int(out[1])
 
     # -- compute (same names as the C ABI)
     def bucket_clip_norms(self, b0: int, b1: int, norms, stream=None) -> None:

@@ -203,8 +203,11 @@ void build_work(bca_plan* p) {
   p->work.clear();
   const Table& TN = p->norm_tab;
   const Table& TA = p->apply_tab;
-  const uint32_t span = std::min(std::max(p->norm_item_chunks, 1u), kMaxNormItemChunks);
+  const uint32_t span_all = std::min(std::max(p->norm_item_chunks, 1u), kMaxNormItemChunks);
   auto push_norm = [&](const std::pair<uint32_t, uint32_t>& g) {
+    // The launch starts with nothing to do but the first group's squared norms while the first Adam items wait:
+    // that group is handed out chunk by chunk, so that more workgroups share it and it is done sooner.
+    const uint32_t span = g.first == 0 ? 1u : span_all;
     for (uint32_t b = g.first; b < g.second; ++b) {
       if (TN.bucket_off[b] == TN.bucket_off[b + 1]) p->work.push_back((kItemEmpty << 30) | b);
       // an item is up to `span` consecutive chunks of one bucket: first chunk in bits 0..27, count - 1 in bits 28..29
@@ -217,11 +220,11 @@ void build_work(bca_plan* p) {
   auto push_adam = [&](const std::pair<uint32_t, uint32_t>& g) {
     for (uint32_t c = TA.bucket_off[g.first]; c < TA.bucket_off[g.second]; ++c) p->work.push_back((kItemAdam << 30) | c);
   };
-  for (size_t i = 0; i < p->groups.size(); ++i) {
-    push_norm(p->groups[i]);
-    if (i > 0) push_adam(p->groups[i - 1]);
+  const size_t G = p->groups.size(), lead = std::max(p->norm_lead, 1u);
+  for (size_t i = 0; i < G + lead; ++i) {
+    if (i < G) push_norm(p->groups[i]);
+    if (i >= lead && i - lead < G) push_adam(p->groups[i - lead]);
   }
-  if (!p->groups.empty()) push_adam(p->groups.back());
 }
 
 void free_profile(bca_plan* p) {
@@ -440,6 +443,7 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
       return fail(BCA_ERR_RANGE, "unknown tuning flag bits");
     if (tuning->adam_lds_reserve > 65536) return fail(BCA_ERR_RANGE, "adam_lds_reserve must be at most 65536");
     if (tuning->norm_item_chunks > kMaxNormItemChunks) return fail(BCA_ERR_RANGE, "norm_item_chunks must be at most 4");
+    if (tuning->norm_lead > 64) return fail(BCA_ERR_RANGE, "norm_lead must be at most 64");
   }
   if (int rc = validate_layout(n_tensors, tensor_numel, n_buckets, bucket_seg_off, segments)) return rc;
 
@@ -466,6 +470,11 @@ static int plan_create(bca_plan** out, int device, uint32_t n_tensors, const uin
   p->tensor_numel.assign(tensor_numel, tensor_numel + n_tensors);
   p->decay.assign(n_tensors, 1);
   build_groups(p, tuning ? tuning->group_bytes : 0, bucket_seg_off, segments);
+  // Squared norms run one bucket group ahead of the Adam items; two when groups hold several buckets (measured: with
+  // 4 MiB buckets 13 K instead of 2 K Adam items per step find their bucket not ready at one group's lead, and the
+  // step takes 2.4 % longer), which leaves three groups' gradients to be kept cached: fine for 8 Mi-element groups,
+  // too much for groups that are one 50 MiB bucket.
+  p->norm_lead = (tuning && tuning->norm_lead) ? tuning->norm_lead : (p->n_buckets >= 2 * p->groups.size() ? 2 : 1);
   if (tuning && tuning->norm_item_chunks) {
     p->norm_item_chunks = tuning->norm_item_chunks;
   } else if (chunk_norm == 0) {
@@ -713,6 +722,25 @@ int bca_plan_profile_read(bca_plan* p, double* ms, uint32_t* n_calls) {
   *n_calls = p->prof_calls;
   p->prof_calls = 0;
   return BCA_OK;
+}
+
+int bca_plan_wait_stats(bca_plan* p, uint64_t* out) {
+  if (!p || !out) return fail(BCA_ERR_NULL, "NULL argument");
+  out[0] = out[1] = 0;
+  if (p->device < 0) return fail(BCA_ERR_UNBOUND, "host-only plan");
+  DeviceGuard g(p->device);
+  hipError_t e = hipDeviceSynchronize();
+  return no_throw([&] {
+    std::vector<uint32_t> words(32 * kStatSlots);
+    if (e == hipSuccess) e = hipMemcpy(words.data(), p->d_ctl + kCtlStats, words.size() * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemset(p->d_ctl + kCtlStats, 0, words.size() * sizeof(uint32_t));
+    if (e != hipSuccess) return fail_hip(e, "reading the wait statistics");
+    for (uint32_t sl = 0; sl < kStatSlots; ++sl) {
+      out[0] += words[32 * sl];
+      out[1] += (uint64_t)words[32 * sl + 2] | ((uint64_t)words[32 * sl + 3] << 32);
+    }
+    return (int)BCA_OK;
+  });
 }
 
 int bca_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream) {

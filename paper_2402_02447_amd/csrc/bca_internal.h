@@ -106,7 +106,12 @@ enum : uint32_t {
   kCtlAbort = 288,
   kCtlSkipped = 320,
   kCtlStatus = 352,
-  kCtlWords = 384
+  // statistics: kStatSlots lines of 32 words, slot = workgroup index mod kStatSlots; word 0: items of that slot that
+  // found their bucket not ready at their first look, words 2..3 (64 bits): the polls they made in all.  Only
+  // items that waited touch them, and spread over many lines so that they do not queue up behind one address.
+  kCtlStats = 384,
+  kStatSlots = 256,
+  kCtlWords = kCtlStats + 32 * kStatSlots
 };
 // Work items of k_step: kind in bits 30..31; kItemAdam: apply-table chunk in bits 0..29; kItemNorm: first
 // norm-table chunk in bits 0..27 and the number of consecutive chunks minus one in bits 28..29; kItemEmpty: bucket.
@@ -194,6 +199,7 @@ struct bca_plan {
   uint32_t unroll_apply = 1;
   uint32_t adam_lds_reserve = 0;  // bytes; see bca_tuning::adam_lds_reserve
   uint32_t norm_item_chunks = 1;  // consecutive norm-table chunks per squared-norm item of the fused step
+  uint32_t norm_lead = 1;         // bucket groups by which the squared-norm items run ahead of the Adam items
   uint32_t spin_limit = 0;        // see bca_tuning::spin_limit (default already applied)
   const bca_adam_device* hyper_dev = nullptr;  // hyper-parameters in device memory, when set
   bca::AdamK* d_adamk = nullptr;  // the constants derived from them by k_hyper

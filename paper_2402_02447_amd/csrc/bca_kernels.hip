@@ -868,6 +868,11 @@ __device__ __forceinline__ bool wait_for_bucket(const StepState& st, uint32_t b,
     const bool ok = (uint32_t)(r >> 32) == epoch;
     sh.flag = ok ? 1u : 0u;
     sh.coef = __uint_as_float((uint32_t)r);
+    if (polls != 0u) {  // statistics (bca_plan_wait_stats); an item that never waited does not come here
+      uint32_t* slot = &st.ctl[kCtlStats + 32u * (blockIdx.x % kStatSlots)];
+      atomicAdd(slot, 1u);
+      atomicAdd(reinterpret_cast<unsigned long long*>(slot + 2), (unsigned long long)polls);
+    }
     if (!ok) {
       ctl_store(&st.ctl[kCtlAbort], 1u);
       ctl_or(&st.ctl[kCtlStatus], BCA_STATUS_TIMEOUT);
