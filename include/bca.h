@@ -228,14 +228,14 @@ int bucket_clip(bca_plan* plan, uint32_t b0, uint32_t b1, const float* threshold
  * grad_dtype at g (DEVICE) is clipped in place against *threshold (DEVICE, one float): norm and
  * factor as in bucket_clip_apply, written to *norm / *coef / *status (DEVICE, each may be NULL;
  * status is written, not ORed).  The call allocates nothing and calls no allocating routine: its
- * partial sums live in a fixed array of 512 KiB inside the library's device image (every GPU
+ * partial sums live in a fixed array of 512.25 KiB inside the library's device image (every GPU
  * the library runs on holds that array until the process ends), looked up once per device at the
  * first call made with that device current.  Limit: n <= 2^28 elements, else BCA_ERR_RANGE and
  * nothing is enqueued.  g must be on the device that is current at the call.  All calls on one
  * GPU share the array: calls that overlap in time on one GPU (different streams) race; calls in
  * stream order are fine, each call writes what it later reads and needs nothing cleared.
  * Results equal bucket_clip's on a one-tensor, one-bucket plan with chunk_norm = 16384, bit for
- * bit.  Only enqueues (two kernels). */
+ * bit.  Only enqueues (two kernels; three beyond 16 Mi elements). */
 int bucket_clip_flat(void* g /*DEVICE*/, uint64_t n, int grad_dtype, const float* threshold /*DEVICE*/,
                      float* norm /*DEVICE or NULL*/, float* coef /*DEVICE or NULL*/,
                      int32_t* status /*DEVICE or NULL*/, void* stream);

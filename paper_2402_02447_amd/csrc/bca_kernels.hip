@@ -1182,11 +1182,13 @@ __global__ __launch_bounds__(kBlock) void k_finish(StepState st, int32_t* status
 // For callers that cannot allocate (HIP graph capture, tight loops): the bucket is a
 // pointer and a length, chunk bounds are computed from the chunk index instead of read
 // from a table, and the partial sums live in a fixed array of this library's device
-// image.  Two plain launches (squared norms; coefficient and scale) with the device functions
+// image.  Two plain launches (squared norms; coefficient and scale; three for buckets of more than 16 Mi
+// elements, whose coefficient gets a launch of its own) with the device functions
 // of the plan-based path, so norm, coefficient and scaled gradients are those of
 // bucket_clip on a one-tensor, one-bucket plan whose squared-norm chunk is kFlatChunkNorm.
 
-constexpr size_t kFlatScratchBytes = (size_t)(kFlatMaxElems / kFlatChunkNorm) * kWaves * sizeof(double);
+constexpr uint32_t kFlatHeaderBytes = 256;  // one float: the coefficient of a large bucket, handed from its finalize launch to its scale launch
+constexpr size_t kFlatScratchBytes = kFlatHeaderBytes + (size_t)(kFlatMaxElems / kFlatChunkNorm) * kWaves * sizeof(double);
 static __device__ __align__(256) unsigned char scratch[kFlatScratchBytes];
 
 __device__ __forceinline__ Entry flat_entry(uint64_t g, uint64_t n, uint32_t chunk_elems, uint32_t gsize, uint32_t i) {
@@ -1205,30 +1207,52 @@ __global__ __launch_bounds__(kBlock) void k_flat_sqnorm(uint64_t g, uint64_t n, 
   if ((threadIdx.x & 63u) == 0) partials[(uint64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = ws;
 }
 
-// One workgroup per chunk of the squared-norm cut (one workgroup for an empty bucket): norm and coefficient
-// from the partial sums as in k_clip_scale, then the chunk scaled.  Workgroup 0 writes the outputs; the status word
-// is written, not ORed.
-template <int GDT>
-__global__ __launch_bounds__(kBlock) void k_flat_scale(uint64_t g, uint64_t n, uint32_t n_chunks,
-                                                        const double* __restrict__ partials,
-                                                        const float* __restrict__ threshold, float* norm_out,
-                                                        float* coef_out, int32_t* status) {
-  __shared__ double s_w[kWaves];
-  __shared__ float s_coef;
+// Norm, coefficient and status of the bucket from its partial sums (whole workgroup; thread 0 writes the outputs
+// if `write_outputs`).  Returns the coefficient to every thread.
+__device__ __forceinline__ float flat_coef(const double* __restrict__ partials, uint32_t n_chunks,
+                                           const float* __restrict__ threshold, float* norm_out, float* coef_out,
+                                           int32_t* status, bool write_outputs, double* s_w, float* s_coef) {
   const double tot = sum_partials(partials, 0, (uint64_t)n_chunks * kWaves, s_w);
   if (threadIdx.x == 0) {
     const float norm = (float)sqrt(tot);
     int32_t st = 0;
     const float coef = clip_coef(norm, *threshold, st);
-    s_coef = coef;
-    if (blockIdx.x == 0) {
+    *s_coef = coef;
+    if (write_outputs) {
       if (norm_out != nullptr) *norm_out = norm;
       if (coef_out != nullptr) *coef_out = coef;
-      if (status != nullptr) *status = st;
+      if (status != nullptr) *status = st;  // written, not ORed
     }
   }
   __syncthreads();
-  const float coef = s_coef;
+  return *s_coef;
+}
+
+// Large buckets only (their partials are too many for every workgroup of the scale launch to add up): one
+// workgroup derives the coefficient and leaves it in the scratch header.
+__global__ __launch_bounds__(kBlock) void k_flat_finalize(const double* __restrict__ partials, uint32_t n_chunks,
+                                                           const float* __restrict__ threshold, float* norm_out,
+                                                           float* coef_out, int32_t* status, float* coef_header) {
+  __shared__ double s_w[kWaves];
+  __shared__ float s_coef;
+  const float coef = flat_coef(partials, n_chunks, threshold, norm_out, coef_out, status, true, s_w, &s_coef);
+  if (threadIdx.x == 0) *coef_header = coef;
+}
+
+// One workgroup per chunk of the squared-norm cut (one workgroup for an empty bucket).  coef_header == nullptr:
+// every workgroup derives norm and coefficient from the partial sums itself, as in k_clip_scale, and workgroup 0
+// writes the outputs; else the coefficient is read from there.  Then the chunk is scaled.
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void k_flat_scale(uint64_t g, uint64_t n, uint32_t n_chunks,
+                                                        const double* __restrict__ partials,
+                                                        const float* __restrict__ threshold, float* norm_out,
+                                                        float* coef_out, int32_t* status,
+                                                        const float* __restrict__ coef_header) {
+  __shared__ double s_w[kWaves];
+  __shared__ float s_coef;
+  const float coef = coef_header != nullptr
+                         ? *coef_header
+                         : flat_coef(partials, n_chunks, threshold, norm_out, coef_out, status, blockIdx.x == 0, s_w, &s_coef);
   if (coef == 1.f || blockIdx.x >= n_chunks) return;  // an unclipped bucket is not touched
   scale_norm_chunk<GDT>(flat_entry(g, n, kFlatChunkNorm, sizeof(typename Grad<GDT>::elem), blockIdx.x), coef);
 }
@@ -1466,21 +1490,28 @@ hipError_t launch_clip_flat(int device, int gdt, void* g, uint64_t n, const floa
   if (g_flat_scratch_err[device] != hipSuccess) return g_flat_scratch_err[device];
   unsigned char* base = static_cast<unsigned char*>(g_flat_scratch[device]);
   if (base == nullptr) return hipErrorInvalidSymbol;
-  double* partials = reinterpret_cast<double*>(base);
+  float* coef_header = reinterpret_cast<float*>(base);
+  double* partials = reinterpret_cast<double*>(base + kFlatHeaderBytes);
   const uint32_t n_norm = (uint32_t)((n + kFlatChunkNorm - 1) / kFlatChunkNorm);
   const uint64_t ga = (uint64_t)(uintptr_t)g;
+  const bool large = n_norm > kMaxChunksForInlineFinalize;
   hipError_t e = hipSuccess;
-  // Nothing in the scratch array has to start at zero: every partial that the second kernel reads is written
-  // by the first kernel of this same call.
+  // Nothing in the scratch array has to start at zero: every partial (and the header) that a later kernel of the
+  // call reads is written by an earlier kernel of this same call.
   if (n_norm != 0) {
     pick_gdt(gdt, [&](auto gd) {
       hipLaunchKernelGGL((k_flat_sqnorm<decltype(gd)::value>), dim3(n_norm), dim3(kBlock), 0, stream, ga, n, partials);
     });
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  if (large) {
+    hipLaunchKernelGGL(k_flat_finalize, dim3(1), dim3(kBlock), 0, stream, partials, n_norm, threshold, norm, coef, status,
+                       coef_header);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   pick_gdt(gdt, [&](auto gd) {
     hipLaunchKernelGGL((k_flat_scale<decltype(gd)::value>), dim3(std::max(n_norm, 1u)), dim3(kBlock), 0, stream, ga, n, n_norm,
-                       partials, threshold, norm, coef, status);
+                       partials, threshold, norm, coef, status, large ? coef_header : nullptr);
   });
   return hipGetLastError();
 }

@@ -99,6 +99,18 @@ def test_two_calls_in_a_row_the_second_smaller_match_bucket_clip_bit_for_bit(gdt
             assert results[0][1] != results[1][1]
 
 
+def test_bucket_beyond_16_mi_elements_takes_the_separate_finalize_and_still_matches():
+    """More than 1 024 chunks: the coefficient is derived by a launch of its own (both entry points switch there),
+    followed by a smaller call that goes back to the usual two launches."""
+    gdt = B.BCA_GRAD_F32
+    for k, n in enumerate((17_000_001, 5_000_000)):
+        h = host_grads(n, 200 + k, gdt)
+        thr = torch.tensor([0.5 * host_norm(h)], dtype=torch.float32, device="cuda")
+        flat, ref = flat_clip(h, gdt, 0, thr), plan_clip(h, gdt, 0, thr)
+        assert same(flat, ref), (n, flat[1:], ref[1:])
+        assert flat[2] < 1.0 and abs(flat[1] - host_norm(h)) <= 1e-5 * host_norm(h)
+
+
 def test_back_to_back_on_a_stream_without_synchronising_in_between():
     """Two calls enqueued one behind the other (the second smaller) before anything is waited for."""
     gdt = B.BCA_GRAD_F32
