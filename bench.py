@@ -350,9 +350,11 @@ def main():
                               adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10,
                               norm_item_chunks=a.norm_item_chunks, norm_lead=a.norm_lead)
     plan.bind(g, p, m, v)
+    mask = None
     if a.decay_mask:
         H, L, F = (768, 12, 3072) if a.config == 2 else (1024, 24, 4096)
-        plan.set_decay_mask(W.bert_decay_mask(30522, H, L, F, 512))
+        mask = W.bert_decay_mask(30522, H, L, F, 512)
+        plan.set_decay_mask(mask)
     if a.calibrate_copy:     # a kernel with exactly known traffic, for counter runs
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
         dst = torch.empty_like(src)
@@ -372,10 +374,22 @@ def main():
     flags = 0        # gradients are read, never written: the timed steps keep clipping the same way
     stream = torch.cuda.current_stream()
 
-    # host copies for the CPU baseline are taken before the state evolves
+    # host copies for the CPU baseline are taken before the state evolves; and so that the benched configuration is
+    # itself held to the oracle, one fused step runs on copies of p, m, v (a second plan), to be compared below
     host = None
+    check = None
     if not a.no_cpu_baseline:
         host = [[t.cpu().numpy() for t in xs] for xs in (g, p, m, v)]
+        pc, mc, vc = ([x.clone() for x in xs] for xs in (p, m, v))
+        plan_c = B.Plan.from_layout(lay, gdt, device=0)
+        plan_c.bind(g, pc, mc, vc)
+        plan_c.set_decay_mask(mask)
+        norms_c, coefs_c, status_c = torch.zeros_like(norms), torch.zeros_like(norms), torch.zeros_like(status)
+        plan_c.bucket_clip_adam(thr, hp, w.first_step, flags, norms_c, coefs_c, status_c, stream)
+        torch.cuda.synchronize()
+        check = [[t.cpu().numpy() for t in xs] for xs in (pc, mc, vc)] + [norms_c.cpu().numpy(), int(status_c.item())]
+        plan_c.close()
+        del pc, mc, vc
 
     step = w.first_step
     def one_step():
@@ -469,14 +483,43 @@ def main():
         hg, hp_, hm, hv = host
         with ThreadPoolExecutor(max_workers=8) as ex:
             op, om, ov = (list(ex.map(lambda x: x.astype(np.float64), xs)) for xs in (hp_, hm, hv))
-        t1 = time.perf_counter()
+        cpu_s = 0.0
+        parity = None
         for k in range(a.oracle_steps):
-            oracle.bucket_clip_adam(lay, hg, op, om, ov, w.thresholds, w.hyper.lr, w.hyper.beta1, w.hyper.beta2,
-                                    w.hyper.eps, w.hyper.weight_decay, w.first_step + k)
-        cpu_ms = (time.perf_counter() - t1) * 1e3 / a.oracle_steps
+            t1 = time.perf_counter()
+            onorm, _, ost = oracle.bucket_clip_adam(lay, hg, op, om, ov, w.thresholds, w.hyper.lr, w.hyper.beta1, w.hyper.beta2,
+                                                    w.hyper.eps, w.hyper.weight_decay, w.first_step + k, decay=mask)
+            cpu_s += time.perf_counter() - t1
+            if k == 0:
+                # the GPU's first step on this very workload against the oracle's, every element, BASELINE's tolerances
+                # (relative 1e-5, or absolute 1e-7 where |oracle| < 1e-2; norms relative 1e-5)
+                cp, cm, cv, cn, cst = check
+                worst = {}
+                n_bad = 0
+                for name, got, want in (("p", cp, op), ("m", cm, om), ("v", cv, ov)):
+                    big = small = rel_all = 0.0
+                    for t in range(lay.n_tensors):
+                        if got[t].size:
+                            r = oracle.compare_f32(got[t], want[t])
+                            n_bad += r["n_bad"]
+                            big, small = max(big, r["max_rel_big"]), max(small, r["max_abs_small"])
+                            rel_all = max(rel_all, r["max_rel_all"])
+                    worst[name] = {"max_rel_where_oracle_ge_1e-2": float(f"{big:.3g}"),
+                                   "max_abs_where_oracle_lt_1e-2": float(f"{small:.3g}")}
+                    if name == "v":      # no cancellation in v: the relative error holds everywhere
+                        worst[name]["max_rel_everywhere"] = float(f"{rel_all:.3g}")
+                        assert rel_all <= 1e-5, rel_all
+                norm_rel = float(np.max(np.abs(cn.astype(np.float64) - onorm) / np.maximum(onorm, 1e-300)))
+                assert n_bad == 0 and norm_rel <= 1e-5 and cst == ost, (n_bad, norm_rel, cst, ost)
+                parity = {"checked": "first fused step of this workload, every element of p, m, v and every bucket norm, "
+                                     "against the oracle", "elements_out_of_tolerance": n_bad,
+                          "errors": worst,
+                          "max_rel_err_norms": float(f"{norm_rel:.3g}")}
+        cpu_ms = cpu_s * 1e3 / a.oracle_steps
         cpu = {"value": round(cpu_ms, 1), "unit": "ms/step", "cores": 1, "kind": "oracle",
                "sample": f"{a.oracle_steps} full fused steps of the same workload ({N} elements), single thread, "
                          f"host has {os.cpu_count()} logical cpus"}
+        extras["parity_vs_oracle"] = parity
 
     out = {
         "metric": ("fused bucket_clip_adam step time, BERT-Large fp32 (ms/step; HBM fraction in roofline)"
