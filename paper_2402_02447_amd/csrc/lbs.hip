@@ -66,6 +66,16 @@ constexpr uint32_t kMaxSpreadGpus = 8192;  // k_lbs_global keeps one LDS word pe
 // free up, balance better than few long ones (measured: 16 -> 6.4 ms, 32 -> 5.9, 64 -> 5.8, 128 -> 5.7 for the five
 // methods at once; beyond that a workgroup runs too few trials to pay for loading the tables)
 constexpr uint32_t kGridPerCu = 128;
+// ... and with few simulated GPUs a trial is so short that the tables' load has to be spread over more of them:
+// a workgroup runs about three trials at 1 024 GPUs and proportionally more below (12 at 256 GPUs and fewer),
+// but the grid never falls below four rounds of resident workgroups (32 per compute unit), so that the last
+// round is a small part of the whole.
+inline uint32_t trial_grid(uint64_t n_trials, uint32_t n_gpus, int n_cus) {
+  const uint64_t most = (uint64_t)n_cus * kGridPerCu, least = (uint64_t)n_cus * 32u;
+  const uint64_t scaled = n_trials * n_gpus / (3u * 1024u);
+  const uint64_t want = std::min(most, std::max(least, scaled));
+  return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(n_trials, want));
+}
 
 thread_local std::string g_error;
 int fail(int code, const std::string& msg) {
@@ -850,7 +860,7 @@ static int simulate_one(const lbs_dataset* ds, const lbs_run* run, uint32_t meth
   const size_t lds = sizeof(uint32_t) * (tables + (local ? kWaves * pool : method == LBS_GLOBAL ? ds->max_len + 1u + (spread ? run->n_gpus : 0u) : 0u));
   if (e == hipSuccess && run->n_trials > 0) {
     // trials cost the same, so a few workgroups per resident slot balance; each loops over its share of the trials
-    const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
+    const dim3 grid(trial_grid(run->n_trials, run->n_gpus, ds->n_cus)), block(kBlock);
     P.first_trial = run->first_trial, P.n_trials = (uint32_t)run->n_trials;
     if (local) {
       const uint32_t gpn = run->gpus_per_node;
@@ -920,7 +930,7 @@ int lbs_simulate_all(const lbs_dataset* ds, const lbs_run* run, uint32_t* trial_
   hipLaunchKernelGGL(k_lbs_clear_all, dim3(1), dim3(64), 0, s, ds_sums);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess) {
-    const dim3 grid((uint32_t)std::min<uint64_t>(run->n_trials, (uint64_t)ds->n_cus * kGridPerCu)), block(kBlock);
+    const dim3 grid(trial_grid(run->n_trials, run->n_gpus, ds->n_cus)), block(kBlock);
     const uint32_t pool = gpn * lb;
     void (*kernel)(const Params, const uint32_t*, const uint32_t*, uint32_t*, uint32_t*, unsigned long long*) =
         pool <= 64 ? k_lbs_all<1> : pool <= 128 ? k_lbs_all<2> : pool <= 256 ? k_lbs_all<4> : pool <= 512 ? k_lbs_all<8> : k_lbs_all<16>;
