@@ -132,6 +132,45 @@ def test_back_to_back_on_a_stream_without_synchronising_in_between():
     assert same((g2.cpu().numpy(), out[2].item(), out[3].item(), int(st[1])), r2)
 
 
+def test_captured_in_a_hip_graph_and_replayed_on_new_data():
+    """What the entry point is for: two calls (a larger and a smaller bucket) captured in one HIP graph, replayed
+    several times on fresh gradients with eager work and synchronisations in between; every replay is held to
+    bucket_clip on a plan, bit for bit.  The first, eager call has looked the scratch array up already, so the
+    captured calls consist of kernel launches only."""
+    gdt = B.BCA_GRAD_F16
+    n1, n2 = 300_000, 50_001
+    thr1 = torch.tensor([0.2], dtype=torch.float32, device="cuda")
+    thr2 = torch.tensor([0.05], dtype=torch.float32, device="cuda")
+    _, g1 = to_dev(host_grads(n1, 30, gdt), 0)
+    _, g2 = to_dev(host_grads(n2, 31, gdt), 0)
+    out = torch.full((4,), -1.0, device="cuda")
+    st = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        B.bucket_clip_flat(g1, n1, gdt, thr1, out[0:1], out[1:2], st[0:1], s)          # eager: sets the library up
+        s.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cg, stream=s):
+            cur = torch.cuda.current_stream()
+            B.bucket_clip_flat(g1, n1, gdt, thr1, out[0:1], out[1:2], st[0:1], cur)
+            B.bucket_clip_flat(g2, n2, gdt, thr2, out[2:3], out[3:4], st[1:2], cur)
+    torch.cuda.synchronize()
+    for k in range(4):
+        h1, h2 = host_grads(n1, 40 + k, gdt), host_grads(n2, 50 + k, gdt)
+        g1.copy_(torch.from_numpy(h1))
+        g2.copy_(torch.from_numpy(h2))
+        out.fill_(-1.0)
+        st.fill_(-1)
+        torch.cuda.synchronize()
+        cg.replay()
+        torch.cuda.synchronize()
+        r1, r2 = plan_clip(h1, gdt, 0, thr1), plan_clip(h2, gdt, 0, thr2)       # eager work between the replays
+        assert same((g1.cpu().numpy(), out[0].item(), out[1].item(), int(st[0])), r1), k
+        assert same((g2.cpu().numpy(), out[2].item(), out[3].item(), int(st[1])), r2), k
+        assert out[1].item() < 1.0 and out[3].item() < 1.0
+
+
 def test_status_bits_and_optional_outputs():
     gdt = B.BCA_GRAD_F32
     h = host_grads(50_000, 3, gdt)
