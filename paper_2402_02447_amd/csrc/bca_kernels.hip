@@ -371,6 +371,28 @@ __device__ __forceinline__ float clip_coef(float norm, float c, int32_t& status)
   return 1.f;
 }
 
+// The sum of partials[lo .. hi) in THE order every path uses (thread t adds lo + t, lo + t + 256, ... one after the
+// other, lanes by butterfly, wavefronts in index order), computed by the whole workgroup; loads are issued eight
+// at a time before the first addition, a slot past the end adding +0.0.  Valid in thread 0.
+__device__ __forceinline__ double sum_partials(const double* __restrict__ partials, uint64_t lo, uint64_t hi, double* s_w) {
+  const uint32_t tid = threadIdx.x;
+  double s = 0.0;
+  for (uint64_t i = lo + tid; i < hi; i += 8u * kBlock) {
+    double part[8];
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) {
+      const uint64_t j = i + (uint64_t)q * kBlock;
+      part[q] = j < hi ? partials[j] : 0.0;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 8u; ++q) s += part[q];
+  }
+  s = wave_sum(s);
+  if ((tid & 63u) == 0) s_w[tid >> 6] = s;
+  __syncthreads();
+  return ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
+}
+
 // One workgroup per bucket: threads take the bucket's partials in strides of 256
 // in fp64, lanes are combined by a butterfly, the four wavefronts through LDS in
 // index order.  Same order on every run, so norms are reproducible.
@@ -382,13 +404,8 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
   __shared__ double s_w[kWaves];
   const uint32_t b = b0 + blockIdx.x;
   const uint64_t lo = (uint64_t)bucket_chunk_off[b] * kWaves, hi = (uint64_t)bucket_chunk_off[b + 1] * kWaves;
-  double s = 0.0;
-  for (uint64_t i = lo + threadIdx.x; i < hi; i += kBlock) s += partials[i];
-  s = wave_sum(s);
-  if ((threadIdx.x & 63u) == 0) s_w[threadIdx.x >> 6] = s;
-  __syncthreads();
+  const double tot = sum_partials(partials, lo, hi, s_w);
   if (threadIdx.x == 0) {
-    const double tot = ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
     const float norm = (float)sqrt(tot);
     norms[b] = norm;
     if (bucket_sq != nullptr) bucket_sq[b] = tot;
@@ -677,6 +694,7 @@ __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, 
   float pp = 0.f, uu = 0.f;
   for (uint32_t j = tid; j < nvec; j += kBlock) {
     f32x4 g = G::template load4<GNT>(gv, j), p = ldv<true>(pv + j), m = ldv<true>(mv + j), v = ldv<true>(vv + j);
+    loads_issued();
     if constexpr (FUSED) g = g * coef;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -773,6 +791,7 @@ __global__ __launch_bounds__(kBlock) void k_lamb_update(const Chunk* __restrict_
     for (uint32_t j = tid; j < nvec; j += kBlock) {
       f32x4 p = ldv<true>(pv + j);
       const f32x4 m = ldv<true>(mv + j), v = ldv<true>(vv + j);
+      loads_issued();
 #pragma unroll
       for (int i = 0; i < 4; ++i) p[i] = __fmaf_rn(sc, adam_direction(p[i], m[i], v[i], k, wd), p[i]);
       stv<true>(pv + j, p);
@@ -1042,28 +1061,6 @@ __global__ __launch_bounds__(kBlock) void k_step(StepState st, const uint32_t* _
     // squared-norm items carry their chunk count (1 .. 4) in bits 28..29
     norm_item<GDT>(st, kind, item & 0x0fffffffu, ((item >> 28) & 3u) + 1u, epoch, thresholds, norms, coefs, sh);
   }
-}
-
-// The sum of partials[lo .. hi) in k_finalize's order (thread t adds lo + t, lo + t + 256, ... one after the
-// other, lanes by butterfly, wavefronts in index order), computed by the whole workgroup; loads are issued eight
-// at a time before the first addition, a slot past the end adding +0.0.  Valid in thread 0.
-__device__ __forceinline__ double sum_partials(const double* __restrict__ partials, uint64_t lo, uint64_t hi, double* s_w) {
-  const uint32_t tid = threadIdx.x;
-  double s = 0.0;
-  for (uint64_t i = lo + tid; i < hi; i += 8u * kBlock) {
-    double part[8];
-#pragma unroll
-    for (uint32_t q = 0; q < 8u; ++q) {
-      const uint64_t j = i + (uint64_t)q * kBlock;
-      part[q] = j < hi ? partials[j] : 0.0;
-    }
-#pragma unroll
-    for (uint32_t q = 0; q < 8u; ++q) s += part[q];
-  }
-  s = wave_sum(s);
-  if ((tid & 63u) == 0) s_w[tid >> 6] = s;
-  __syncthreads();
-  return ((s_w[0] + s_w[1]) + s_w[2]) + s_w[3];
 }
 
 // g <- coef * g over one chunk of the squared-norm cut.  A full, 16-byte aligned chunk of kDefaultChunkNorm
