@@ -34,11 +34,11 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for libbca's plain copy kernel
 # (profiles/k_step_<workload>.txt).  Key: (config, gradient type, single_launch).
 MEASURED_TRAFFIC_BYTES = {      # from profiles/k_step_<workload>.txt; a combination without a counter run reports null
-    (3, "f32", True): 10800042509, (2, "f32", True): 3527685663, (4, "f16", True): 9461053918,
-    (5, "f32", True): 10802529127, (3, "bf16", True): 9459152367}
-# The same for the other entry points (all kernels of one call summed), config 3, fp32 gradients.
-MEASURED_TRAFFIC_OTHER_OPS = {"adam": 9446928384, "norms": 1341876224, "lamb": 13542207488, "clip_lamb": 14911010816}
-
+    (3, "f32", True): 10803960290, (2, "f32", True): 3529458180, (4, "f16", True): 9465252253,
+    (5, "f32", True): 10805399362, (3, "bf16", True): 9463045573}
+# The same for the other entry points (all kernels of one call summed), config 3, fp32 gradients
+# (profiles/other_entry_points_bert_large_fp32_50MiB.txt).
+MEASURED_TRAFFIC_OTHER_OPS = {"adam": 9446939648, "norms": 1346181120, "lamb": 13547380736, "clip_lamb": 14914948096}
 
 def parse():
     ap = argparse.ArgumentParser()
