@@ -129,7 +129,7 @@ def other_ops(a, w, plan, g, p, m, v, dev):
         # Alg. 1 in the paper's order, without the all-reduce: every bucket clipped by a call of its own (norm, then
         # scale in place: every bucket of this workload clips), then Adam on the stored gradients
         "per_bucket": (per_bucket, gb + 2 * gb + 24 + gb,
-                       "bucket_clip per bucket (k_clip + k_finish each), then adam_step (k_adam)"),
+                       "bucket_clip per bucket (k_sqnorm + k_clip_scale each), then adam_step (k_adam)"),
     }
     fn, per_elt, what = ops[a.op]
 

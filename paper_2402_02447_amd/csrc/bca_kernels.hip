@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (MI355X): squared-norm partials, per-bucket finalize,
-// in-place scale, the (optionally clip-fused) Adam sweep, the whole fused step as
-// one pipelined launch, and LAMB's two sweeps.  Gradients are fp32, fp16 or bf16.
+// in-place scale, the two launches of the per-bucket clip (with and without a plan),
+// the (optionally clip-fused) Adam sweep, the whole fused step as one pipelined
+// launch with its finish kernel, and LAMB's two sweeps.  Gradients are fp32, fp16 or bf16.
 //
 // All streaming kernels are table driven: the host cuts the bucket layout into
 // chunks (<= chunk_elems consecutive elements of one tensor in one bucket,
@@ -859,7 +860,7 @@ __device__ __forceinline__ void ctl_or(uint32_t* w, uint32_t bits) {
   (void)__hip_atomic_fetch_or(w, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Shared memory of one k_step / k_clip workgroup.
+// Shared memory of one k_step workgroup.
 struct StepShared {
   uint32_t item;
   uint32_t flag;
