@@ -59,6 +59,23 @@ int main(void) {
   CHECK(strstr(bca_last_error(), "tensor 0") != NULL);
 
   {
+    /* Alg. 1's per-bucket thresholds, and the argument checks of the call that allocates nothing (all of them
+     * come before anything touches a GPU) */
+    float thr[4] = {0.f, 0.f, 0.f, 0.f};
+    uint64_t stats[2];
+    CHECK(bca_alg1_thresholds(2.0, 4, thr) == BCA_OK && thr[0] == 1.0f && thr[3] == 1.0f);
+    CHECK(bca_alg1_thresholds(0.0, 4, thr) == BCA_ERR_HPARAM);
+    CHECK(bca_alg1_thresholds(1.0, 4, NULL) == BCA_ERR_NULL);
+    CHECK(bucket_clip_flat(&dummy, ((uint64_t)1 << 28) + 1, BCA_GRAD_F32, &dummy, NULL, NULL, NULL, NULL) == BCA_ERR_RANGE);
+    CHECK(strstr(bca_last_error(), "at most") != NULL);
+    CHECK(bucket_clip_flat(&dummy, 16, 9, &dummy, NULL, NULL, NULL, NULL) == BCA_ERR_DTYPE);
+    CHECK(bucket_clip_flat(NULL, 16, BCA_GRAD_F32, &dummy, NULL, NULL, NULL, NULL) == BCA_ERR_NULL);
+    CHECK(bucket_clip_flat(&dummy, 16, BCA_GRAD_F32, NULL, NULL, NULL, NULL, NULL) == BCA_ERR_NULL);
+    CHECK(bucket_clip_flat((char*)&dummy + 1, 16, BCA_GRAD_F16, &dummy, NULL, NULL, NULL, NULL) == BCA_ERR_ALIGN);
+    CHECK(bca_plan_wait_stats(NULL, stats) == BCA_ERR_NULL);
+  }
+
+  {
     /* lengths 1..4 with 10, 0, 5, 5 samples; two strata */
     const uint32_t cum[5] = {0, 10, 10, 15, 20};
     const uint32_t ends[2] = {2, 4};
