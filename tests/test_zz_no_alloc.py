@@ -99,6 +99,24 @@ def test_two_calls_in_a_row_the_second_smaller_match_bucket_clip_bit_for_bit(gdt
             assert results[0][1] != results[1][1]
 
 
+def test_random_sizes_offsets_types_and_thresholds():
+    """Sixty random buckets in a row (sizes from empty to a few hundred thousand elements, element-aligned pointers,
+    all three gradient types, thresholds on both sides of the norm and at the norm itself), each against bucket_clip."""
+    rng = np.random.default_rng(2024)
+    for k in range(60):
+        gdt = int(rng.choice([B.BCA_GRAD_F32, B.BCA_GRAD_F16, B.BCA_GRAD_BF16]))
+        n = int(rng.choice([0, 1, 7, 255, 1024, 16383, 16384, 16385, 65536, 100_003, 300_000])) + int(rng.integers(0, 3))
+        offset = int(rng.integers(0, 8))
+        h = host_grads(n, 500 + k, gdt)
+        factor = float(rng.choice([0.01, 0.5, 0.999, 1.0, 1.001, 2.0, 1e6]))
+        thr = torch.tensor([factor * host_norm(h) if n else 1.0], dtype=torch.float32, device="cuda")
+        flat, ref = flat_clip(h, gdt, offset, thr), plan_clip(h, gdt, offset, thr)
+        assert same(flat, ref), (k, gdt, n, offset, factor, flat[1:], ref[1:])
+        if n:
+            assert abs(flat[1] - host_norm(h)) <= 1e-5 * host_norm(h)
+            assert 0.0 < flat[2] <= 1.0
+
+
 def test_bucket_beyond_16_mi_elements_takes_the_separate_finalize_and_still_matches():
     """More than 1 024 chunks: the coefficient is derived by a launch of its own (both entry points switch there),
     followed by a smaller call that goes back to the usual two launches."""
