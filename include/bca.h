@@ -190,6 +190,12 @@ uint32_t bca_plan_num_chunks(const bca_plan* plan, int table);
 /* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
 int bca_plan_chunk_info(const bca_plan* plan, int table, uint32_t i, uint32_t* tensor, uint64_t* begin,
                         uint32_t* len, uint32_t* bucket);
+/* The work list of the fused step, in the order its workgroups take it: item i is kind 0 = squared norms of
+ * `count` consecutive chunks of BCA_TABLE_NORM starting at `first`, kind 1 = Adam on chunk `first` of
+ * BCA_TABLE_APPLY (count 1), kind 2 = stand-in for bucket `first`, which has no elements (count 0).  Every
+ * squared-norm item of a bucket comes before every Adam item of that bucket. */
+uint32_t bca_plan_num_work_items(const bca_plan* plan);
+int bca_plan_work_item(const bca_plan* plan, uint32_t i, uint32_t* kind, uint32_t* first, uint32_t* count);
 /* Chunks of bucket b are [first, first + count); for BCA_TABLE_LAMB b is a tensor index. */
 int bca_plan_bucket_chunks(const bca_plan* plan, int table, uint32_t b, uint32_t* first, uint32_t* count);
 

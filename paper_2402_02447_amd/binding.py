@@ -25,7 +25,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
 EXPORTS = ["bca_alg1_thresholds", "bucket_clip_flat", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
-           "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
+           "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_work_items", "bca_plan_work_item", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
            "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_plan_wait_stats", "bca_copy_bytes", "bca_last_error",
            "bca_version"]
@@ -114,6 +114,9 @@ def load_library():
     L.bca_plan_num_groups.restype = u32
     L.bca_plan_norm_item_chunks.argtypes = [vp]
     L.bca_plan_norm_item_chunks.restype = u32
+    L.bca_plan_num_work_items.argtypes = [vp]
+    L.bca_plan_num_work_items.restype = u32
+    L.bca_plan_work_item.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32)]
     L.bca_plan_num_chunks.argtypes = [vp, i32]
     L.bca_plan_num_chunks.restype = u32
     L.bca_plan_chunk_info.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
@@ -241,6 +244,15 @@ class Plan:
     @property
     def norm_item_chunks(self) -> int:
         return int(self._L.bca_plan_norm_item_chunks(self._h))
+
+    def work_items(self):
+        """The fused step's work list as (kind, first, count) triples (bca_plan_work_item)."""
+        k, f, c = C.c_uint32(), C.c_uint32(), C.c_uint32()
+        out = []
+        for i in range(int(self._L.bca_plan_num_work_items(self._h))):
+            _check(self._L.bca_plan_work_item(self._h, i, C.byref(k), C.byref(f), C.byref(c)))
+            out.append((k.value, f.value, c.value))
+        return out
 
     def n_chunks(self, table: int = BCA_TABLE_APPLY) -> int:
         return int(self._L.bca_plan_num_chunks(self._h, table))

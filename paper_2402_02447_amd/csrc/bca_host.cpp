@@ -649,6 +649,18 @@ uint32_t bca_plan_num_groups(const bca_plan* p) { return p ? (uint32_t)p->groups
 
 uint32_t bca_plan_norm_item_chunks(const bca_plan* p) { return p ? p->norm_item_chunks : 0; }
 
+uint32_t bca_plan_num_work_items(const bca_plan* p) { return p ? (uint32_t)p->work.size() : 0; }
+
+int bca_plan_work_item(const bca_plan* p, uint32_t i, uint32_t* kind, uint32_t* first, uint32_t* count) {
+  if (!p) return fail(BCA_ERR_NULL, "plan is NULL");
+  if (i >= p->work.size()) return fail(BCA_ERR_RANGE, "work item index out of range");
+  const uint32_t item = p->work[i], k = item >> 30;
+  if (kind) *kind = k;
+  if (first) *first = k == kItemAdam ? (item & 0x3fffffffu) : (item & 0x0fffffffu);
+  if (count) *count = k == kItemNorm ? ((item >> 28) & 3u) + 1u : k == kItemAdam ? 1u : 0u;
+  return BCA_OK;
+}
+
 int bca_plan_chunk_info(const bca_plan* p, int which, uint32_t i, uint32_t* tensor, uint64_t* begin, uint32_t* len,
                         uint32_t* bucket) {
   const Table* t = pick_table(p, which);

