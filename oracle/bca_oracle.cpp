@@ -32,9 +32,11 @@
 //
 // Parity pins: every function here is pinned by tests/test_oracle_*.py against
 // closed forms, invariants, brute force and library routines (orc_compare_f32, the
-// acceptance rule of the GPU tests, by tests/test_oracle_compare.py).  The values that
-// propagate from non-finite gradients are "parity unpinned" (NaN != NaN); only
-// the status flag and the skip mode are pinned.
+// acceptance rule of the GPU tests, by tests/test_oracle_compare.py).  Non-finite
+// gradients get no special case beyond the status bit and the skip mode: what
+// propagates from them is what IEEE arithmetic gives for the formulas as written
+// (an Inf makes the norm Inf and the coefficient 0, a NaN makes the comparison with
+// the threshold false and the coefficient 1), pinned in tests/test_oracle_adam.py.
 
 #include <cmath>
 #include <cstdint>

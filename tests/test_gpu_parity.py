@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2402_02447_amd as B
 import workloads as W
-from gpu_util import (Device, bits_equal, check_norms, check_state, f64, hp_kwargs, hyper, to_host)
+from gpu_util import (REL_TOL, Device, bits_equal, check_norms, check_state, f64, hp_kwargs, hyper, to_dev, to_host)
 
 pytestmark = pytest.mark.gpu
 
@@ -731,3 +731,184 @@ def test_expired_wait_costs_time_only(gdtype):
         ref.sync()
         assert int(ref.status.item()) == 0
         d.close(), ref.close()
+
+
+# ------------------------------------------------------------------ values that propagate from Inf and NaN gradients
+
+
+def _same_where_numbers_nan_where_nan(got, expect, what):
+    """Stored gradients: a NaN where a NaN is due (its payload is the hardware's business), the exact bits elsewhere."""
+    gf = W.bf16_bits_to_float32(got) if got.dtype == np.uint16 else got
+    ef = W.bf16_bits_to_float32(expect) if expect.dtype == np.uint16 else expect
+    nan = np.isnan(ef)
+    assert np.array_equal(np.isnan(gf), nan), f"{what}: NaNs are not where they should be"
+    gb, eb = got.view(np.uint8).reshape(got.shape[0], -1), expect.view(np.uint8).reshape(expect.shape[0], -1)
+    assert np.array_equal(gb[~nan], eb[~nan]), f"{what}: stored gradient is not fl(coef * g)"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_inf_and_nan_gradients_propagate_as_in_the_oracle(dtype):
+    """No route treats a non-finite gradient specially beyond the status bit, and neither does the oracle: an infinite
+    element makes its bucket's norm +Inf and the coefficient 0 (finite elements of the bucket then only decay, the
+    infinite one becomes NaN in g-hat, m, v and p); a NaN makes the norm NaN and the coefficient 1 (the NaN stays in its
+    own element).  Every output of every route is compared element by element, NaN against NaN."""
+    numels = [40_000, 20_003, 70_001, 5_000, 33_000, 32_768]
+    lay = W.layout_flat_split(numels, 30_000)
+    nb = lay.n_buckets
+    assert nb >= 6 and lay.tensors_split() >= 2
+    if dtype == "f32":
+        g = W.normal_tensors(numels, 77, "g", 1e-2, threads=1)
+    elif dtype == "f16":
+        g = W.student_t_fp16_tensors(numels, 77, 1e-3, threads=1)
+    else:
+        g = oracle.Bf16(W.normal_bf16_tensors(numels, 77, 1e-2, threads=1))
+    p, m, v = (W.normal_tensors(numels, 77, "p", 0.02, threads=1), W.normal_tensors(numels, 77, "m", 3e-4, threads=1),
+               W.warm_second_moment(numels, 77, threads=1))
+    clean = oracle.bucket_norms(lay, g)
+    thr = np.asarray([clean[b] * (0.5 if b % 2 else 2.0) for b in range(nb)], np.float32)
+
+    def code(x):                                                   # the value in the gradients' storage type
+        if dtype == "bf16":
+            return W.float32_to_bf16_bits(np.asarray([x], np.float32))[0]
+        return g[0].dtype.type(x)
+
+    def plant(b, where, x):
+        t, beg, ln = next(iter(lay.segments_of(b)))
+        g[t][beg + int(where * (ln - 1))] = code(x)
+
+    plant(0, 0.5, np.inf)                                          # +Inf alone
+    plant(2, 0.0, np.nan)                                          # NaN alone, first element of the bucket
+    plant(3, 1.0, -np.inf), plant(3, 0.25, np.nan)                 # -Inf and NaN together: Inf + NaN = NaN
+    plant(5, 0.1, np.inf), plant(5, 0.9, -np.inf)                  # two infinities
+    kind = {0: "inf", 2: "nan", 3: "nan", 5: "inf"}
+    hp, step = W.Hyper(), 4
+
+    def check_head(dev, onorm, ocoef, ost):
+        gn, gc = dev.norms.cpu().numpy(), dev.coefs.cpu().numpy()
+        for b in range(nb):
+            if kind.get(b) == "inf":
+                assert np.isposinf(onorm[b]) and np.isposinf(gn[b]) and ocoef[b] == 0.0 and gc[b] == 0.0, b
+            elif kind.get(b) == "nan":
+                assert np.isnan(onorm[b]) and np.isnan(gn[b]) and ocoef[b] == 1.0 and gc[b] == 1.0, b
+            else:
+                assert abs(gn[b] - onorm[b]) <= REL_TOL * onorm[b] and np.isclose(gc[b], ocoef[b], rtol=1e-6, atol=0), b
+        assert ost == B.BCA_STATUS_NONFINITE and int(dev.status.item()) == ost
+        return gc
+
+    def check_stored(dev, og, gc):
+        got = to_host(dev.g)
+        for b in range(nb):
+            c = np.float32(gc[b])
+            for t, beg, ln in lay.segments_of(b):
+                o, a = g[t][beg:beg + ln], got[t][beg:beg + ln]
+                with np.errstate(invalid="ignore"):
+                    if dtype == "bf16":
+                        expect = W.float32_to_bf16_bits(W.bf16_bits_to_float32(o) * c) if c != 1 else o
+                    else:
+                        expect = (o.astype(np.float32) * c).astype(o.dtype) if c != 1 else o
+                _same_where_numbers_nan_where_nan(a, expect, f"bucket {b}, tensor {t}")
+        for t, (a, w) in enumerate(zip(got, og)):                   # and against the oracle's own stored values
+            af = W.bf16_bits_to_float32(a) if a.dtype == np.uint16 else a.astype(np.float32)
+            wf = W.bf16_bits_to_float32(w) if w.dtype == np.uint16 else w.astype(np.float32)
+            assert np.array_equal(np.isnan(af), np.isnan(wf)), t
+            ok = ~np.isnan(wf)
+            if a.dtype == np.float32:
+                assert np.allclose(af[ok], wf[ok], rtol=5e-7, atol=1e-45), t
+            else:
+                ai, wi = a.view(np.int16).astype(np.int32), w.view(np.int16).astype(np.int32)
+                assert np.abs(ai - wi)[ok].max(initial=0) <= 1, t
+
+    def check_pmv(dev, op, om, ov):
+        check_state("p", to_host(dev.p), op), check_state("m", to_host(dev.m), om)
+        check_state("v", to_host(dev.v), ov, strict_rel=True)
+        n_nan = sum(int(np.isnan(x).sum()) for x in op)
+        assert n_nan == 6, n_nan                                   # the six planted elements, nothing else
+
+    # fused, without and with write-back
+    for flags in (0, B.BCA_WRITE_BACK_GRADS):
+        dev = Device(lay, g, p, m, v)
+        dev.plan.bucket_clip_adam(dev.thresholds(thr), hyper(hp), step, flags, dev.norms, dev.coefs, dev.status)
+        dev.sync()
+        og = type(g)(x.copy() for x in g)
+        op, om, ov = f64(p), f64(m), f64(v)
+        onorm, ocoef, ost = oracle.bucket_clip_adam(lay, og, op, om, ov, thr, step=step, write_back=bool(flags),
+                                                    **hp_kwargs(hp))
+        gc = check_head(dev, onorm, ocoef, ost)
+        check_pmv(dev, op, om, ov)
+        if flags:
+            check_stored(dev, og, gc)
+        else:
+            assert bits_equal(to_host(dev.g), g)
+        dev.close()
+
+    # clip-only in one call and as norms + apply, then Adam on the stored gradients
+    one, two = Device(lay, g, p, m, v), Device(lay, g, p, m, v)
+    one.plan.bucket_clip(0, nb, one.thresholds(thr), one.norms, one.coefs, one.status)
+    two.plan.bucket_clip_norms(0, nb, two.norms)
+    two.plan.bucket_clip_apply(0, nb, two.thresholds(thr), two.norms, two.coefs, two.status)
+    one.sync()
+    onorm = oracle.bucket_norms(lay, g)
+    ocoef, ost = oracle.clip_coefs(onorm, thr)
+    og = type(g)(x.copy() for x in g)
+    oracle.bucket_scale(lay, og, ocoef)
+    for dev in (one, two):
+        gc = check_head(dev, onorm, ocoef, ost)
+        check_stored(dev, og, gc)
+    assert bits_equal(to_host(one.g), to_host(two.g))              # the same instructions: the same NaN payloads too
+    if dtype != "f32":
+        one.set_grads(og)
+    one.plan.adam_step(hyper(hp), step)
+    one.sync()
+    op, om, ov = f64(p), f64(m), f64(v)
+    oracle.adam_step(lay, og, op, om, ov, step=step, **hp_kwargs(hp))
+    check_pmv(one, op, om, ov)
+    one.close(), two.close()
+
+    # LAMB after the same clipping: a tensor that holds a NaN has NaN norms, which the ratio rule (both norms > 0,
+    # else 1) turns into a ratio of 1 on both sides; the other tensors are untouched by their neighbours' trouble
+    dev = Device(lay, g, p, m, v)
+    dev.plan.bucket_clip_lamb(dev.thresholds(thr), hyper(hp), step, 0, dev.norms, dev.coefs, dev.trust, dev.status)
+    dev.sync()
+    og = type(g)(x.copy() for x in g)
+    op, om, ov = f64(p), f64(m), f64(v)
+    onorm, ocoef, otrust, ost = oracle.bucket_clip_lamb(lay, og, op, om, ov, thr, step=step, **hp_kwargs(hp))
+    check_head(dev, onorm, ocoef, ost)
+    gt = dev.trust.cpu().numpy()[:lay.n_tensors]
+    assert np.all(np.isfinite(otrust)) and np.all(np.abs(gt - otrust) <= REL_TOL * otrust)
+    with_nan = [t for t in range(lay.n_tensors) if np.isnan(om[t]).any()]
+    assert with_nan and all(otrust[t] == 1.0 and gt[t] == 1.0 for t in with_nan)
+    assert any(otrust[t] != 1.0 for t in range(lay.n_tensors) if t not in with_nan)
+    check_pmv(dev, op, om, ov)
+    dev.close()
+
+    # the flat call on one contiguous array
+    t = 2
+    h = g[t].copy()
+    for x in (np.inf, np.nan):
+        hh = h.copy()
+        hh[:] = np.where(np.isfinite(W.bf16_bits_to_float32(h) if dtype == "bf16" else h.astype(np.float32)), h, code(0.0))
+        hh[12_345] = code(x)
+        lay1 = W.layout_one_tensor_per_bucket([hh.shape[0]])
+        g1 = oracle.Bf16([hh]) if dtype == "bf16" else [hh]
+        d1 = Device(lay1, g1, [p[t]], [m[t]], [v[t]], chunk_norm=16384)
+        t1 = d1.thresholds(np.asarray([1e-3], np.float32))
+        flat = to_dev(g1)[0]
+        fn, fc = torch.full((1,), -1.0, device="cuda"), torch.full((1,), -1.0, device="cuda")
+        fs = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        B.bucket_clip_flat(flat, hh.shape[0], d1.plan.grad_dtype, t1, fn, fc, fs)
+        d1.plan.bucket_clip(0, 1, t1, d1.norms, d1.coefs, d1.status)
+        d1.sync()
+        assert int(fs.item()) == B.BCA_STATUS_NONFINITE == int(d1.status.item())
+        assert bits_equal([fn.cpu().numpy(), fc.cpu().numpy()], [d1.norms.cpu().numpy(), d1.coefs.cpu().numpy()])
+        assert bits_equal(to_host([flat]), to_host(d1.g))
+        on = oracle.bucket_norms(lay1, g1)
+        oc, _ = oracle.clip_coefs(on, np.asarray([1e-3], np.float32))
+        o1 = type(g1)(y.copy() for y in g1)
+        oracle.bucket_scale(lay1, o1, oc)
+        assert (np.isposinf(on[0]) and np.isposinf(fn.item()) and fc.item() == 0.0 == oc[0]) if np.isinf(x) else \
+               (np.isnan(on[0]) and np.isnan(fn.item()) and fc.item() == 1.0 == oc[0])
+        a, w = to_host([flat])[0], o1[0]
+        af = W.bf16_bits_to_float32(a) if dtype == "bf16" else a.astype(np.float32)
+        wf = W.bf16_bits_to_float32(w) if dtype == "bf16" else w.astype(np.float32)
+        assert np.array_equal(af, wf, equal_nan=True) and int(np.isnan(wf).sum()) == 1
+        d1.close()

@@ -321,6 +321,62 @@ def test_nonfinite_gradient_sets_flag_and_skip_mode_is_a_bit_exact_noop():
     assert any(not np.array_equal(a, b) for a, b in zip(p, ref[:len(p)]))
 
 
+def test_values_that_propagate_from_inf_and_nan_gradients_are_what_ieee_arithmetic_gives():
+    """The formulas applied as they stand (no special case beyond the status bit).  An infinite gradient makes its
+    bucket's norm infinite and the coefficient c / inf = 0: every finite gradient of that bucket becomes 0, so its
+    elements only decay (m' = b1 m, v' = b2 v, and p' follows from those: the zero-gradient closed form), while the
+    infinite element itself is 0 * inf = NaN in m, v and p.  A NaN gradient makes the norm NaN, the comparison
+    norm >= c false and the coefficient 1: the bucket is not scaled, the NaN stays in its own element and the other
+    elements take an ordinary Adam step (held to the independent high-precision recurrence).  Buckets are
+    independent: a third, clean bucket is clipped and updated as if the others were not there."""
+    lay = W.layout_one_tensor_per_bucket([4, 3, 2])
+    g = [np.asarray([np.inf, 3.0, -4.0, 0.0], np.float32), np.asarray([np.nan, 2.0, -0.5], np.float32),
+         np.asarray([3.0, 4.0], np.float32)]
+    p0 = [np.asarray([0.5, -0.25, 0.125, 1.0]), np.asarray([0.3, 0.2, -0.1]), np.asarray([1.0, -1.0])]
+    m0 = [np.asarray([0.01, -0.02, 0.03, 0.0]), np.asarray([0.0, 0.0, 0.0]), np.asarray([0.0, 0.0])]
+    v0 = [np.asarray([1e-4, 4e-4, 9e-4, 0.0]), np.asarray([0.0, 0.0, 0.0]), np.asarray([0.0, 0.0])]
+    p, m, v = [x.copy() for x in p0], [x.copy() for x in m0], [x.copy() for x in v0]
+    thr = np.asarray([1.0, 1.0, 2.5], np.float32)
+    t = 3
+    norms, coefs, st = oracle.bucket_clip_adam(lay, g, p, m, v, thr, step=t, **HP)
+    assert st == oracle.STATUS_NONFINITE
+    assert np.isposinf(norms[0]) and coefs[0] == 0.0
+    assert np.isnan(norms[1]) and coefs[1] == 1.0
+    assert norms[2] == 5.0 and coefs[2] == np.float32(0.5)
+    b1, b2, lr, eps, wd = HP["beta1"], HP["beta2"], HP["lr"], HP["eps"], HP["weight_decay"]
+    # bucket 0: element 0 is NaN everywhere; elements 1..3 see a zero gradient
+    assert np.isnan(p[0][0]) and np.isnan(m[0][0]) and np.isnan(v[0][0])
+    for i in (1, 2, 3):
+        em, ev = b1 * m0[0][i], b2 * v0[0][i]
+        ep = p0[0][i] - lr * ((em / (1 - b1 ** t)) / (math.sqrt(ev / (1 - b2 ** t)) + eps) + wd * p0[0][i])
+        assert m[0][i] == pytest.approx(em, rel=1e-15, abs=0) and v[0][i] == pytest.approx(ev, rel=1e-15, abs=0)
+        assert p[0][i] == pytest.approx(ep, rel=1e-14)
+    # bucket 1: element 0 NaN, the others an ordinary first-moment-from-zero step at t = 3 with their own gradient
+    assert np.isnan(p[1][0]) and np.isnan(m[1][0]) and np.isnan(v[1][0])
+    for i, gi in ((1, 2.0), (2, -0.5)):
+        em, ev = (1 - b1) * gi, (1 - b2) * gi * gi
+        ep = p0[1][i] - lr * ((em / (1 - b1 ** t)) / (math.sqrt(ev / (1 - b2 ** t)) + eps) + wd * p0[1][i])
+        assert m[1][i] == pytest.approx(em, rel=1e-15) and v[1][i] == pytest.approx(ev, rel=1e-15)
+        assert p[1][i] == pytest.approx(ep, rel=1e-14)
+    # bucket 2: clipped to half, as if alone
+    for i, gi in ((0, 1.5), (1, 2.0)):
+        assert m[2][i] == pytest.approx((1 - b1) * gi, rel=1e-15) and v[2][i] == pytest.approx((1 - b2) * gi * gi, rel=1e-15)
+    # the unfused chain stores the scaled gradients: 0 * inf = NaN, 0 * finite = 0 (signed), the NaN bucket untouched
+    g2 = [x.copy() for x in g]
+    oracle.bucket_scale(lay, g2, coefs)
+    assert np.isnan(g2[0][0]) and np.all(g2[0][1:] == 0.0) and np.signbit(g2[0][2]) and not np.signbit(g2[0][1])
+    assert np.isnan(g2[1][0]) and np.array_equal(g2[1][1:], g[1][1:]) and np.array_equal(g2[2], np.asarray([1.5, 2.0], np.float32))
+    # negative infinity and an overflowing sum of finite squares behave the same way
+    for bad in (-np.inf, np.float32(3e38)):
+        gg = [np.asarray([bad, 3e38 if bad > 0 else 1.0], np.float32)]
+        pp, mm, vv = [np.asarray([1.0, 1.0])], [np.zeros(2)], [np.zeros(2)]
+        n, c, s2 = oracle.bucket_clip_adam(W.layout_one_tensor_per_bucket([2]), gg, pp, mm, vv, np.asarray([1.0], np.float32), step=1, **HP)
+        if np.isinf(bad):
+            assert np.isposinf(n[0]) and c[0] == 0.0 and s2 == oracle.STATUS_NONFINITE and np.isnan(mm[0][0]) and mm[0][1] == 0.0
+        else:       # 3e38^2 is finite in fp64: the oracle's norm is finite (the GPU's fp32 squares would overflow; see R14)
+            assert np.isfinite(n[0]) and s2 == 0
+
+
 def test_adam_and_lamb_steps_do_not_depend_on_the_gradient_scale_when_eps_is_zero():
     # Adam's direction mhat / sqrt(vhat) is homogeneous of degree 0 in the gradient history; scaling every
     # gradient by a power of two scales m by it and v by its square exactly, so p must come out bit-identical.
