@@ -781,10 +781,11 @@ int bucket_clip_norms(bca_plan* p, uint32_t b0, uint32_t b1, float* norms, void*
   hipStream_t s = (hipStream_t)stream;
   const Table& T = p->norm_tab;
   const uint32_t c0 = T.bucket_off[b0], n = T.bucket_off[b1] - c0;
-  // Called per bucket as buckets become ready, bucket_clip_apply follows shortly:
-  // keep the gradients cacheable.
+  // Called per bucket as buckets become ready, bucket_clip_apply follows shortly: keep the gradients cacheable,
+  // unless the range is too large to be found in the cache again.
+  const bool keep = (uint64_t)n * T.chunk_elems * grad_bytes(p->grad_dtype) <= kKeepCachedBytes;
   hipError_t e = launch_sqnorm(p->grad_dtype, T.d_chunks, c0, n, p->d_partials, nullptr,
-                               make_launch(p, norm_grid(p, n), n, true), s);
+                               make_launch(p, norm_grid(p, n), n, keep), s);
   if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
   e = launch_finalize(p->d_partials, T.d_bucket_off, b0, b1, nullptr, norms, nullptr, nullptr, nullptr, s);
   if (e != hipSuccess) return fail_hip(e, "launching the finalize kernel");
@@ -829,7 +830,8 @@ int bucket_clip(bca_plan* p, uint32_t b0, uint32_t b1, const float* thresholds, 
   for (uint32_t b = b0; b < b1; ++b) most = std::max(most, TN.bucket_off[b + 1] - TN.bucket_off[b]);
   // First launch: the squared-norm partials of the range's chunks (one workgroup per chunk: a single bucket has
   // few of them); it also clears the status word.
-  hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, cn0, nn, p->d_partials, st, make_launch(p, 0, nn, true), s);
+  const bool keep = (uint64_t)nn * TN.chunk_elems * grad_bytes(p->grad_dtype) <= kKeepCachedBytes;
+  hipError_t e = launch_sqnorm(p->grad_dtype, TN.d_chunks, cn0, nn, p->d_partials, st, make_launch(p, 0, nn, keep), s);
   if (e != hipSuccess) return fail_hip(e, "launching the squared-norm kernel");
   if (most <= kMaxChunksForInlineFinalize && !(p->tune_flags & BCA_TUNE_MULTI_LAUNCH)) {
     // Second launch: one workgroup per chunk derives the bucket's coefficient from the partials and scales the chunk.
