@@ -134,6 +134,10 @@ typedef struct bca_tuning {
                             (1 when chunk_norm is given)                                               */
   uint32_t norm_lead;    /* fused calls: bucket groups by which the squared-norm items run ahead of the Adam
                             items in the work list (their gradients must stay cached that long); 0: default */
+  uint64_t lamb_group_elems; /* lamb_step: the tensors are swept in runs of consecutive tensors of at most this many
+                            elements (a larger tensor is a run of its own), both sweeps of a run before the next run, so
+                            that the second sweep reads the moments from cache; 0: default (32 Mi); results do not
+                            depend on it                                                                        */
 } bca_tuning;
 
 /* which chunk table an introspection call looks at */
@@ -190,6 +194,12 @@ uint32_t bca_plan_num_chunks(const bca_plan* plan, int table);
 /* For chunk i: tensor index, first element, length, bucket.  Any out pointer may be NULL. */
 int bca_plan_chunk_info(const bca_plan* plan, int table, uint32_t i, uint32_t* tensor, uint64_t* begin,
                         uint32_t* len, uint32_t* bucket);
+/* The runs of tensors in which lamb_step sweeps the plan (bca_tuning.lamb_group_elems): their number, and the
+ * tensors [*first_tensor, *end_tensor) of run i (either pointer may be NULL).  Runs are consecutive and cover all
+ * tensors.  BCA_ERR_RANGE for i out of range. */
+uint32_t bca_plan_num_lamb_runs(const bca_plan* plan);
+int bca_plan_lamb_run(const bca_plan* plan, uint32_t i, uint32_t* first_tensor, uint32_t* end_tensor);
+
 /* The work list of the fused step, in the order its workgroups take it: item i is kind 0 = squared norms of
  * `count` consecutive chunks of BCA_TABLE_NORM starting at `first`, kind 1 = Adam on chunk `first` of
  * BCA_TABLE_APPLY (count 1), kind 2 = stand-in for bucket `first`, which has no elements (count 0).  Every

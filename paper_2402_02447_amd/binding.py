@@ -25,7 +25,7 @@ _ERR_NAMES = {-1: "BCA_ERR_NULL", -2: "BCA_ERR_LAYOUT", -3: "BCA_ERR_RANGE", -4:
               -5: "BCA_ERR_UNBOUND", -6: "BCA_ERR_HIP", -7: "BCA_ERR_DTYPE", -8: "BCA_ERR_ALIGN", -9: "BCA_ERR_NOMEM"}
 
 EXPORTS = ["bca_alg1_thresholds", "bucket_clip_flat", "bca_plan_create", "bca_plan_bind", "bca_plan_set_decay_mask", "bca_plan_set_device_hyper", "bca_plan_destroy", "bca_plan_num_buckets",
-           "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_work_items", "bca_plan_work_item", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
+           "bca_plan_num_groups", "bca_plan_norm_item_chunks", "bca_plan_num_work_items", "bca_plan_work_item", "bca_plan_num_lamb_runs", "bca_plan_lamb_run", "bca_plan_num_chunks", "bca_plan_chunk_info", "bca_plan_bucket_chunks",
            "bucket_clip_norms", "bucket_clip_apply", "bucket_clip", "adam_step", "bucket_clip_adam", "lamb_step",
            "bucket_clip_lamb", "bca_plan_profile", "bca_plan_profile_read", "bca_plan_wait_stats", "bca_copy_bytes", "bca_last_error",
            "bca_version"]
@@ -50,7 +50,7 @@ class _Tuning(C.Structure):
     _fields_ = [("chunk_norm", C.c_uint32), ("chunk_apply", C.c_uint32), ("grid_norm", C.c_uint32),
                 ("grid_apply", C.c_uint32), ("unroll_apply", C.c_uint32), ("flags", C.c_uint32),
                 ("group_bytes", C.c_uint64), ("adam_lds_reserve", C.c_uint32), ("spin_limit", C.c_uint32),
-                ("norm_item_chunks", C.c_uint32), ("norm_lead", C.c_uint32)]
+                ("norm_item_chunks", C.c_uint32), ("norm_lead", C.c_uint32), ("lamb_group_elems", C.c_uint64)]
 
 
 @dataclass
@@ -117,6 +117,9 @@ def load_library():
     L.bca_plan_num_work_items.argtypes = [vp]
     L.bca_plan_num_work_items.restype = u32
     L.bca_plan_work_item.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32)]
+    L.bca_plan_num_lamb_runs.argtypes = [vp]
+    L.bca_plan_num_lamb_runs.restype = u32
+    L.bca_plan_lamb_run.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u32)]
     L.bca_plan_num_chunks.argtypes = [vp, i32]
     L.bca_plan_num_chunks.restype = u32
     L.bca_plan_chunk_info.argtypes = [vp, i32, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u32), C.POINTER(u32)]
@@ -188,7 +191,7 @@ class Plan:
                  seg_begin: Sequence[int], seg_len: Sequence[int], grad_dtype: int = BCA_GRAD_F32, device: int = 0,
                  chunk_norm: int = 0, chunk_apply: int = 0, grid_norm: int = 0, grid_apply: int = 0,
                  unroll_apply: int = 0, tune_flags: int = 0, group_bytes: int = 0, adam_lds_reserve: int = 0,
-                 spin_limit: int = 0, norm_item_chunks: int = 0, norm_lead: int = 0):
+                 spin_limit: int = 0, norm_item_chunks: int = 0, norm_lead: int = 0, lamb_group_elems: int = 0):
         L = load_library()
         self._L = L
         self._h = C.c_void_p()
@@ -199,7 +202,7 @@ class Plan:
         for i in range(n_seg):
             segs[i] = _Segment(int(seg_tensor[i]), 0, int(seg_begin[i]), int(seg_len[i]))
         tune = _Tuning(chunk_norm, chunk_apply, grid_norm, grid_apply, unroll_apply, tune_flags, group_bytes,
-                       adam_lds_reserve, spin_limit, norm_item_chunks, norm_lead)
+                       adam_lds_reserve, spin_limit, norm_item_chunks, norm_lead, lamb_group_elems)
         _check(L.bca_plan_create(C.byref(self._h), device, len(numel), numel.ctypes.data_as(C.POINTER(C.c_uint64)),
                                  len(off) - 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), segs, grad_dtype,
                                  C.byref(tune)))
@@ -244,6 +247,15 @@ class Plan:
     @property
     def norm_item_chunks(self) -> int:
         return int(self._L.bca_plan_norm_item_chunks(self._h))
+
+    def lamb_runs(self):
+        """The runs of tensors lamb_step sweeps one after the other, as (first_tensor, end_tensor) pairs."""
+        a, b = C.c_uint32(), C.c_uint32()
+        out = []
+        for i in range(int(self._L.bca_plan_num_lamb_runs(self._h))):
+            _check(self._L.bca_plan_lamb_run(self._h, i, C.byref(a), C.byref(b)))
+            out.append((a.value, b.value))
+        return out
 
     def work_items(self):
         """The fused step's work list as (kind, first, count) triples (bca_plan_work_item)."""

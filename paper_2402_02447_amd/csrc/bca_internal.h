@@ -83,6 +83,10 @@ constexpr uint64_t kDefaultGroupElems = 8ull << 20;
 // before it is read again, and streams faster with non-temporal loads (measured on MI355X, BERT-Large, all buckets
 // in one call: 202 instead of 225 us).
 constexpr uint64_t kKeepCachedBytes = 128ull << 20;
+// lamb_step: tensors are swept in runs of at most this many elements, both sweeps of a run before the next run, so
+// that the second sweep reads the moments from cache (measured on MI355X, BERT-Large: 16 Mi 2.20 ms, 32 Mi 2.04,
+// 48 Mi 2.04, 64 Mi 2.11, one run 2.18; the gain of short runs is eaten by their three launches each).
+constexpr uint64_t kLambGroupElems = 32ull << 20;
 // The stand-alone Adam sweep streams 3-5 % faster with three workgroups (twelve wavefronts) per compute unit
 // than with all eight: fewer requests in flight suit the four-read / three-write mix (measured on MI355X:
 // BERT-Large 1.614 -> 1.537 ms, BERT-Base 0.529 -> 0.511 ms).  48 KiB of the 160 KiB LDS per workgroup give that.
@@ -184,7 +188,7 @@ hipError_t launch_clip_flat(int device, int gdt, void* g, uint64_t n, const floa
 // coefs == nullptr: gradients as stored.  Trust: per tensor, ratio and step scale.
 // Stage 2: p <- p + scale_t * update, the update recomputed from the stored moments.
 hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const float* coefs, bool write_back,
-                               double* sums, const AdamK& k, hipStream_t stream);
+                               double* sums, bool keep, const AdamK& k, hipStream_t stream);
 // Derives the sweeps' constants from hyper-parameters in device memory (one thread).
 hipError_t launch_hyper(const bca_adam_device* dev, AdamK* out, hipStream_t stream);
 hipError_t launch_lamb_trust(const double* sums, const uint32_t* tensor_off, uint32_t n_tensors, const AdamK& k,
@@ -214,6 +218,7 @@ struct bca_plan {
   bca::Table norm_tab, apply_tab;
   // LAMB: the fine cut again, tensor by tensor (chunks of tensor t are tensor_off[t] .. tensor_off[t+1]-1)
   bca::Table lamb_tab;
+  std::vector<std::pair<uint32_t, uint32_t>> lamb_groups;  // runs of consecutive tensors [first, last) swept together
   std::vector<uint32_t> tensor_off;
   uint32_t* d_tensor_off = nullptr;
   uint32_t* d_apply_to_lamb = nullptr;  // for every chunk of apply_tab, its index in lamb_tab

@@ -676,7 +676,7 @@ __device__ __forceinline__ double block_sum(double x, double* s_w) {
 // are added in fp32 first).  coef != 1 only behind clipping; WB: the scaled gradient,
 // rounded to its storage type, also replaces g.  GNT: whether g streams (it does not
 // when the squared-norm pass has just read it and it is still cached).
-template <int GDT, bool FUSED, bool WB, bool GNT>
+template <int GDT, bool FUSED, bool WB, bool GNT, bool KEEP = false>
 __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, const AdamK& k, double* s_pp,
                                                    double* s_uu, double* __restrict__ out) {
   typedef Grad<GDT> G;
@@ -705,7 +705,7 @@ __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, 
       pp = __fmaf_rn(p[i], p[i], pp), uu = __fmaf_rn(u, u, uu);
       m[i] = mi, v[i] = vi;
     }
-    stv<true>(mv + j, m), stv<true>(vv + j, v);
+    stv<!KEEP>(mv + j, m), stv<!KEEP>(vv + j, v);
     if (wb) G::template store4<GNT>(gv, j, g);
   }
   void* gbase = reinterpret_cast<void*>(en.g);
@@ -727,7 +727,7 @@ __device__ __forceinline__ void lamb_moments_chunk(const Entry& en, float coef, 
   if (tid == 0) out[0] = tpp, out[1] = tuu;
 }
 
-template <int GDT, bool FUSED, bool WB>
+template <int GDT, bool FUSED, bool WB, bool KEEP>
 __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict__ table, uint32_t n,
                                                           const float* __restrict__ coefs,
                                                           double* __restrict__ sums, const AdamK ka) {
@@ -737,7 +737,7 @@ __global__ __launch_bounds__(kBlock) void k_lamb_moments(const Chunk* __restrict
     const Entry en = read_entry(&table[ci]);
     float coef = 1.f;
     if constexpr (FUSED) coef = coefs[en.bucket];
-    lamb_moments_chunk<GDT, FUSED, WB, true>(en, coef, k, s_pp, s_uu, sums + (uint64_t)ci * 2u);
+    lamb_moments_chunk<GDT, FUSED, WB, true, KEEP>(en, coef, k, s_pp, s_uu, sums + (uint64_t)ci * 2u);
     __syncthreads();  // s_pp / s_uu are reused by the next chunk
   }
 }
@@ -1445,16 +1445,17 @@ hipError_t launch_adam(int gdt, const Chunk* table, uint32_t c0, uint32_t n, con
 }
 
 hipError_t launch_lamb_moments(int gdt, const Chunk* table, uint32_t n, const float* coefs, bool write_back,
-                               double* sums, const AdamK& k, hipStream_t stream) {
+                               double* sums, bool keep, const AdamK& k, hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  pick_gdt(gdt, [&](auto gd) {
-    constexpr int GDT = decltype(gd)::value;
-    if (coefs == nullptr)
-      hipLaunchKernelGGL((k_lamb_moments<GDT, false, false>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
-    else if (!write_back)
-      hipLaunchKernelGGL((k_lamb_moments<GDT, true, false>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
-    else
-      hipLaunchKernelGGL((k_lamb_moments<GDT, true, true>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+  pick2(keep, write_back, [&](auto kp, auto wbk) {
+    constexpr bool KEEP = decltype(kp)::value, WB = decltype(wbk)::value;
+    pick_gdt(gdt, [&](auto gd) {
+      constexpr int GDT = decltype(gd)::value;
+      if (coefs == nullptr)
+        hipLaunchKernelGGL((k_lamb_moments<GDT, false, false, KEEP>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+      else
+        hipLaunchKernelGGL((k_lamb_moments<GDT, true, WB, KEEP>), dim3(n), dim3(kBlock), 0, stream, table, n, coefs, sums, k);
+    });
   });
   return hipGetLastError();
 }

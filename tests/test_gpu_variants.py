@@ -257,6 +257,42 @@ def test_lamb_is_reproducible_and_the_update_has_length_lr_times_parameter_norm(
             assert d == pytest.approx(w.hyper.lr * np.linalg.norm(old.astype(np.float64)), rel=2e-3), t
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_lamb_step_in_runs_of_tensors_equals_one_run_bit_for_bit(dtype):
+    """lamb_step sweeps a large model run by run (both sweeps of a run of tensors before the next run, the moments stored
+    with cacheable stores in between).  Whatever the runs, trust ratios, p, m, v are the bits of a single run over
+    everything, over two steps; and they match the oracle."""
+    w = small_bert("large")
+    lay, hp = w.layout, w.hyper
+    numels = [int(n) for n in lay.tensor_numel]
+    if dtype == "f32":
+        g = w.grads()
+    elif dtype == "f16":
+        g = W.student_t_fp16_tensors(numels, 9, 1e-3, threads=1)
+    else:
+        g = oracle.Bf16(W.normal_bf16_tensors(numels, 9, 1e-2, threads=1))
+    p, m, v = state_of(w)
+    outs = []
+    for limit in (2 ** 62, 1, 20_000, 100_000):
+        dev = Device(lay, g, p, m, v, lamb_group_elems=limit)
+        n_runs = len(dev.plan.lamb_runs())
+        assert (n_runs == 1) == (limit == 2 ** 62) and (limit != 1 or n_runs == lay.n_tensors)
+        for step in (3, 4):
+            dev.plan.lamb_step(hyper(hp), step, dev.trust)
+        dev.sync()
+        outs.append((dev.trust.cpu().numpy().copy(), to_host(dev.p), to_host(dev.m), to_host(dev.v)))
+        assert bits_equal(to_host(dev.g), g)
+        dev.close()
+    for o in outs[1:]:
+        assert np.array_equal(o[0], outs[0][0])
+        assert all(bits_equal(o[i], outs[0][i]) for i in (1, 2, 3))
+    op, om, ov = f64(p), f64(m), f64(v)
+    for step in (3, 4):
+        otrust = oracle.lamb_step(lay, g, op, om, ov, step=step, **hp_kwargs(hp))
+    check_trust(outs[1][0][:lay.n_tensors], otrust)
+    check_state("p", outs[1][1], op), check_state("m", outs[1][2], om), check_state("v", outs[1][3], ov, strict_rel=True)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_lamb_random_layouts(seed):
     rng = np.random.default_rng(2000 + seed)

@@ -31,7 +31,7 @@ def test_binding_constants_equal_the_headers():
         errs = {int(v): k for k, v in defines.items() if "_ERR_" in k}
         assert errs == table, (header, errs, table)
     # struct layouts the C side and ctypes must agree on (C99 layout rules: natural alignment)
-    assert C.sizeof(binding._Segment) == 24 and C.sizeof(binding._Tuning) == 48 and C.sizeof(lbs._Run) == 72
+    assert C.sizeof(binding._Segment) == 24 and C.sizeof(binding._Tuning) == 56 and C.sizeof(lbs._Run) == 72
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -367,3 +367,25 @@ def test_work_list_of_the_fused_step(tuning):
             assert buckets_normed == set(range(nb))
         else:
             assert len(buckets_normed) < nb
+
+
+def test_runs_of_tensors_for_the_lamb_sweeps():
+    """Runs are consecutive, cover every tensor once, hold at most the limit unless a single tensor exceeds it,
+    and are as long as the limit allows (the next tensor would not have fitted)."""
+    numels = [10, 0, 5000, 300, 300, 9000, 1, 1, 1, 4000, 999]
+    lay = W.layout_flat_split(numels, 2000)
+    assert host_plan(lay).lamb_runs() == [(0, len(numels))]                    # default limit: far above this model
+    assert host_plan(lay, lamb_group_elems=2 ** 63).lamb_runs() == [(0, len(numels))]
+    for limit in (1, 600, 5000, 5310, 9000, 20000):
+        runs = host_plan(lay, lamb_group_elems=limit).lamb_runs()
+        assert runs[0][0] == 0 and runs[-1][1] == len(numels)
+        assert all(a[1] == b[0] for a, b in zip(runs, runs[1:])) and all(a < b for a, b in runs)
+        for a, b in runs:
+            tot = sum(numels[a:b])
+            assert tot <= limit or b - a == 1
+            if b < len(numels):
+                assert tot + numels[b] > limit
+    assert host_plan(lay, lamb_group_elems=1).lamb_runs() == [(t, t + 1) for t in range(len(numels))]
+    big = host_plan(W.config_bert_large().layout)
+    runs = big.lamb_runs()
+    assert len(runs) == 11 and sum(b - a for a, b in runs) == 391
