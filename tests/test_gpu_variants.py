@@ -370,6 +370,46 @@ def test_clip_lamb_in_a_hip_graph_replays_like_eager_calls():
     graph.close()
 
 
+def test_lamb_step_in_runs_in_a_hip_graph_replays_like_eager_calls():
+    """lamb_step in runs of tensors is three launches per run and nothing else: captured once, replayed with new
+    gradients and eager work in between, every replay gives the bits of an eager call on a twin."""
+    w = small_bert("multistep")
+    lay = w.layout
+    p, m, v = state_of(w)
+    eager = Device(lay, w.grads(0), p, m, v, lamb_group_elems=30_000)
+    graph = Device(lay, w.grads(0), p, m, v, lamb_group_elems=30_000)
+    assert len(graph.plan.lamb_runs()) >= 5
+    hp = hyper(w.hyper)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        graph.plan.lamb_step(hp, 7, graph.trust, stream=s)   # warm-up
+        eager.plan.lamb_step(hp, 7, eager.trust, stream=s)
+        s.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cg, stream=s):
+            graph.plan.lamb_step(hp, 7, graph.trust, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for k in range(1, 5):
+        gk = w.grads(k)
+        eager.set_grads(gk)
+        graph.set_grads(gk)
+        torch.cuda.synchronize()
+        cg.replay()
+        eager.plan.lamb_step(hp, 7, eager.trust)
+        torch.cuda.synchronize()
+        assert np.array_equal(graph.trust.cpu().numpy(), eager.trust.cpu().numpy())
+        for a, b in ((graph.p, eager.p), (graph.m, eager.m), (graph.v, eager.v)):
+            assert bits_equal(to_host(a), to_host(b)), k
+    op, om, ov = f64(p), f64(m), f64(v)
+    for k in [0, 1, 2, 3, 4]:
+        oracle.lamb_step(lay, w.grads(k), op, om, ov, step=7, **hp_kwargs(w.hyper))
+    check_state("p", to_host(eager.p), op)
+    check_state("v", to_host(eager.v), ov, strict_rel=True)
+    eager.close()
+    graph.close()
+
+
 def test_clip_lamb_single_launch_equals_the_separate_launches_bit_for_bit():
     for kind in ("large", "fp16"):
         w = small_bert(kind)
