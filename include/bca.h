@@ -293,9 +293,11 @@ int bucket_clip_adam(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, con
  * exactly as bucket_clip_adam does (thresholds, norms, coefs, status as there) and feeds
  * LAMB the scaled gradient formed in registers; flags: BCA_WRITE_BACK_GRADS only.
  * trust (DEVICE [n_tensors], may be NULL) receives the ratios.  Two sweeps over p, m, v:
- * moments + per-tensor sums, then the parameter update; bucket_clip_lamb runs the squared
- * norms and the first sweep as one pipelined launch, as bucket_clip_adam does with Adam
- * (separate launches under BCA_TUNE_MULTI_LAUNCH; same results bit for bit). */
+ * moments + per-tensor sums, then the parameter update; lamb_step carries them out run by
+ * run of tensors (bca_tuning.lamb_group_elems; results do not depend on the runs);
+ * bucket_clip_lamb runs the squared norms and the first sweep as one pipelined launch, as
+ * bucket_clip_adam does with Adam (separate launches under BCA_TUNE_MULTI_LAUNCH; same
+ * results bit for bit). */
 int lamb_step(bca_plan* plan, const bca_adam* hp /*HOST*/, uint64_t step, float* trust /*DEVICE or NULL*/,
               void* stream);
 int bucket_clip_lamb(bca_plan* plan, const float* thresholds /*DEVICE [B]*/, const bca_adam* hp /*HOST*/,
