@@ -67,6 +67,9 @@ def parse():
     ap.add_argument("--grid-norm", type=int, default=0)
     ap.add_argument("--grid-apply", type=int, default=0)
     ap.add_argument("--tune-flags", type=int, default=0)
+    ap.add_argument("--lamb-group-mi", type=int, default=0, help="lamb_step: run length in Mi elements (0: library default)")
+    ap.add_argument("--graph", action="store_true",
+                    help="--op other than clip_adam: capture one step in a HIP graph and time its replays instead of eager calls")
     ap.add_argument("--oracle-steps", type=int, default=8)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many 1 GiB plain copies (k_copy) so that counter runs have a known reference")
@@ -105,11 +108,11 @@ def other_ops(a, w, plan, g, p, m, v, dev):
         thr_rows = base * (0.9 ** torch.arange(rows, dtype=torch.float64, device=dev)).to(torch.float32)[:, None].repeat(
             1, lay.n_buckets).contiguous()
 
+    thr_now = torch.zeros(lay.n_buckets, dtype=torch.float32, device=dev)    # the row in use (a fixed address for --graph)
+
     def per_bucket():
-        t = thr_rows[n_calls[0]]
-        n_calls[0] += 1
         for b in range(lay.n_buckets):
-            plan.bucket_clip(b, b + 1, t, norms, coefs, status, stream)
+            plan.bucket_clip(b, b + 1, thr_now, norms, coefs, status, stream)
         plan.adam_step(hp, step[0], stream)
     # algorithmic bytes per element: every sweep's reads and writes, nothing assumed cached
     ops = {
@@ -133,7 +136,29 @@ def other_ops(a, w, plan, g, p, m, v, dev):
     }
     fn, per_elt, what = ops[a.op]
 
+    if a.graph:          # one step captured once; every timed step is a replay (same host arguments, so the same step count)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        eager_fn = fn
+        with torch.cuda.stream(side):
+            stream = side
+            if thr_rows is not None:
+                thr_now.copy_(thr_rows[0])
+            eager_fn()                                   # warm-up outside the capture
+            side.synchronize()
+            cg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cg, stream=side):
+                stream = torch.cuda.current_stream()
+                eager_fn()
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+        fn = cg.replay
+        what += "; HIP graph replays"
+
     def one():
+        if thr_rows is not None:
+            thr_now.copy_(thr_rows[n_calls[0]])
+            n_calls[0] += 1
         fn()
         step[0] += 1
     for _ in range(a.warmup):
@@ -348,7 +373,8 @@ def main():
                               chunk_apply=a.chunk_apply, grid_norm=a.grid_norm, grid_apply=a.grid_apply,
                               unroll_apply=a.unroll_apply, tune_flags=a.tune_flags, group_bytes=a.group_mib << 20,
                               adam_lds_reserve=1 if a.adam_lds_kib < 0 else a.adam_lds_kib << 10,
-                              norm_item_chunks=a.norm_item_chunks, norm_lead=a.norm_lead)
+                              norm_item_chunks=a.norm_item_chunks, norm_lead=a.norm_lead,
+                              lamb_group_elems=a.lamb_group_mi << 20)
     plan.bind(g, p, m, v)
     mask = None
     if a.decay_mask:
