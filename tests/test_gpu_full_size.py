@@ -155,6 +155,38 @@ def test_bert_large_lamb_bf16_masked_full_size():
     dev.close()
 
 
+def test_bert_large_lamb_step_in_its_default_runs_full_size():
+    # lamb_step as bench.py times it: BERT-Large in the library's default runs of tensors (11 of them), against the
+    # same step as a single run bit for bit, and against the oracle
+    w = W.config_bert_large()
+    lay = w.layout
+    g, p, m, v = w.grads(), w.params(), w.exp_avg(), w.exp_avg_sq()
+    runs = Device(lay, g, p, m, v)
+    assert len(runs.plan.lamb_runs()) == 11
+    runs.plan.lamb_step(hyper(w.hyper), w.first_step, runs.trust)
+    runs.sync()
+    got = (runs.trust.cpu().numpy().copy(), to_host(runs.p), to_host(runs.m), to_host(runs.v))
+    assert bits_equal(to_host(runs.g), g)
+    runs.close()
+    del runs
+    one = Device(lay, g, p, m, v, lamb_group_elems=2 ** 62)
+    assert len(one.plan.lamb_runs()) == 1
+    one.plan.lamb_step(hyper(w.hyper), w.first_step, one.trust)
+    one.sync()
+    assert np.array_equal(got[0], one.trust.cpu().numpy())
+    for name, a, b in (("p", got[1], one.p), ("m", got[2], one.m), ("v", got[3], one.v)):
+        assert bits_equal(a, to_host(b)), name
+    one.close()
+    del one
+    t0 = time.time()
+    op, om, ov = f64(p), f64(m), f64(v)
+    otrust = oracle.lamb_step(lay, g, op, om, ov, step=w.first_step, **hp_kwargs(w.hyper))
+    print(f"[lamb runs] oracle step {time.time() - t0:.1f}s", flush=True)
+    trel = np.abs(got[0][:lay.n_tensors].astype(np.float64) - otrust) / otrust
+    assert trel.max() <= 1e-5, trel.max()
+    check_state("p", got[1], op), check_state("m", got[2], om), check_state("v", got[3], ov, strict_rel=True)
+
+
 def test_bert_large_whole_tensor_buckets_full_size():
     # DDP-style packing: whole tensors per bucket (the 31 M-element word embedding is one bucket of its own)
     lay = W.layout_whole_tensors(W.bert_large_numels(), 50 * W.MIB // 4)
