@@ -50,10 +50,29 @@ int main(void) {
   CHECK(bca_plan_bucket_chunks(plan, BCA_TABLE_LAMB, 1, &first, &count) == BCA_OK && first == 4 && count == 1);
   CHECK(bca_plan_chunk_info(plan, BCA_TABLE_APPLY, 5, NULL, NULL, NULL, NULL) == BCA_ERR_RANGE);
   CHECK(bca_plan_set_decay_mask(plan, mask) == BCA_OK);
+  {
+    /* the fused step's work list and lamb_step's runs of tensors, read back */
+    uint32_t kind = 9, n_items = bca_plan_num_work_items(plan), i, n_norm = 0, n_adam = 0, t0 = 9, t1 = 9;
+    CHECK(n_items >= 5 + 2 && bca_plan_norm_item_chunks(plan) >= 1);
+    for (i = 0; i < n_items; ++i) {
+      CHECK(bca_plan_work_item(plan, i, &kind, &first, &count) == BCA_OK && kind <= 2);
+      if (kind == 0) n_norm += count;
+      if (kind == 1) n_adam += count;
+    }
+    CHECK(n_norm == bca_plan_num_chunks(plan, BCA_TABLE_NORM) && n_adam == 5);
+    CHECK(bca_plan_work_item(plan, n_items, &kind, NULL, NULL) == BCA_ERR_RANGE);
+    CHECK(bca_plan_num_lamb_runs(plan) == 1 && bca_plan_lamb_run(plan, 0, &t0, &t1) == BCA_OK && t0 == 0 && t1 == 2);
+    CHECK(bca_plan_lamb_run(plan, 1, NULL, NULL) == BCA_ERR_RANGE);
+  }
   CHECK(adam_step(plan, &hp, 1, NULL) == BCA_ERR_UNBOUND);       /* host-only plan: no kernels */
   CHECK(lamb_step(plan, &hp, 0, NULL, NULL) == BCA_ERR_HPARAM);  /* step counts from 1 */
   CHECK(bucket_clip_adam(plan, &dummy, &hp, 1, 64u, NULL, NULL, NULL, NULL) == BCA_ERR_RANGE);
   bca_plan_destroy(plan);
+  tune.lamb_group_elems = 600; /* tensor 0 (3000 elements) is a run of its own, tensor 1 (500) the next */
+  CHECK(bca_plan_create(&plan, -1, 2, numel, 2, seg_off, segs, BCA_GRAD_F32, &tune) == BCA_OK);
+  CHECK(bca_plan_num_lamb_runs(plan) == 2 && bca_plan_lamb_run(plan, 1, &first, &count) == BCA_OK && first == 1 && count == 2);
+  bca_plan_destroy(plan);
+  tune.lamb_group_elems = 0;
   segs[2].len = 1999; /* one element of tensor 0 not covered */
   CHECK(bca_plan_create(&plan, -1, 2, numel, 2, seg_off, segs, BCA_GRAD_F32, NULL) == BCA_ERR_LAYOUT && plan == NULL);
   CHECK(strstr(bca_last_error(), "tensor 0") != NULL);
