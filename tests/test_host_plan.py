@@ -389,3 +389,30 @@ def test_runs_of_tensors_for_the_lamb_sweeps():
     big = host_plan(W.config_bert_large().layout)
     runs = big.lamb_runs()
     assert len(runs) == 11 and sum(b - a for a, b in runs) == 391
+
+
+def test_the_packages_bucket_layouts_are_valid_and_match_the_test_generators():
+    """paper_2402_02447_amd.buckets (what a user builds plans from) against the layouts the tests are written with
+    (workloads.py, written separately): the same arrays for random tensor lists and capacities, empty tensors and
+    empty models included; and the library accepts them (every element in exactly one segment)."""
+    rng = np.random.default_rng(3)
+    cases = [([], 10), ([0, 0], 10), ([7], 7), ([7], 3), ([5, 0, 0, 7], 5), ([5, 0], 100), ([0, 5], 2)]
+    for _ in range(60):
+        n = int(rng.integers(1, 12))
+        numels = [int(x) for x in rng.choice([0, 1, 2, 31, 100, 1024, 5000], n)]
+        cases.append((numels, int(rng.choice([1, 7, 100, 1024, 3000, 100000]))))
+    fields = ("tensor_numel", "bucket_seg_off", "seg_tensor", "seg_begin", "seg_len")
+    for numels, cap in cases:
+        for rev in (True, False):
+            for mine, ref in ((B.flat_split(numels, cap, rev), W.layout_flat_split(numels, cap, rev)),
+                              (B.whole_tensors(numels, cap, rev), W.layout_whole_tensors(numels, cap, rev))):
+                for f in fields:
+                    a, b = getattr(mine, f), getattr(ref, f)
+                    assert a.dtype == b.dtype and np.array_equal(a, b), (numels, cap, rev, f, a, b)
+                assert mine.n_buckets == ref.n_buckets and mine.n_elements == ref.n_elements
+                with host_plan(mine) as p:
+                    assert p.n_buckets == mine.n_buckets
+    big = B.flat_split(W.bert_large_numels(), 50 * W.MIB // 4)
+    assert big.n_buckets == 26 and int(big.bucket_seg_off[-1]) == 416
+    with pytest.raises(ValueError):
+        B.flat_split([1, 2], 0)
