@@ -465,7 +465,16 @@ def main():
     c1.record(stream)
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    del src, dst
+    # and a yardstick that is not this library's: torch's own element-wise kernel over the same gigabyte (read + written)
+    a32, b32 = src.view(torch.float32), dst.view(torch.float32)
+    torch.add(a32, 1.0, out=b32)
+    c0.record(stream)
+    for _ in range(5):
+        torch.add(a32, 1.0, out=b32)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    torch_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst, a32, b32
 
     gbytes = 2 if (f16 or bf16) else 4
     single = not (a.tune_flags & B.BCA_TUNE_MULTI_LAUNCH)
@@ -496,6 +505,7 @@ def main():
         "step_GBps_hbm_bytes": round(hbm_per_elt * N / (ms_per_step * 1e-3) / 1e9, 1),
         "step_frac_of_peak_hbm_bytes": round(hbm_per_elt * N / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "plain_copy_frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
+        "torch_elementwise_add_GBps": round(torch_gbps, 1),
         "items_that_waited_per_step": round(n_waited / (a.warmup + a.steps), 1),
         "polls_per_waiting_item": round(n_polls / max(n_waited, 1), 1),
         "elements": N, "buckets": lay.n_buckets, "chunks_norm": plan.n_chunks(B.BCA_TABLE_NORM),
